@@ -1,0 +1,174 @@
+/*
+ * milo.h — C ABI of the MI355X-native W3A16 + low-rank expert linear
+ * (inference hot path of MiLo, arXiv 2504.02658).
+ *
+ * What the library computes (paper Section 3.1.2, compensated weight
+ * W~ = Q^-1(W_q) + U V, and Section 3.2, Eq. wq / wdq):
+ *
+ *      Y = X * dequant(Q3)^T + (X * V^T) * U^T
+ *
+ *   X  [M x K]  fp16 activations, row-major
+ *   W  [N x K]  weight (out x in); Q3 holds its 3-bit codes q in 0..7,
+ *               one fp16 scale s and one fp16 zero-point z per group of 64
+ *               consecutive k of a row:  W_dq[n,k] = s[n,g] * (q[n,k] - z[n,g])
+ *   U  [N x r], V [r x K]  fp16 low-rank compensator of rank r (r may be 0)
+ *   Y  [M x N]  fp16, row-major; accumulation is fp32, one rounding at the end.
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless the
+ *     argument comment says "host".  The library never frees or keeps a pointer
+ *     and allocates nothing: scratch memory comes in through `workspace`.
+ *   - fp16 values are IEEE binary16 bit patterns (`milo_half` = uint16_t).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All calls only enqueue work on that stream and return without waiting.
+ *   - Every call returns a milo_status (0 = OK).  Argument errors are detected
+ *     on the host before anything is launched; the library never aborts.
+ *   - Shapes: K % 64 == 0, N % 16 == 0, M >= 1, group size must be 64
+ *     (the only group size of the paper's kernel, appendix "Correctness Test").
+ *   - Pointers must be 16-byte aligned; inputs and outputs must not alias.
+ *
+ * Packed format ("Q3 blob", exactly 3 bits per weight, Section 3.3
+ * "Zero bit waste 3-bit weights packing"; the concrete layout is this
+ * library's own):
+ *   - unit(n, g) = the 64 codes of row n, group g; units are ordered
+ *         u = ((n / 16) * (K / 64) + g) * 16 + n % 16
+ *   - a unit is six little-endian 32-bit words d0..d5; plane A (first N*K/4
+ *     bytes of the blob) stores d0..d3 of unit u at byte 16u, plane B (the next
+ *     N*K/8 bytes) stores d4, d5 at byte 8u
+ *   - the unit's codes form pairs P = (q[2P], q[2P+1]) = (lo, hi); for P < 30,
+ *     word j = P / 5, slot c = P % 5: lo in bits 3c..3c+2, hi in bits
+ *     16+3c..16+3c+2; bits 15 and 31 of words 0,1,2 carry bits 0,1,2 of pair 30
+ *     (lo in bit 15, hi in bit 31), those of words 3,4,5 carry pair 31
+ *   - scales and zeros are fp16 arrays of N*K/64 entries in the same unit order.
+ */
+#ifndef MILO_H
+#define MILO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t milo_half;
+
+enum milo_status {
+    MILO_OK = 0,
+    MILO_ERR_NULL = 1,       /* a required pointer is NULL                                  */
+    MILO_ERR_SHAPE = 2,      /* K % 64, N % 16, M < 1, a size overflows, bad top-k / E      */
+    MILO_ERR_GROUP = 3,      /* group_size != 64                                            */
+    MILO_ERR_RANK = 4,       /* r < 0, r > min(N, K), or r > 0 with U or V NULL             */
+    MILO_ERR_WORKSPACE = 5,  /* workspace NULL or smaller than the *_workspace() size       */
+    MILO_ERR_ROUTING = 6,    /* an expert id outside 0..E-1 was met (reported after the run)*/
+    MILO_ERR_ALIGN = 7,      /* a pointer is not 16-byte aligned                            */
+    MILO_ERR_HIP = 100       /* a HIP runtime call failed (launch error, no device, ...)    */
+};
+
+/* Static text for a status code; never NULL. */
+const char* milo_status_string(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int milo_version(void);
+
+/* Bytes of the Q3 blob of an [N x K] weight: exactly N*K*3/8 (0 if the shape is invalid). */
+size_t milo_w3_packed_bytes(int64_t N, int64_t K);
+
+/*
+ * Quantize and pack (Section 3.2 Eq. wq with U = V = 0, round-to-nearest; Section 3.3).
+ * Per group: s = fp16((max - min) / 7), z = round(-min / s), q = clamp(round(w / s + z), 0, 7),
+ * all in binary32 with round-half-even and no fused multiply-add; a group whose fp16 scale is
+ * zero or not finite stores s = 1, z = fp16(-min), q = 0.
+ *   W       [N x K] fp32 row-major (device, read only)
+ *   q3      out, milo_w3_packed_bytes(N, K) bytes
+ *   scales  out, N*K/64 fp16 in unit order;  zeros likewise
+ * Errors: NULL, SHAPE, GROUP, ALIGN, HIP.
+ */
+int milo_pack_w3(const float* W, int64_t N, int64_t K, int group_size,
+                 void* q3, milo_half* scales, milo_half* zeros, void* stream);
+
+/* Test aid: codes[n*K + k] = q[n,k] as bytes, from a Q3 blob. */
+int milo_unpack_w3(const void* q3, int64_t N, int64_t K, uint8_t* codes, void* stream);
+
+/*
+ * Dequantize a packed weight to dense fp16 (Eq. wdq), W_dq [N x K] row-major, with the same
+ * in-register conversion the GEMM kernels use.  Used to build the residual W - W_dq that the
+ * compensator is fitted to, and by the tests.
+ */
+int milo_dequant_w3(const void* q3, const milo_half* scales, const milo_half* zeros,
+                    int64_t N, int64_t K, milo_half* W_dq, void* stream);
+
+/*
+ * One compensated W3A16 linear:  Y = X dequant(Q3)^T + (X V^T) U^T.
+ *   X [M x K] fp16;  q3/scales/zeros as written by milo_pack_w3 (zeros may be any finite fp16,
+ *   integer or not);  U [N x r], V [r x K] fp16 row-major, ignored when r == 0;  Y [M x N] fp16.
+ *   workspace: at least milo_w3lr_gemm_workspace(M, N, K, r) bytes of device memory; its
+ *   contents are scratch.  Calls that share a workspace must be ordered on one stream.
+ * M <= 16 takes the weight-streaming decode kernel, larger M the tiled MFMA kernel.
+ * Errors: NULL, SHAPE, RANK, WORKSPACE, ALIGN, HIP.
+ */
+size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int r);
+int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t K,
+                   const void* q3, const milo_half* scales, const milo_half* zeros,
+                   const milo_half* U, const milo_half* V, int r,
+                   milo_half* Y, void* workspace, size_t workspace_bytes, void* stream);
+
+/* One packed weight with its compensator (all device pointers). */
+typedef struct milo_w3lr_weight {
+    const void* q3;
+    const milo_half* scales;
+    const milo_half* zeros;
+    const milo_half* U;      /* [N x r] or NULL when r == 0 */
+    const milo_half* V;      /* [r x K] or NULL when r == 0 */
+    int32_t r;
+    int32_t reserved;        /* must be 0 */
+} milo_w3lr_weight;
+
+/* A SwiGLU expert: w1, w3 are [F x H] (gate, up), w2 is [H x F] (down). */
+typedef struct milo_w3lr_expert {
+    milo_w3lr_weight w1, w3, w2;
+} milo_w3lr_expert;
+
+/*
+ * Host-side validation of an expert table before it is copied to the device.
+ *   experts  HOST array of E entries;  r_max_out (host, may be NULL) receives the largest rank.
+ * Errors: NULL, SHAPE, RANK, ALIGN.
+ */
+int milo_moe_w3lr_check_experts(const milo_w3lr_expert* experts, int E, int64_t H, int64_t F,
+                                int* r_max_out);
+
+/*
+ * Top-k routed MoE feed-forward layer over compensated W3A16 experts:
+ *     y_t = sum_j gates[t,j] * lin_w2^e( SiLU(lin_w1^e(x_t)) * lin_w3^e(x_t) ),   e = ids[t,j]
+ * with SiLU(a) = a / (1 + exp(-a)) and every lin the compensated linear above.  Tokens are
+ * grouped per expert inside the call; the router (gate GEMM, softmax, top-k) is the caller's.
+ * Always-on shared experts are passed as extra routing columns with weight 1.
+ *   X            [T x H] fp16
+ *   experts      DEVICE array of E entries (a byte copy of a host table that passed
+ *                milo_moe_w3lr_check_experts);  r_max = largest rank in the table
+ *   topk_ids     [T x topk] int32, the ids of one token must be distinct
+ *   topk_weights [T x topk] fp32
+ *   Y            [T x H] fp16
+ *   workspace    at least milo_moe_w3lr_workspace(T, H, F, E, topk, r_max) bytes
+ * An id outside 0..E-1 contributes nothing and raises a flag that
+ * milo_moe_w3lr_routing_status() reports; an expert with no tokens is legal.
+ * The combine over the top-k slots is done in a fixed order in fp32 with one rounding, so two
+ * runs give bit-identical results.
+ * Errors: NULL, SHAPE, RANK, WORKSPACE, ALIGN, HIP.
+ */
+size_t milo_moe_w3lr_workspace(int64_t T, int64_t H, int64_t F, int E, int topk, int r_max);
+int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, int64_t F,
+                          const milo_w3lr_expert* experts, int E, int r_max,
+                          const int32_t* topk_ids, const float* topk_weights, int topk,
+                          milo_half* Y, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Waits for `stream` and returns MILO_ERR_ROUTING if the last milo_moe_w3lr_forward that used
+ * this workspace met an expert id out of range, MILO_OK otherwise.
+ */
+int milo_moe_w3lr_routing_status(const void* workspace, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MILO_H */

@@ -1,0 +1,228 @@
+"""ctypes binding over the C ABI of libmilo.so (see include/milo.h).
+
+Argument marshalling only: every step of the path runs inside the HIP library.  PyTorch is
+used for device memory and for the current stream, nothing else.  Importing this module
+without a built library raises: there is no fallback path.
+"""
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libmilo.so")
+
+STATUS_NAMES = {0: "MILO_OK", 1: "MILO_ERR_NULL", 2: "MILO_ERR_SHAPE", 3: "MILO_ERR_GROUP",
+                4: "MILO_ERR_RANK", 5: "MILO_ERR_WORKSPACE", 6: "MILO_ERR_ROUTING",
+                7: "MILO_ERR_ALIGN", 100: "MILO_ERR_HIP"}
+
+# every symbol include/milo.h declares
+EXPORTS = ("milo_status_string", "milo_version", "milo_w3_packed_bytes", "milo_pack_w3",
+           "milo_unpack_w3", "milo_dequant_w3", "milo_w3lr_gemm_workspace", "milo_w3lr_gemm",
+           "milo_moe_w3lr_check_experts", "milo_moe_w3lr_workspace", "milo_moe_w3lr_forward",
+           "milo_moe_w3lr_routing_status")
+
+
+class MiloError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        text = lib().milo_status_string(status).decode()
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)} ({text})")
+
+
+class Weight(ctypes.Structure):
+    _fields_ = [("q3", ctypes.c_void_p), ("scales", ctypes.c_void_p), ("zeros", ctypes.c_void_p),
+                ("U", ctypes.c_void_p), ("V", ctypes.c_void_p), ("r", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
+
+
+class Expert(ctypes.Structure):
+    _fields_ = [("w1", Weight), ("w3", Weight), ("w2", Weight)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run __graft_entry__.build() "
+                              "(or paper_2504_02658_amd/csrc/build.sh)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, ci, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+        L.milo_status_string.restype = ctypes.c_char_p
+        L.milo_status_string.argtypes = [ci]
+        L.milo_version.restype = ci
+        L.milo_w3_packed_bytes.restype = sz
+        L.milo_w3_packed_bytes.argtypes = [i64, i64]
+        L.milo_pack_w3.restype = ci
+        L.milo_pack_w3.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
+        L.milo_unpack_w3.restype = ci
+        L.milo_unpack_w3.argtypes = [vp, i64, i64, vp, vp]
+        L.milo_dequant_w3.restype = ci
+        L.milo_dequant_w3.argtypes = [vp, vp, vp, i64, i64, vp, vp]
+        L.milo_w3lr_gemm_workspace.restype = sz
+        L.milo_w3lr_gemm_workspace.argtypes = [i64, i64, i64, ci]
+        L.milo_w3lr_gemm.restype = ci
+        L.milo_w3lr_gemm.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, ci, vp, vp, sz, vp]
+        L.milo_moe_w3lr_check_experts.restype = ci
+        L.milo_moe_w3lr_check_experts.argtypes = [ctypes.POINTER(Expert), ci, i64, i64,
+                                                  ctypes.POINTER(ci)]
+        L.milo_moe_w3lr_workspace.restype = sz
+        L.milo_moe_w3lr_workspace.argtypes = [i64, i64, i64, ci, ci, ci]
+        L.milo_moe_w3lr_forward.restype = ci
+        L.milo_moe_w3lr_forward.argtypes = [vp, i64, i64, i64, vp, ci, ci, vp, vp, ci, vp, vp, sz, vp]
+        L.milo_moe_w3lr_routing_status.restype = ci
+        L.milo_moe_w3lr_routing_status.argtypes = [vp, vp]
+        _lib = L
+    return _lib
+
+
+def _check(status, where):
+    if status != 0:
+        raise MiloError(status, where)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _dev(t, dtype, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous CUDA tensor of {dtype}")
+    return t
+
+
+class PackedWeight:
+    """Device buffers of one packed [N x K] weight and its optional compensator."""
+
+    def __init__(self, N, K, q3, scales, zeros, U=None, V=None):
+        self.N, self.K = int(N), int(K)
+        self.q3, self.scales, self.zeros = q3, scales, zeros
+        self.U, self.V = U, V
+
+    @property
+    def r(self):
+        return 0 if self.U is None else int(self.U.shape[1])
+
+    def with_compensator(self, U, V):
+        U = _dev(U, torch.float16, "U")
+        V = _dev(V, torch.float16, "V")
+        assert U.shape[0] == self.N and V.shape[1] == self.K and U.shape[1] == V.shape[0]
+        if U.shape[1] == 0:
+            U = V = None
+        return PackedWeight(self.N, self.K, self.q3, self.scales, self.zeros, U, V)
+
+    def weight_bytes(self):
+        n = self.q3.numel() + 2 * self.scales.numel() + 2 * self.zeros.numel()
+        if self.U is not None:
+            n += 2 * self.U.numel() + 2 * self.V.numel()
+        return n
+
+    def c_struct(self):
+        return Weight(self.q3.data_ptr(), self.scales.data_ptr(), self.zeros.data_ptr(),
+                      0 if self.U is None else self.U.data_ptr(),
+                      0 if self.V is None else self.V.data_ptr(), self.r, 0)
+
+
+def packed_bytes(N, K):
+    return int(lib().milo_w3_packed_bytes(N, K))
+
+
+def pack_w3(W, group_size=64):
+    """milo_pack_w3: fp32 CUDA weight [N, K] -> PackedWeight (no compensator)."""
+    W = _dev(W, torch.float32, "W")
+    N, K = W.shape
+    nbytes = packed_bytes(N, K)
+    q3 = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=W.device)
+    groups = max(N * K // 64, 8)
+    scales = torch.empty(groups, dtype=torch.float16, device=W.device)
+    zeros = torch.empty(groups, dtype=torch.float16, device=W.device)
+    _check(lib().milo_pack_w3(_ptr(W), N, K, group_size, _ptr(q3), _ptr(scales), _ptr(zeros),
+                              _stream()), "milo_pack_w3")
+    return PackedWeight(N, K, q3[:nbytes], scales[: N * K // 64], zeros[: N * K // 64])
+
+
+def unpack_w3(pw):
+    codes = torch.empty((pw.N, pw.K), dtype=torch.uint8, device=pw.q3.device)
+    _check(lib().milo_unpack_w3(_ptr(pw.q3), pw.N, pw.K, _ptr(codes), _stream()), "milo_unpack_w3")
+    return codes
+
+
+def dequant_w3(pw):
+    out = torch.empty((pw.N, pw.K), dtype=torch.float16, device=pw.q3.device)
+    _check(lib().milo_dequant_w3(_ptr(pw.q3), _ptr(pw.scales), _ptr(pw.zeros), pw.N, pw.K,
+                                 _ptr(out), _stream()), "milo_dequant_w3")
+    return out
+
+
+def gemm_workspace_bytes(M, N, K, r):
+    return int(lib().milo_w3lr_gemm_workspace(M, N, K, r))
+
+
+def w3lr_gemm(X, pw, out=None, workspace=None):
+    """milo_w3lr_gemm: Y = X dequant(Q3)^T + (X V^T) U^T."""
+    X = _dev(X, torch.float16, "X")
+    M, K = X.shape
+    if K != pw.K:
+        raise ValueError("X and weight disagree on K")
+    if out is None:
+        out = torch.empty((M, pw.N), dtype=torch.float16, device=X.device)
+    need = gemm_workspace_bytes(M, pw.N, K, pw.r)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    _check(lib().milo_w3lr_gemm(_ptr(X), M, pw.N, K, _ptr(pw.q3), _ptr(pw.scales), _ptr(pw.zeros),
+                                _ptr(pw.U), _ptr(pw.V), pw.r, _ptr(out), _ptr(workspace),
+                                workspace.numel(), _stream()), "milo_w3lr_gemm")
+    return out
+
+
+class MoELayer:
+    """Expert table of one MoE layer: validates on the host, keeps the device copy of the table."""
+
+    def __init__(self, experts, H, F):
+        # experts: list of (w1, w3, w2) PackedWeight triples
+        self.H, self.F, self.E = int(H), int(F), len(experts)
+        self.experts = experts                      # keeps the device buffers alive
+        arr = (Expert * self.E)()
+        for e, (w1, w3, w2) in enumerate(experts):
+            arr[e] = Expert(w1.c_struct(), w3.c_struct(), w2.c_struct())
+        rmax = ctypes.c_int(0)
+        _check(lib().milo_moe_w3lr_check_experts(arr, self.E, self.H, self.F, ctypes.byref(rmax)),
+               "milo_moe_w3lr_check_experts")
+        self.r_max = int(rmax.value)
+        host = np.frombuffer(bytes(arr), dtype=np.uint8).copy()
+        self.table = torch.from_numpy(host).cuda()
+        self._ws = None
+
+    def workspace_bytes(self, T, topk):
+        return int(lib().milo_moe_w3lr_workspace(T, self.H, self.F, self.E, topk, self.r_max))
+
+    def forward(self, X, ids, gates, out=None, workspace=None):
+        X = _dev(X, torch.float16, "X")
+        ids = _dev(ids, torch.int32, "ids")
+        gates = _dev(gates, torch.float32, "gates")
+        T, H = X.shape
+        topk = ids.shape[1]
+        need = self.workspace_bytes(T, topk)
+        if workspace is None:
+            if self._ws is None or self._ws.numel() < need:
+                self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+            workspace = self._ws
+        if out is None:
+            out = torch.empty((T, H), dtype=torch.float16, device=X.device)
+        _check(lib().milo_moe_w3lr_forward(_ptr(X), T, H, self.F, _ptr(self.table), self.E,
+                                           self.r_max, _ptr(ids), _ptr(gates), topk, _ptr(out),
+                                           _ptr(workspace), workspace.numel(), _stream()),
+               "milo_moe_w3lr_forward")
+        self.last_workspace = workspace
+        return out
+
+    def routing_status(self):
+        return int(lib().milo_moe_w3lr_routing_status(_ptr(self.last_workspace), _stream()))

@@ -1,0 +1,92 @@
+// Status text, version and the single-linear entry point milo_w3lr_gemm.
+#include "milo_host.h"
+#include "milo_kernels.h"
+
+using namespace milo;
+
+extern "C" const char* milo_status_string(int status) {
+    switch (status) {
+        case MILO_OK: return "ok";
+        case MILO_ERR_NULL: return "a required pointer is NULL";
+        case MILO_ERR_SHAPE: return "invalid shape (need K % 64 == 0, N % 16 == 0, M >= 1, sizes in range)";
+        case MILO_ERR_GROUP: return "group size must be 64";
+        case MILO_ERR_RANK: return "invalid rank (need 0 <= r <= min(N, K), U and V given when r > 0)";
+        case MILO_ERR_WORKSPACE: return "workspace missing or too small";
+        case MILO_ERR_ROUTING: return "expert id out of range";
+        case MILO_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+        case MILO_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+extern "C" int milo_version(void) { return 100; }
+
+static int64_t rank_pad(int r) { return ((int64_t)r + 15) / 16 * 16; }
+
+static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
+    return M >= 1 && M <= (int64_t)0x3fffffff && weight_shape_ok(N, K);
+}
+
+extern "C" size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int r) {
+    if (!gemm_shape_ok(M, N, K) || r < 0) return 0;
+    // T = X V^T as fp16 [M x pad16(r)]; never zero so that callers can always allocate it
+    return align_up((size_t)M * (size_t)rank_pad(r) * 2 + 256, 256);
+}
+
+extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t K, const void* q3,
+                              const milo_half* scales, const milo_half* zeros, const milo_half* U,
+                              const milo_half* V, int r, milo_half* Y, void* workspace,
+                              size_t workspace_bytes, void* stream_) {
+    if (!X || !q3 || !scales || !zeros || !Y) return MILO_ERR_NULL;
+    if (!gemm_shape_ok(M, N, K)) return MILO_ERR_SHAPE;
+    if (r < 0 || r > N || r > K) return MILO_ERR_RANK;
+    if (r > 0 && (!U || !V)) return MILO_ERR_RANK;
+    if (!workspace || workspace_bytes < milo_w3lr_gemm_workspace(M, N, K, r))
+        return MILO_ERR_WORKSPACE;
+    if (!aligned16(X) || !aligned16(q3) || !aligned16(scales) || !aligned16(zeros) ||
+        !aligned16(Y) || !aligned16(workspace) || (r > 0 && (!aligned16(U) || !aligned16(V))))
+        return MILO_ERR_ALIGN;
+    hipStream_t stream = (hipStream_t)stream_;
+
+    WeightDev w;
+    w.q3 = q3;
+    w.scales = reinterpret_cast<const f16*>(scales);
+    w.zeros = reinterpret_cast<const f16*>(zeros);
+    w.U = reinterpret_cast<const f16*>(U);
+    w.V = reinterpret_cast<const f16*>(V);
+    w.r = r;
+    w.reserved = 0;
+    f16* T = reinterpret_cast<f16*>(workspace);
+    const int64_t ldt = rank_pad(r);
+
+    const bool decode = M <= 16;
+    const int mb = decode ? 1 : (M <= 32 ? 1 : (M <= 64 ? 2 : 4));
+    const int bm = 32 * mb;
+    const int64_t m_tiles = (M + bm - 1) / bm;
+    if (m_tiles > 65535) return MILO_ERR_SHAPE;
+
+    RowSpace rs;
+    rs.tiles = nullptr; rs.n_tiles = nullptr; rs.experts = nullptr;
+    rs.which[0] = rs.which[1] = 0;
+    rs.w[0] = rs.w[1] = w;
+    rs.M = M; rs.x_rows = nullptr; rs.x_row_div = 1;
+
+    if (r > 0) {
+        TArgs ta;
+        ta.rs = rs; ta.X = reinterpret_cast<const f16*>(X); ta.ldx = K; ta.K = K;
+        ta.T[0] = ta.T[1] = T; ta.ldt = ldt; ta.bm = bm;
+        const int st = launch_t_kernel(ta, 1, (int)m_tiles, stream);
+        if (st != MILO_OK) return st;
+    }
+    if (decode) {
+        DecodeArgs da;
+        da.X = reinterpret_cast<const f16*>(X); da.M = (int)M; da.N = N; da.K = K;
+        da.w = w; da.T = T; da.ldt = ldt; da.Y = reinterpret_cast<f16*>(Y);
+        return launch_decode(da, stream);
+    }
+    TiledArgs ga;
+    ga.rs = rs; ga.X = reinterpret_cast<const f16*>(X); ga.ldx = K; ga.N = N; ga.K = K;
+    ga.T[0] = ga.T[1] = T; ga.ldt = ldt;
+    ga.out = Y; ga.ldo = N; ga.out_rows = nullptr; ga.out_scale = nullptr;
+    return launch_tiled(ga, 1, mb, EPI_STORE, (int)m_tiles, stream);
+}

@@ -1,0 +1,30 @@
+// Host-side helpers shared by the entry points: argument checks and launch error handling.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/milo.h"
+
+namespace milo {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// K % 64 == 0, N % 16 == 0, both positive, and N*K small enough for 64-bit byte arithmetic
+// and 32-bit group counts per row.
+inline bool weight_shape_ok(int64_t N, int64_t K) {
+    if (N <= 0 || K <= 0) return false;
+    if ((K % 64) != 0 || (N % 16) != 0) return false;
+    if (K > (int64_t(1) << 30) || N > (int64_t(1) << 30)) return false;
+    if (N > (int64_t(1) << 56) / K) return false;
+    return true;
+}
+
+inline int launch_status() {
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? MILO_OK : MILO_ERR_HIP;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace milo

@@ -1,0 +1,85 @@
+// Argument blocks and host-side launchers of the GEMM kernels (internal to the library).
+#pragma once
+
+#include "milo_device.h"
+
+namespace milo {
+
+// Same bytes as the public milo_w3lr_weight.
+struct WeightDev {
+    const void* q3;
+    const f16* scales;
+    const f16* zeros;
+    const f16* U;
+    const f16* V;
+    int32_t r;
+    int32_t reserved;
+};
+static_assert(sizeof(WeightDev) == sizeof(milo_w3lr_weight), "weight descriptor layout");
+static_assert(sizeof(milo_w3lr_expert) == 3 * sizeof(WeightDev), "expert descriptor layout");
+
+// One M-tile of a grouped problem: rows [row0, row0 + rows) of the expert-sorted row space.
+struct TileDesc {
+    int32_t expert;
+    int32_t row0;
+    int32_t rows;
+    int32_t pad;
+};
+
+// Row-space conventions shared by the tiled kernel and the T kernel.
+//   Ungrouped (tiles == nullptr): tile y covers rows [y*BM, min(M, (y+1)*BM)), weights = w[].
+//   Grouped: tile y = tiles[y] if y < *n_tiles (else the workgroup exits); the weights are
+//   experts[tile.expert].{w1,w3,w2}[which[a]].
+//   Input row of tile row R:  x_rows ? x_rows[R] / x_row_div : R.
+struct RowSpace {
+    const TileDesc* tiles;
+    const int32_t* n_tiles;
+    const milo_w3lr_expert* experts;
+    int which[2];
+    WeightDev w[2];
+    int64_t M;
+    const int32_t* x_rows;
+    int32_t x_row_div;
+};
+
+struct TiledArgs {
+    RowSpace rs;
+    const f16* X;       // input rows, leading dimension ldx
+    int64_t ldx;
+    int64_t N, K;       // weight shape (out x in)
+    const f16* T[2];    // X V^T per weight stream, [rows x ldt] fp16, zero beyond the rank
+    int64_t ldt;
+    void* out;          // EPI 0/1: fp16 [rows x ldo];  EPI 2: fp32 [.. x ldo]
+    int64_t ldo;
+    const int32_t* out_rows;   // EPI 2: output row of tile row R (nullptr: R)
+    const float* out_scale;    // EPI 2: factor per output row (nullptr: 1)
+};
+
+struct TArgs {
+    RowSpace rs;
+    const f16* X;
+    int64_t ldx;
+    int64_t K;
+    f16* T[2];
+    int64_t ldt;
+    int bm;             // rows per tile of the row space (multiple of 32)
+};
+
+enum { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_SCALE_SCATTER = 2 };
+
+// Launchers.  mb = tile rows / 32 (1, 2 or 4); m_tiles = grid extent over tiles.
+int launch_t_kernel(const TArgs& a, int nw, int m_tiles, hipStream_t stream);
+int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipStream_t stream);
+
+struct DecodeArgs {
+    const f16* X;       // [M x K], M <= 16
+    int M;
+    int64_t N, K;
+    WeightDev w;
+    const f16* T;       // [M x ldt] fp16 (X V^T), zero beyond the rank
+    int64_t ldt;
+    f16* Y;             // [M x N]
+};
+int launch_decode(const DecodeArgs& a, hipStream_t stream);
+
+}  // namespace milo

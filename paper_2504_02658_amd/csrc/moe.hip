@@ -1,0 +1,286 @@
+// milo_moe_w3lr_forward: top-k routed SwiGLU experts over compensated W3A16 linears.
+//
+// Launch sequence on the caller's stream (no host synchronisation in between):
+//   route     group the (token, slot) pairs per expert: stable counting sort + M-tile list
+//   T13       T1 = X V1^T, T3 = X V3^T per expert (low-rank inputs of gate and up projection)
+//   gate/up   H = SiLU(lin_w1(x)) * lin_w3(x), both projections in one grouped launch
+//   T2        T2 = H V2^T
+//   down      O[pair] = gate_weight * lin_w2(H)       (fp32, one row per routed pair)
+//   combine   y_t = fp16( sum over the token's slots, in slot order, of O )
+#include "milo_host.h"
+#include "milo_kernels.h"
+
+namespace milo {
+
+constexpr int kRouteThreads = 1024;
+
+struct RouteArgs {
+    const int32_t* ids;     // [P] expert id per (token, slot) pair, pair index p = t*topk + j
+    int32_t P;
+    int32_t E;
+    int32_t bm;             // rows per M-tile
+    int32_t* sorted;        // [P] pair indices grouped by expert, original order inside a group
+    TileDesc* tiles;
+    int32_t* header;        // [0] routing status, [1] number of tiles
+};
+
+// One workgroup per expert.  Every workgroup histograms all ids itself (integer LDS atomics),
+// so no workgroup depends on another one and a single launch suffices.
+__global__ __launch_bounds__(kRouteThreads) void route_kernel(const RouteArgs a) {
+    extern __shared__ int32_t hist[];               // [E]
+    __shared__ int32_t s_off, s_tile0, s_tiles_total, s_bad, s_running;
+    __shared__ int32_t wcount[kRouteThreads / 64];
+
+    const int e = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < a.E; i += kRouteThreads) hist[i] = 0;
+    if (tid == 0) { s_off = 0; s_tile0 = 0; s_tiles_total = 0; s_bad = 0; s_running = 0; }
+    __syncthreads();
+    int bad = 0;
+    for (int i = tid; i < a.P; i += kRouteThreads) {
+        const int id = a.ids[i];
+        if (id >= 0 && id < a.E) atomicAdd(&hist[id], 1); else bad = 1;
+    }
+    if (bad) atomicOr(&s_bad, 1);
+    __syncthreads();
+    {
+        int off = 0, t0 = 0, tt = 0;
+        for (int i = tid; i < a.E; i += kRouteThreads) {
+            const int c = hist[i];
+            const int nt = (c + a.bm - 1) / a.bm;
+            tt += nt;
+            if (i < e) { off += c; t0 += nt; }
+        }
+        if (off) atomicAdd(&s_off, off);
+        if (t0) atomicAdd(&s_tile0, t0);
+        if (tt) atomicAdd(&s_tiles_total, tt);
+    }
+    __syncthreads();
+    const int off_e = s_off, tile0 = s_tile0, count = hist[e];
+
+    // stable scatter of the pairs routed to expert e
+    for (int base = 0; base < a.P; base += kRouteThreads) {
+        const int i = base + tid;
+        const bool mine = (i < a.P) && (a.ids[i] == e);
+        const unsigned long long bal = __ballot(mine);
+        if (lane == 0) wcount[wave] = __popcll(bal);
+        __syncthreads();
+        int before = s_running;
+        for (int w = 0; w < wave; ++w) before += wcount[w];
+        if (mine) a.sorted[off_e + before + __popcll(bal & ((1ull << lane) - 1ull))] = i;
+        __syncthreads();
+        if (tid == 0) {
+            int tot = 0;
+            for (int w = 0; w < kRouteThreads / 64; ++w) tot += wcount[w];
+            s_running += tot;
+        }
+        __syncthreads();
+    }
+
+    const int nt = (count + a.bm - 1) / a.bm;
+    for (int i = tid; i < nt; i += kRouteThreads) {
+        TileDesc td;
+        td.expert = e;
+        td.row0 = off_e + i * a.bm;
+        td.rows = (count - i * a.bm) < a.bm ? (count - i * a.bm) : a.bm;
+        td.pad = 0;
+        a.tiles[tile0 + i] = td;
+    }
+    if (e == 0 && tid == 0) {
+        a.header[0] = s_bad ? MILO_ERR_ROUTING : MILO_OK;
+        a.header[1] = s_tiles_total;
+    }
+}
+
+// y[t, h..h+3] = fp16( sum_j O[t*topk + j, h..h+3] ), slots in order, invalid ids skipped.
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ O,
+                                                      const int32_t* __restrict__ ids, int E,
+                                                      int topk, int64_t T, int64_t H,
+                                                      f16* __restrict__ Y) {
+    const int64_t t = blockIdx.y;
+    const int64_t h = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (h >= H) return;
+    f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int j = 0; j < topk; ++j) {
+        const int id = ids[t * topk + j];
+        if (id < 0 || id >= E) continue;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(O + (t * topk + j) * H + h);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum[e] += v[e];
+    }
+    f16x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (f16)sum[e];
+    *reinterpret_cast<f16x4*>(Y + t * H + h) = o;
+}
+
+struct MoeLayout {
+    int bm;
+    int max_tiles;
+    int64_t ldt;
+    size_t off_header, off_sorted, off_tiles, off_t1, off_t3, off_h, off_o, total;
+};
+
+static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_max, MoeLayout* L) {
+    if (T <= 0 || E <= 0 || topk <= 0 || r_max < 0) return false;
+    if (!weight_shape_ok(F, H) || !weight_shape_ok(H, F)) return false;
+    if (H % 4 != 0) return false;
+    const int64_t P = T * topk;
+    if (P > (int64_t)0x3fffffff || E > 65536) return false;
+    const int64_t avg = P / E;
+    L->bm = avg >= 96 ? 128 : (avg >= 48 ? 64 : 32);
+    const int64_t max_tiles32 = (P + 31) / 32 + E;      // bound for the smallest tile height
+    const int64_t max_tiles = (P + L->bm - 1) / L->bm + E;
+    if (max_tiles > 65535) return false;
+    L->max_tiles = (int)max_tiles;
+    L->ldt = ((int64_t)r_max + 15) / 16 * 16;
+    size_t off = 0;
+    L->off_header = off; off = align_up(off + 64, 256);
+    L->off_sorted = off; off = align_up(off + (size_t)P * 4, 256);
+    L->off_tiles = off;  off = align_up(off + (size_t)max_tiles32 * sizeof(TileDesc), 256);
+    L->off_t1 = off;     off = align_up(off + (size_t)P * L->ldt * 2, 256);
+    L->off_t3 = off;     off = align_up(off + (size_t)P * L->ldt * 2, 256);
+    L->off_h = off;      off = align_up(off + (size_t)P * F * 2, 256);
+    L->off_o = off;      off = align_up(off + (size_t)P * H * 4, 256);
+    L->total = off;
+    return true;
+}
+
+static int check_weight(const milo_w3lr_weight& w, int64_t N, int64_t K) {
+    if (!w.q3 || !w.scales || !w.zeros) return MILO_ERR_NULL;
+    if (w.r < 0 || w.r > N || w.r > K) return MILO_ERR_RANK;
+    if (w.r > 0 && (!w.U || !w.V)) return MILO_ERR_RANK;
+    if (!aligned16(w.q3) || !aligned16(w.scales) || !aligned16(w.zeros) || !aligned16(w.U) ||
+        !aligned16(w.V))
+        return MILO_ERR_ALIGN;
+    return MILO_OK;
+}
+
+}  // namespace milo
+
+using namespace milo;
+
+extern "C" int milo_moe_w3lr_check_experts(const milo_w3lr_expert* experts, int E, int64_t H,
+                                           int64_t F, int* r_max_out) {
+    if (!experts) return MILO_ERR_NULL;
+    if (E <= 0 || !weight_shape_ok(F, H) || !weight_shape_ok(H, F)) return MILO_ERR_SHAPE;
+    int r_max = 0;
+    for (int e = 0; e < E; ++e) {
+        const milo_w3lr_weight* ws[3] = {&experts[e].w1, &experts[e].w3, &experts[e].w2};
+        for (int i = 0; i < 3; ++i) {
+            const int64_t N = (i < 2) ? F : H, K = (i < 2) ? H : F;
+            const int st = check_weight(*ws[i], N, K);
+            if (st != MILO_OK) return st;
+            if (ws[i]->r > r_max) r_max = ws[i]->r;
+        }
+    }
+    if (r_max_out) *r_max_out = r_max;
+    return MILO_OK;
+}
+
+extern "C" size_t milo_moe_w3lr_workspace(int64_t T, int64_t H, int64_t F, int E, int topk,
+                                          int r_max) {
+    MoeLayout L;
+    if (!moe_layout(T, H, F, E, topk, r_max, &L)) return 0;
+    return L.total;
+}
+
+extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, int64_t F,
+                                     const milo_w3lr_expert* experts, int E, int r_max,
+                                     const int32_t* topk_ids, const float* topk_weights, int topk,
+                                     milo_half* Y, void* workspace, size_t workspace_bytes,
+                                     void* stream_) {
+    if (!X || !experts || !topk_ids || !topk_weights || !Y) return MILO_ERR_NULL;
+    MoeLayout L;
+    if (!moe_layout(T, H, F, E, topk, r_max, &L)) return MILO_ERR_SHAPE;
+    if (r_max > H || r_max > F) return MILO_ERR_RANK;
+    if (!workspace || workspace_bytes < L.total) return MILO_ERR_WORKSPACE;
+    if (!aligned16(X) || !aligned16(Y) || !aligned16(workspace) || !aligned16(experts) ||
+        !aligned16(topk_ids) || !aligned16(topk_weights))
+        return MILO_ERR_ALIGN;
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = reinterpret_cast<char*>(workspace);
+    int32_t* header = reinterpret_cast<int32_t*>(ws + L.off_header);
+    int32_t* sorted = reinterpret_cast<int32_t*>(ws + L.off_sorted);
+    TileDesc* tiles = reinterpret_cast<TileDesc*>(ws + L.off_tiles);
+    f16* T1 = reinterpret_cast<f16*>(ws + L.off_t1);
+    f16* T3 = reinterpret_cast<f16*>(ws + L.off_t3);
+    f16* Hbuf = reinterpret_cast<f16*>(ws + L.off_h);
+    float* O = reinterpret_cast<float*>(ws + L.off_o);
+    const int P = (int)(T * topk);
+
+    RouteArgs ra;
+    ra.ids = topk_ids; ra.P = P; ra.E = E; ra.bm = L.bm;
+    ra.sorted = sorted; ra.tiles = tiles; ra.header = header;
+    route_kernel<<<dim3((unsigned)E), dim3(kRouteThreads), (size_t)E * sizeof(int32_t), stream>>>(ra);
+    int st = launch_status();
+    if (st != MILO_OK) return st;
+
+    RowSpace rs;
+    rs.tiles = tiles; rs.n_tiles = header + 1; rs.experts = experts;
+    rs.M = P;
+    const int mb = L.bm / 32;
+
+    // gate / up projection
+    rs.which[0] = 0; rs.which[1] = 1;
+    rs.x_rows = sorted; rs.x_row_div = topk;
+    if (r_max > 0) {
+        TArgs ta;
+        ta.rs = rs; ta.X = reinterpret_cast<const f16*>(X); ta.ldx = H; ta.K = H;
+        ta.T[0] = T1; ta.T[1] = T3; ta.ldt = L.ldt; ta.bm = L.bm;
+        st = launch_t_kernel(ta, 2, L.max_tiles, stream);
+        if (st != MILO_OK) return st;
+    }
+    {
+        TiledArgs ga;
+        ga.rs = rs; ga.X = reinterpret_cast<const f16*>(X); ga.ldx = H; ga.N = F; ga.K = H;
+        ga.T[0] = T1; ga.T[1] = T3; ga.ldt = L.ldt;
+        ga.out = Hbuf; ga.ldo = F; ga.out_rows = nullptr; ga.out_scale = nullptr;
+        st = launch_tiled(ga, 2, mb, EPI_SWIGLU, L.max_tiles, stream);
+        if (st != MILO_OK) return st;
+    }
+    // down projection (T2 reuses the T1 buffer: T1 is dead once the gate/up kernel has run)
+    rs.which[0] = 2; rs.which[1] = 2;
+    rs.x_rows = nullptr; rs.x_row_div = 1;
+    if (r_max > 0) {
+        TArgs ta;
+        ta.rs = rs; ta.X = Hbuf; ta.ldx = F; ta.K = F;
+        ta.T[0] = T1; ta.T[1] = T1; ta.ldt = L.ldt; ta.bm = L.bm;
+        st = launch_t_kernel(ta, 1, L.max_tiles, stream);
+        if (st != MILO_OK) return st;
+    }
+    {
+        TiledArgs da;
+        da.rs = rs; da.X = Hbuf; da.ldx = F; da.N = H; da.K = F;
+        da.T[0] = T1; da.T[1] = T1; da.ldt = L.ldt;
+        da.out = O; da.ldo = H; da.out_rows = sorted; da.out_scale = topk_weights;
+        st = launch_tiled(da, 1, mb, EPI_SCALE_SCATTER, L.max_tiles, stream);
+        if (st != MILO_OK) return st;
+    }
+    {
+        const unsigned gx = (unsigned)((H / 4 + 255) / 256);
+        if (T > 65535) {
+            // grid.y limit: split the token range
+            for (int64_t t0 = 0; t0 < T; t0 += 65535) {
+                const int64_t nt = (T - t0) < 65535 ? (T - t0) : 65535;
+                combine_kernel<<<dim3(gx, (unsigned)nt), dim3(256), 0, stream>>>(
+                    O + t0 * topk * H, topk_ids + t0 * topk, E, topk, nt, H,
+                    reinterpret_cast<f16*>(Y) + t0 * H);
+            }
+        } else {
+            combine_kernel<<<dim3(gx, (unsigned)T), dim3(256), 0, stream>>>(
+                O, topk_ids, E, topk, T, H, reinterpret_cast<f16*>(Y));
+        }
+        st = launch_status();
+    }
+    return st;
+}
+
+extern "C" int milo_moe_w3lr_routing_status(const void* workspace, void* stream) {
+    if (!workspace) return MILO_ERR_NULL;
+    int32_t header[2] = {0, 0};
+    if (hipMemcpyAsync(header, workspace, sizeof(header), hipMemcpyDeviceToHost,
+                       (hipStream_t)stream) != hipSuccess)
+        return MILO_ERR_HIP;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return MILO_ERR_HIP;
+    return header[0] == MILO_OK ? MILO_OK : MILO_ERR_ROUTING;
+}

@@ -1,0 +1,203 @@
+// milo_pack_w3 / milo_unpack_w3 / milo_dequant_w3: group quantizer (Eq. wq, round-to-nearest
+// reading), the zero-waste 3-bit packer (Section 3.3) and the two test aids.
+//
+// This translation unit is compiled with -ffp-contract=off: the quantizer must perform one
+// binary32 rounding per operation (no fused multiply-add) so that its codes are reproducible
+// bit for bit.
+#include "milo_device.h"
+#include "milo_host.h"
+
+namespace milo {
+
+// 16 lanes cooperate on one unit (64 weights, one float4 each); a wave packs four units that
+// are consecutive groups of one row, so every load instruction of a wave reads 1 KB of that row.
+constexpr int kPackThreads = 256;
+constexpr int kUnitsPerBlock = kPackThreads / 16;
+
+__device__ __forceinline__ float shfl_xor16(float v, int m) { return __shfl_xor(v, m, 16); }
+__device__ __forceinline__ uint32_t shfl_xor16(uint32_t v, int m) {
+    return (uint32_t)__shfl_xor((int)v, m, 16);
+}
+
+__global__ __launch_bounds__(kPackThreads) void pack_w3_kernel(
+    const float* __restrict__ W, int64_t N, int64_t K, uint32_t* __restrict__ planeA,
+    uint32_t* __restrict__ planeB, f16* __restrict__ scales, f16* __restrict__ zeros) {
+    const int64_t G = K / kGroup;
+    const int64_t total = N * G;
+    const int64_t gu = (int64_t)blockIdx.x * kUnitsPerBlock + (threadIdx.x >> 4);
+    const int l16 = threadIdx.x & 15;
+    if (gu >= total) return;          // whole 16-lane groups leave together
+    const int64_t n = gu / G;
+    const int64_t g = gu - n * G;
+
+    const float4 v = *reinterpret_cast<const float4*>(W + n * K + g * kGroup + 4 * l16);
+    float mn = fminf(fminf(v.x, v.y), fminf(v.z, v.w));
+    float mx = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
+#pragma unroll
+    for (int m = 1; m < 16; m <<= 1) {
+        mn = fminf(mn, shfl_xor16(mn, m));
+        mx = fmaxf(mx, shfl_xor16(mx, m));
+    }
+
+    const float s32 = (mx - mn) / 7.0f;
+    f16 s16 = (f16)s32;
+    float sf = (float)s16;
+    const bool degenerate = !(sf > 0.0f && sf <= 65504.0f);   // zero, NaN or overflowed scale
+    f16 z16;
+    uint32_t q[4];
+    if (degenerate) {
+        s16 = (f16)1.0f;
+        z16 = (f16)(-mn);
+        q[0] = q[1] = q[2] = q[3] = 0u;
+    } else {
+        float z = __builtin_rintf((-mn) / sf);
+        z = fminf(fmaxf(z, -65504.0f), 65504.0f);
+        z16 = (f16)z;
+        const float zf = (float)z16;
+        const float in[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float t = in[i] / sf;
+            t = t + zf;
+            t = __builtin_rintf(t);
+            t = fminf(fmaxf(t, 0.0f), 7.0f);
+            q[i] = (uint32_t)t;
+        }
+    }
+
+    // This lane owns code pairs P0 = 2*l16 (codes 4*l16, 4*l16+1) and P0+1.  Build its share of
+    // the six words, then OR the shares of the 16 lanes together.
+    uint32_t d[6] = {0u, 0u, 0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int P = 2 * l16 + h;
+        const uint32_t lo = q[2 * h], hi = q[2 * h + 1];
+        if (P < 30) {
+            const int j = P / 5, c = P - 5 * j;
+            const uint32_t bits = (lo << (3 * c)) | (hi << (16 + 3 * c));
+#pragma unroll
+            for (int jj = 0; jj < 6; ++jj)
+                if (jj == j) d[jj] |= bits;
+        } else {
+            const int base = (P == 30) ? 0 : 3;
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const uint32_t bits = (((lo >> i) & 1u) << 15) | (((hi >> i) & 1u) << 31);
+#pragma unroll
+                for (int jj = 0; jj < 6; ++jj)
+                    if (jj == base + i) d[jj] |= bits;
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 1; m < 16; m <<= 1) {
+#pragma unroll
+        for (int jj = 0; jj < 6; ++jj) d[jj] |= shfl_xor16(d[jj], m);
+    }
+
+    if (l16 == 0) {
+        const int64_t u = unit_index(n, g, G);
+        *reinterpret_cast<u32x4*>(planeA + 4 * u) = u32x4{d[0], d[1], d[2], d[3]};
+        *reinterpret_cast<u32x2*>(planeB + 2 * u) = u32x2{d[4], d[5]};
+        scales[u] = s16;
+        zeros[u] = z16;
+    }
+}
+
+// One thread per unit: unpack to bytes / dequantize to fp16.  Test aids, not tuned.
+__global__ __launch_bounds__(256) void unpack_w3_kernel(W3View w, int64_t N, int64_t K,
+                                                        uint8_t* __restrict__ codes) {
+    const int64_t G = w.G;
+    const int64_t gu = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gu >= N * G) return;
+    const int64_t n = gu / G, g = gu - n * G;
+    const int64_t u = unit_index(n, g, G);
+    const u32x4 a = w.planeA[u];
+    const u32x2 b = w.planeB[u];
+    const uint32_t d[6] = {a.x, a.y, a.z, a.w, b.x, b.y};
+    uint8_t* out = codes + n * K + g * kGroup;
+    for (int P = 0; P < 32; ++P) {
+        uint32_t lo, hi;
+        if (P < 30) {
+            const int j = P / 5, c = P % 5;
+            lo = (d[j] >> (3 * c)) & 7u;
+            hi = (d[j] >> (16 + 3 * c)) & 7u;
+        } else {
+            const int base = (P == 30) ? 0 : 3;
+            lo = hi = 0u;
+            for (int i = 0; i < 3; ++i) {
+                lo |= ((d[base + i] >> 15) & 1u) << i;
+                hi |= ((d[base + i] >> 31) & 1u) << i;
+            }
+        }
+        out[2 * P] = (uint8_t)lo;
+        out[2 * P + 1] = (uint8_t)hi;
+    }
+}
+
+__global__ __launch_bounds__(256) void dequant_w3_kernel(W3View w, int64_t N, int64_t K,
+                                                         f16* __restrict__ Wdq) {
+    const int64_t G = w.G;
+    const int64_t gu = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gu >= N * G) return;
+    const int64_t n = gu / G, g = gu - n * G;
+    const RawUnit ru = load_unit<false>(w, unit_index(n, g, G));
+    uint32_t wv[32];
+    dequant_unit(ru, wv);
+    u32x4* out = reinterpret_cast<u32x4*>(Wdq + n * K + g * kGroup);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out[i] = u32x4{wv[4 * i], wv[4 * i + 1], wv[4 * i + 2], wv[4 * i + 3]};
+}
+
+}  // namespace milo
+
+using namespace milo;
+
+extern "C" size_t milo_w3_packed_bytes(int64_t N, int64_t K) {
+    if (!weight_shape_ok(N, K)) return 0;
+    return (size_t)(N * K / 8 * 3);
+}
+
+extern "C" int milo_pack_w3(const float* W, int64_t N, int64_t K, int group_size, void* q3,
+                            milo_half* scales, milo_half* zeros, void* stream) {
+    if (!W || !q3 || !scales || !zeros) return MILO_ERR_NULL;
+    if (group_size != kGroup) return MILO_ERR_GROUP;
+    if (!weight_shape_ok(N, K)) return MILO_ERR_SHAPE;
+    if (!aligned16(W) || !aligned16(q3) || !aligned16(scales) || !aligned16(zeros))
+        return MILO_ERR_ALIGN;
+    const int64_t units = N * (K / kGroup);
+    const int64_t blocks = (units + kUnitsPerBlock - 1) / kUnitsPerBlock;
+    if (blocks > 0x7fffffff) return MILO_ERR_SHAPE;
+    uint32_t* planeA = reinterpret_cast<uint32_t*>(q3);
+    uint32_t* planeB = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(q3) + (N * K) / 4);
+    pack_w3_kernel<<<dim3((unsigned)blocks), dim3(kPackThreads), 0, (hipStream_t)stream>>>(
+        W, N, K, planeA, planeB, reinterpret_cast<f16*>(scales), reinterpret_cast<f16*>(zeros));
+    return launch_status();
+}
+
+extern "C" int milo_unpack_w3(const void* q3, int64_t N, int64_t K, uint8_t* codes, void* stream) {
+    if (!q3 || !codes) return MILO_ERR_NULL;
+    if (!weight_shape_ok(N, K)) return MILO_ERR_SHAPE;
+    if (!aligned16(q3)) return MILO_ERR_ALIGN;
+    const int64_t units = N * (K / kGroup);
+    const int64_t blocks = (units + 255) / 256;
+    if (blocks > 0x7fffffff) return MILO_ERR_SHAPE;
+    W3View w = make_view(q3, nullptr, nullptr, N, K);
+    unpack_w3_kernel<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>(w, N, K, codes);
+    return launch_status();
+}
+
+extern "C" int milo_dequant_w3(const void* q3, const milo_half* scales, const milo_half* zeros,
+                               int64_t N, int64_t K, milo_half* W_dq, void* stream) {
+    if (!q3 || !scales || !zeros || !W_dq) return MILO_ERR_NULL;
+    if (!weight_shape_ok(N, K)) return MILO_ERR_SHAPE;
+    if (!aligned16(q3) || !aligned16(scales) || !aligned16(zeros) || !aligned16(W_dq))
+        return MILO_ERR_ALIGN;
+    const int64_t units = N * (K / kGroup);
+    const int64_t blocks = (units + 255) / 256;
+    if (blocks > 0x7fffffff) return MILO_ERR_SHAPE;
+    W3View w = make_view(q3, scales, zeros, N, K);
+    dequant_w3_kernel<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>(
+        w, N, K, reinterpret_cast<f16*>(W_dq));
+    return launch_status();
+}

@@ -1,0 +1,81 @@
+"""Shared plumbing of the GPU parity tests: build one workload on both sides and compare."""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+import oracle
+from paper_2504_02658_amd import workloads as wl
+
+REL_FRO_TOL = 1e-3          # relative Frobenius error against the fp64 oracle
+MAX_ABS_TOL = 2e-2          # max |err| as a fraction of max |Y_ref|
+
+
+def assert_close(Y_gpu, Y_ref, what=""):
+    Y = np.asarray(Y_gpu, dtype=np.float64)
+    R = np.asarray(Y_ref, dtype=np.float64)
+    assert Y.shape == R.shape, (Y.shape, R.shape)
+    assert np.all(np.isfinite(Y)), f"{what}: non-finite output"
+    denom = np.linalg.norm(R)
+    rel = np.linalg.norm(Y - R) / denom if denom > 0 else np.linalg.norm(Y - R)
+    mx = np.max(np.abs(Y - R)) / max(np.max(np.abs(R)), 1e-30)
+    assert rel <= REL_FRO_TOL, f"{what}: relative Frobenius error {rel:.3e} > {REL_FRO_TOL}"
+    assert mx <= MAX_ABS_TOL, f"{what}: max abs error {mx:.3e} of max|Y_ref| > {MAX_ABS_TOL}"
+    return rel, mx
+
+
+def oracle_weight(W, r, seed=0, exact_svd_limit=2048 * 2048):
+    """Quantize W on the CPU and fit the rank-r compensator to the residual."""
+    q, s, z = oracle.quantize_rtn(W)
+    if r > 0:
+        E = W.astype(np.float64) - oracle.dequantize(q, s, z)
+        if W.size <= exact_svd_limit:
+            U, V, _ = oracle.svd_compensator(E, r)
+        else:
+            U, V = oracle.randomized_svd_compensator(E, r, seed=seed)
+        U, V = U.astype(np.float16), V.astype(np.float16)
+    else:
+        U = np.zeros((W.shape[0], 0), np.float16)
+        V = np.zeros((0, W.shape[1]), np.float16)
+    return dict(codes=q, scales=s, zeros=z, U=U, V=V)
+
+
+def gpu_weight(W, ow, check_pack=True):
+    """Pack W with the library; the compensator comes from the oracle side as an input."""
+    import torch
+    from paper_2504_02658_amd import api
+    pw = api.pack_w3(torch.from_numpy(W).cuda())
+    if check_pack:
+        N, K = W.shape
+        assert np.array_equal(pw.q3.cpu().numpy(), oracle.pack_w3(ow["codes"])), "packed codes differ"
+        assert np.array_equal(pw.scales.cpu().numpy().view(np.uint16),
+                              oracle.to_unit_order(ow["scales"]).view(np.uint16)), "scales differ"
+        assert np.array_equal(pw.zeros.cpu().numpy().view(np.uint16),
+                              oracle.to_unit_order(ow["zeros"]).view(np.uint16)), "zeros differ"
+    if ow["U"].shape[1] > 0:
+        pw = pw.with_compensator(torch.from_numpy(ow["U"]).cuda(), torch.from_numpy(ow["V"]).cuda())
+    return pw
+
+
+def build_moe(case, threads=8):
+    """Both sides of an MoE layer: list of oracle expert dicts and the library's MoELayer."""
+    from paper_2504_02658_amd import api
+    ranks = wl.expert_ranks(case)
+    n_exp = case.E + case.n_shared
+
+    def one(e):
+        out = {}
+        for which in ("w1", "w3", "w2"):
+            W = wl.expert_weight(case, e, which)
+            out[which] = (W, oracle_weight(W, ranks[e], seed=case.seed + 7 * e))
+        return out
+
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        built = list(pool.map(one, range(n_exp)))
+    o_experts, g_experts = [], []
+    for b in built:
+        o_experts.append({k: b[k][1] for k in b})
+        g_experts.append(tuple(gpu_weight(b[k][0], b[k][1]) for k in ("w1", "w3", "w2")))
+        for k in b:
+            b[k] = None
+    layer = api.MoELayer(g_experts, case.H, case.F)
+    return o_experts, layer

@@ -1,0 +1,164 @@
+"""GPU parity of milo_w3lr_gemm against the fp64 oracle (decode kernel for M <= 16, tiled above)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2504_02658_amd import workloads as wl
+from helpers import assert_close, oracle_weight, gpu_weight
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(X, pw):
+    import torch
+    from paper_2504_02658_amd import api
+    return api.w3lr_gemm(torch.from_numpy(X).cuda(), pw).cpu().numpy()
+
+
+def _check_case(M, N, K, r, seed, outlier_frac=0.0):
+    case = wl.LinearCase("t", M=M, N=N, K=K, r=r, seed=seed, outlier_frac=outlier_frac)
+    X, W = wl.linear_inputs(case)
+    ow = oracle_weight(W, r, seed=seed)
+    pw = gpu_weight(W, ow)
+    ref = oracle.w3lr_linear(X, **ow)
+    Y = _run(X, pw)
+    return assert_close(Y, ref, f"M{M} N{N} K{K} r{r}")
+
+
+def test_c0_small_config():
+    c = wl.C0
+    _check_case(c.M, c.N, c.K, c.r, c.seed)
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 7, 15, 16])
+def test_decode_rows(M):
+    _check_case(M, 272, 1408, 8, seed=40 + M)          # ragged N (not a multiple of 32), K = 22 groups
+
+
+@pytest.mark.parametrize("N,K,r", [(16, 64, 0), (48, 192, 8), (1024, 4096, 32), (272, 2112, 24),
+                                   (64, 1024, 40), (528, 3136, 16)])
+def test_decode_shapes(N, K, r):
+    _check_case(16, N, K, r, seed=N + K + r)
+    _check_case(5, N, K, r, seed=N + K + r + 1)
+
+
+@pytest.mark.parametrize("M", [17, 32, 33, 64, 100, 130, 257])
+def test_tiled_rows(M):
+    _check_case(M, 272, 1408, 8, seed=60 + M)
+
+
+@pytest.mark.parametrize("N,K,r", [(16, 64, 0), (48, 192, 8), (528, 1024, 64), (1408, 2048, 128),
+                                   (256, 832, 20), (2048, 1408, 136)])
+def test_tiled_shapes(N, K, r):
+    _check_case(96, N, K, r, seed=N + K + r)
+
+
+def test_rank_zero_equals_no_compensator_and_is_deterministic():
+    import torch
+    from paper_2504_02658_amd import api
+    case = wl.LinearCase("t", M=40, N=512, K=1024, r=16, seed=9)
+    X, W = wl.linear_inputs(case)
+    ow = oracle_weight(W, 16)
+    pw = gpu_weight(W, ow)
+    pw0 = api.PackedWeight(pw.N, pw.K, pw.q3, pw.scales, pw.zeros)
+    for Xm in (X, X[:9]):
+        Y0 = _run(Xm, pw0)
+        assert_close(Y0, oracle.w3lr_linear(Xm, ow["codes"], ow["scales"], ow["zeros"]), "rank 0")
+        Y1a, Y1b = _run(Xm, pw), _run(Xm, pw)
+        assert np.array_equal(Y1a.view(np.uint16), Y1b.view(np.uint16)), "two runs differ"
+        assert not np.array_equal(Y0, Y1a)
+
+
+@pytest.mark.parametrize("M", [8, 48])
+def test_integer_case_is_exact(M):
+    import torch
+    from paper_2504_02658_amd import api
+    rng = np.random.default_rng(3)
+    N, K = 64, 256
+    q = rng.integers(0, 8, size=(N, K), dtype=np.uint8)
+    s = np.ones((N, K // 64), np.float16)
+    z = np.zeros((N, K // 64), np.float16)
+    X = rng.integers(-1, 2, size=(M, K)).astype(np.float16)
+    pw = api.PackedWeight(N, K, torch.from_numpy(oracle.pack_w3(q)).cuda(),
+                          torch.from_numpy(oracle.to_unit_order(s)).cuda(),
+                          torch.from_numpy(oracle.to_unit_order(z)).cuda())
+    Y = _run(X, pw).astype(np.float64)
+    assert np.array_equal(Y, oracle.w3lr_linear(X, q, s, z))
+
+
+@pytest.mark.parametrize("M", [16, 64])
+def test_one_hot_activations_expose_the_layout(M):
+    # X = rows of the identity: output row k is column k of W_dq + U V, so any permutation of k
+    # inside a unit, any swapped plane or transposed compensator shows up element by element.
+    N, K, r = 48, 192, 8
+    case = wl.LinearCase("t", M=M, N=N, K=K, r=r, seed=77)
+    _, W = wl.linear_inputs(case)
+    ow = oracle_weight(W, r)
+    pw = gpu_weight(W, ow)
+    Wt = oracle.dequantize(ow["codes"], ow["scales"], ow["zeros"]) + \
+        ow["U"].astype(np.float64) @ ow["V"].astype(np.float64)
+    for k0 in range(0, K, M):
+        X = np.zeros((M, K), np.float16)
+        X[np.arange(M), k0 + np.arange(M)] = 1.0
+        Y = _run(X, pw).astype(np.float64)
+        ref = Wt[:, k0:k0 + M].T
+        assert np.max(np.abs(Y - ref)) <= 2.0 ** -10 * np.max(np.abs(ref)) + 1e-6, f"k0={k0}"
+
+
+def test_real_valued_zero_points():
+    import torch
+    from paper_2504_02658_amd import api
+    rng = np.random.default_rng(12)
+    N, K, r = 128, 512, 0
+    q = rng.integers(0, 8, size=(N, K), dtype=np.uint8)
+    s = rng.uniform(0.005, 0.03, size=(N, K // 64)).astype(np.float16)
+    z = rng.uniform(1.5, 5.5, size=(N, K // 64)).astype(np.float16)
+    pw = api.PackedWeight(N, K, torch.from_numpy(oracle.pack_w3(q)).cuda(),
+                          torch.from_numpy(oracle.to_unit_order(s)).cuda(),
+                          torch.from_numpy(oracle.to_unit_order(z)).cuda())
+    for M in (4, 40):
+        X = rng.standard_normal((M, K)).astype(np.float16)
+        assert_close(_run(X, pw), oracle.w3lr_linear(X, q, s, z), f"real z, M={M}")
+
+
+def test_gpu_argument_errors():
+    import torch
+    from paper_2504_02658_amd import api
+    X = torch.zeros((4, 128), dtype=torch.float16, device="cuda")
+    W = torch.zeros((32, 128), dtype=torch.float32, device="cuda")
+    pw = api.pack_w3(W)
+    with pytest.raises(api.MiloError) as ei:
+        api.pack_w3(W, group_size=128)
+    assert ei.value.status == 3
+    with pytest.raises(api.MiloError) as ei:
+        api.w3lr_gemm(X, pw, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert ei.value.status == 5
+    with pytest.raises(ValueError):
+        api.w3lr_gemm(torch.zeros((4, 64), dtype=torch.float16, device="cuda"), pw)
+
+
+# ------------------------------------------------------------------ full-size configurations
+
+@pytest.fixture(scope="module")
+def c1_weight():
+    c = wl.C1[16]
+    W = wl.gen_weight(c.N, c.K, c.seed, c.outlier_frac, c.outlier_gain)
+    ow = oracle_weight(W, c.r, seed=c.seed)
+    pw = gpu_weight(W, ow)
+    return ow, pw
+
+
+@pytest.mark.parametrize("M", [1, 4, 16])
+def test_c1_mixtral_up_projection_decode(c1_weight, M):
+    ow, pw = c1_weight
+    c = wl.C1[M]
+    X = wl.gen_activations(c.M, c.K, c.seed)
+    assert_close(_run(X, pw), oracle.w3lr_linear(X, **ow), c.name)
+
+
+def test_c2_mixtral_down_projection_prefill():
+    c = wl.C2
+    X, W = wl.linear_inputs(c)
+    ow = oracle_weight(W, c.r, seed=c.seed)
+    pw = gpu_weight(W, ow)
+    assert_close(_run(X, pw), oracle.w3lr_linear(X, **ow), c.name)

@@ -1,0 +1,76 @@
+"""GPU parity of milo_moe_w3lr_forward against the fp64 oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2504_02658_amd import workloads as wl
+from helpers import assert_close, build_moe
+
+pytestmark = pytest.mark.gpu
+
+
+def _forward(layer, X, ids, gates):
+    import torch
+    Y = layer.forward(torch.from_numpy(X).cuda(), torch.from_numpy(ids).cuda(),
+                      torch.from_numpy(gates).cuda())
+    return Y.cpu().numpy()
+
+
+def _check(case, what=None):
+    o_experts, layer = build_moe(case)
+    X = wl.moe_activations(case)
+    ids, gates = wl.moe_routing(case)
+    ref = oracle.moe_forward(X, o_experts, ids, gates)
+    Y = _forward(layer, X, ids, gates)
+    res = assert_close(Y, ref, what or case.name)
+    assert layer.routing_status() == 0
+    Y2 = _forward(layer, X, ids, gates)
+    assert np.array_equal(Y.view(np.uint16), Y2.view(np.uint16)), "two runs differ"
+    return res
+
+
+def test_tiny_layer_all_tile_heights():
+    base = wl.MoECase("tiny", T=40, H=256, F=384, E=4, topk=2, seed=11, rank_choices=(0, 8, 16))
+    _check(base)                                              # ~20 rows per expert: 32-row tiles
+    _check(wl.scaled(base, T=150, name="tiny64"))            # ~75 rows: 64-row tiles
+    _check(wl.scaled(base, T=400, name="tiny128"))           # ~200 rows: 128-row tiles, several per expert
+
+
+def test_single_token_and_empty_experts():
+    case = wl.MoECase("one", T=1, H=128, F=192, E=8, topk=2, seed=12, rank_choices=(8,))
+    _check(case)                                              # six experts receive nothing
+
+
+def test_shared_experts_and_skew():
+    case = wl.scaled(wl.C4, T=200, H=256, F=320, E=16, topk=4, name="ds_small", shared_rank=24)
+    _check(case)
+
+
+def test_reduced_mixtral_and_deepseek_shapes():
+    _check(wl.scaled(wl.C3, T=96, H=512, F=1792, name="c3_reduced"))
+    _check(wl.scaled(wl.C4, T=512, H=512, F=704, name="c4_reduced"))
+
+
+def test_out_of_range_expert_id_is_skipped_and_flagged():
+    case = wl.MoECase("bad", T=24, H=128, F=192, E=4, topk=2, seed=13, rank_choices=(8,))
+    o_experts, layer = build_moe(case)
+    X = wl.moe_activations(case)
+    ids, gates = wl.moe_routing(case)
+    ids = ids.copy()
+    ids[5, 1] = 4
+    ids[7, 0] = -1
+    good = (ids >= 0) & (ids < 4)
+    ref = oracle.moe_forward(X, o_experts, np.where(good, ids, 0), np.where(good, gates, 0).astype(np.float32))
+    Y = _forward(layer, X, ids, gates)
+    assert_close(Y, ref, "bad ids skipped")
+    assert layer.routing_status() == 6
+
+
+@pytest.mark.timeout(900)
+def test_c3_mixtral_layer_full_size():
+    _check(wl.C3)
+
+
+@pytest.mark.timeout(900)
+def test_c4_deepseek_layer_full_size():
+    _check(wl.C4)
