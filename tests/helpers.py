@@ -23,7 +23,7 @@ def assert_close(Y_gpu, Y_ref, what=""):
     return rel, mx
 
 
-def oracle_weight(W, r, seed=0, exact_svd_limit=2048 * 2048):
+def oracle_weight(W, r, seed=0, exact_svd_limit=1024 * 1024):
     """Quantize W on the CPU and fit the rank-r compensator to the residual."""
     q, s, z = oracle.quantize_rtn(W)
     if r > 0:
