@@ -99,12 +99,24 @@ int milo_dequant_w3(const void* q3, const milo_half* scales, const milo_half* ze
                     int64_t N, int64_t K, milo_half* W_dq, void* stream);
 
 /*
+ * Prepare a freshly allocated workspace (for milo_w3lr_gemm or milo_moe_w3lr_forward): clears the
+ * 256-byte control block at its start with a small fill kernel on `stream`.  Call it once after
+ * allocating the workspace and again after a call on it returned an error; the kernels leave the
+ * control block cleared when they finish, so successive calls need no further preparation and no
+ * memset (which makes them safe to capture in a HIP graph and replay).
+ * Errors: NULL, WORKSPACE (fewer than 256 bytes), ALIGN, HIP.
+ */
+int milo_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * One compensated W3A16 linear:  Y = X dequant(Q3)^T + (X V^T) U^T.
  *   X [M x K] fp16;  q3/scales/zeros as written by milo_pack_w3 (zeros may be any finite fp16,
  *   integer or not);  U [N x r], V [r x K] fp16 row-major, ignored when r == 0;  Y [M x N] fp16.
- *   workspace: at least milo_w3lr_gemm_workspace(M, N, K, r) bytes of device memory; its
- *   contents are scratch.  Calls that share a workspace must be ordered on one stream.
- * M <= 16 takes the weight-streaming decode kernel, larger M the tiled MFMA kernel.
+ *   workspace: at least milo_w3lr_gemm_workspace(M, N, K, r) bytes of device memory, prepared
+ *   once with milo_workspace_init; beyond the control block its contents are scratch.  Calls that
+ *   share a workspace must be ordered on one stream (concurrent calls would race on it).
+ * M <= 16 takes the weight-streaming decode kernel (a single launch that also forms X V^T),
+ * larger M the tiled MFMA kernel.
  * Errors: NULL, SHAPE, RANK, WORKSPACE, ALIGN, HIP.
  */
 size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int r);

@@ -19,6 +19,7 @@ STATUS_NAMES = {0: "MILO_OK", 1: "MILO_ERR_NULL", 2: "MILO_ERR_SHAPE", 3: "MILO_
 
 # every symbol include/milo.h declares
 EXPORTS = ("milo_status_string", "milo_version", "milo_w3_packed_bytes", "milo_pack_w3",
+           "milo_workspace_init",
            "milo_unpack_w3", "milo_dequant_w3", "milo_w3lr_gemm_workspace", "milo_w3lr_gemm",
            "milo_moe_w3lr_check_experts", "milo_moe_w3lr_workspace", "milo_moe_w3lr_forward",
            "milo_moe_w3lr_routing_status")
@@ -63,6 +64,8 @@ def lib():
         L.milo_unpack_w3.argtypes = [vp, i64, i64, vp, vp]
         L.milo_dequant_w3.restype = ci
         L.milo_dequant_w3.argtypes = [vp, vp, vp, i64, i64, vp, vp]
+        L.milo_workspace_init.restype = ci
+        L.milo_workspace_init.argtypes = [vp, sz, vp]
         L.milo_w3lr_gemm_workspace.restype = sz
         L.milo_w3lr_gemm_workspace.argtypes = [i64, i64, i64, ci]
         L.milo_w3lr_gemm.restype = ci
@@ -162,6 +165,13 @@ def dequant_w3(pw):
     return out
 
 
+def new_workspace(nbytes, device="cuda"):
+    """Allocate a workspace and prepare its control block (milo_workspace_init)."""
+    ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+    _check(lib().milo_workspace_init(_ptr(ws), ws.numel(), _stream()), "milo_workspace_init")
+    return ws
+
+
 def gemm_workspace_bytes(M, N, K, r):
     return int(lib().milo_w3lr_gemm_workspace(M, N, K, r))
 
@@ -176,7 +186,7 @@ def w3lr_gemm(X, pw, out=None, workspace=None):
         out = torch.empty((M, pw.N), dtype=torch.float16, device=X.device)
     need = gemm_workspace_bytes(M, pw.N, K, pw.r)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+        workspace = new_workspace(need, X.device)
     _check(lib().milo_w3lr_gemm(_ptr(X), M, pw.N, K, _ptr(pw.q3), _ptr(pw.scales), _ptr(pw.zeros),
                                 _ptr(pw.U), _ptr(pw.V), pw.r, _ptr(out), _ptr(workspace),
                                 workspace.numel(), _stream()), "milo_w3lr_gemm")
@@ -213,7 +223,7 @@ class MoELayer:
         need = self.workspace_bytes(T, topk)
         if workspace is None:
             if self._ws is None or self._ws.numel() < need:
-                self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+                self._ws = new_workspace(need, X.device)
             workspace = self._ws
         if out is None:
             out = torch.empty((T, H), dtype=torch.float16, device=X.device)

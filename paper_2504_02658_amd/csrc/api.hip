@@ -21,6 +21,19 @@ extern "C" const char* milo_status_string(int status) {
 
 extern "C" int milo_version(void) { return 100; }
 
+namespace milo {
+__global__ void clear_control_kernel(uint32_t* p) { p[threadIdx.x] = 0u; }
+}  // namespace milo
+
+extern "C" int milo_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+    if (!workspace) return MILO_ERR_NULL;
+    if (workspace_bytes < 256) return MILO_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return MILO_ERR_ALIGN;
+    clear_control_kernel<<<dim3(1), dim3(64), 0, (hipStream_t)stream>>>(
+        reinterpret_cast<uint32_t*>(workspace));
+    return launch_status();
+}
+
 static int64_t rank_pad(int r) { return ((int64_t)r + 15) / 16 * 16; }
 
 static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
@@ -29,8 +42,9 @@ static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
 
 extern "C" size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int r) {
     if (!gemm_shape_ok(M, N, K) || r < 0) return 0;
-    // T = X V^T as fp16 [M x pad16(r)]; never zero so that callers can always allocate it
-    return align_up((size_t)M * (size_t)rank_pad(r) * 2 + 256, 256);
+    if (M <= 16) return decode_workspace_bytes(r);
+    // T = X V^T as fp16 [M x pad16(r)] behind a 256-byte control block
+    return 256 + align_up((size_t)M * (size_t)rank_pad(r) * 2 + 256, 256);
 }
 
 extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t K, const void* q3,
@@ -56,11 +70,21 @@ extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t 
     w.V = reinterpret_cast<const f16*>(V);
     w.r = r;
     w.reserved = 0;
-    f16* T = reinterpret_cast<f16*>(workspace);
+    const bool decode = M <= 16;
+    if (decode) {
+        // 32-bit buffer offsets in the decode kernel
+        if ((uint64_t)M * K * 2 >= 0xFFFFFFF0ull || ((uint64_t)r + 128) * K * 2 >= 0xFFFFFFF0ull ||
+            (uint64_t)N * (uint64_t)(r > 0 ? r : 1) * 2 >= 0xFFFFFFF0ull)
+            return MILO_ERR_SHAPE;
+        DecodeArgs da;
+        da.X = reinterpret_cast<const f16*>(X); da.M = (int)M; da.N = N; da.K = K;
+        da.w = w; da.Y = reinterpret_cast<f16*>(Y);
+        return launch_decode(da, workspace, stream);
+    }
+    f16* T = reinterpret_cast<f16*>(reinterpret_cast<char*>(workspace) + 256);
     const int64_t ldt = rank_pad(r);
 
-    const bool decode = M <= 16;
-    const int mb = decode ? 1 : (M <= 32 ? 1 : (M <= 64 ? 2 : 4));
+    const int mb = M <= 32 ? 1 : (M <= 64 ? 2 : 4);
     const int bm = 32 * mb;
     const int64_t m_tiles = (M + bm - 1) / bm;
     if (m_tiles > 65535) return MILO_ERR_SHAPE;
@@ -77,12 +101,6 @@ extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t 
         ta.T[0] = ta.T[1] = T; ta.ldt = ldt; ta.bm = bm;
         const int st = launch_t_kernel(ta, 1, (int)m_tiles, stream);
         if (st != MILO_OK) return st;
-    }
-    if (decode) {
-        DecodeArgs da;
-        da.X = reinterpret_cast<const f16*>(X); da.M = (int)M; da.N = N; da.K = K;
-        da.w = w; da.T = T; da.ldt = ldt; da.Y = reinterpret_cast<f16*>(Y);
-        return launch_decode(da, stream);
     }
     TiledArgs ga;
     ga.rs = rs; ga.X = reinterpret_cast<const f16*>(X); ga.ldx = K; ga.N = N; ga.K = K;

@@ -1,187 +1,381 @@
-// Weight-streaming kernel for the compensated W3A16 linear at M <= 16 (decode).
+// Weight-streaming kernel for the compensated W3A16 linear at M <= 16 (decode): ONE launch that
+// streams the packed weight once from HBM, forms T = X V^T cooperatively and adds T U^T.
 //
-// The job is bound by reading the packed weight once from HBM, so the kernel is organised
-// around the weight stream: a workgroup of four waves owns 32 output features (two 16-row
-// blocks) over the whole K.  K is walked in stages of 1024; inside a stage wave w takes the
-// 256-wide chunk w, so that one lane of one wave loads exactly one unit (24 bytes of codes,
-// one scale, one zero-point) per row block and chunk with fully coalesced 16- and 8-byte
-// loads, several stages ahead of their use.  The lane converts its unit in registers and
-// feeds it as the A operand of v_mfma_f32_16x16x32_f16 (lane quad q = group 4c+q, eight steps
-// of eight codes); the activations are the B operand, staged per stage in LDS in MFMA lane
-// order (double buffered) and shared by both row blocks.  At the end the four waves' partial
-// sums are added in a fixed order through LDS, the low-rank term T U^T is added with a few
-// more MFMAs and the tile is rounded once to fp16.
+// Weight stream.  A workgroup of eight waves owns 16*R output features over the whole K.  K is
+// walked in pieces of 16 chunks of 256; wave w takes chunks w and w+8 of the piece for all R
+// 16-row blocks, so for K = 4096 every load of the launch is issued in the first few hundred
+// cycles.  For a chunk a
+// lane loads one unit per 16-row block (24 bytes of codes, one scale, one zero-point) with fully
+// coalesced 16- and 8-byte buffer loads and no branches (lanes without data read out of range
+// and get zeros), converts it in registers and feeds it as the A operand of
+// v_mfma_f32_16x16x32_f16 (lane quad q = group 4c+q, eight steps of eight codes).
+// The activations of a chunk, X[0..15][256c .. 256c+255], are the B operand of every block.  The
+// workgroup stages a whole piece of X (16 rows x 4096 columns, 128 KB) in LDS once: a wave
+// copies each of its chunks with eight coalesced 1-KB buffer-to-LDS loads (two full 512-byte row pieces
+// each, no registers involved); the
+// 16-byte segment that sits at slot position p of row j is segment p ^ j of the row, which makes
+// the later per-lane ds_read_b128 of the B fragments conflict free although the 16 lanes of a
+// quad read 16 rows.  One barrier per piece; the waves' partial sums are added in a fixed order
+// at the very end.
+//
+// Low-rank term.  The first `nt` workgroups do no streaming: each computes one K-slice of
+// T = X V^T (fp32 partial in the workspace); whichever of them finishes last adds the partials in
+// slice order (so the result does not depend on which one that was), writes T as fp16 and
+// raises a flag.  The streaming workgroups only need T in their epilogue, where they add T U^T
+// with a few more MFMAs.  The workers never wait for anything, they have the lowest workgroup
+// ids, and the grid never exceeds what the device keeps resident, so the epilogue's wait always
+// ends.  Data that crosses workgroups is written and read with device-coherent accesses, and
+// the last workgroup to leave restores the control words to zero for the next launch.
+#include <stdlib.h>
+
 #include "milo_host.h"
 #include "milo_kernels.h"
 
 namespace milo {
 
-constexpr int kDecThreads = 256;
-constexpr int kDecRows = 32;            // output features per workgroup
-constexpr int kDecStageK = 1024;        // k per stage (4 waves x 256)
-constexpr int kDecStageBytes = 16 * kDecStageK * 2;   // X stage for 16 rows
-constexpr int kDecAhead = 2;            // stages of weights in flight beyond the current one
+constexpr int kDecWaves = 8;
+constexpr int kDecThreads = 64 * kDecWaves;
+constexpr int kDecPiece = 16;                               // chunks of 256 k staged at a time
+constexpr int kDecSlotBytes = 16 * 512;                     // one chunk of X: 16 rows x 256 k
+constexpr int kDecLdsBytes = kDecPiece * kDecSlotBytes;     // 128 KB
+constexpr int kDecRankPass = 128;       // ranks a T worker handles per pass (8 MFMA blocks)
 
-// 16-byte slice "chunk c (0..3), step t, k-quad q, row j" of an X stage.
-__device__ __forceinline__ int dec_xs_offset(int c, int t, int q, int j) {
-    return ((c * 8 + t) * 64 + q * 16 + (j ^ t ^ ((c & 1) << 3))) * 16;
+__device__ __forceinline__ void buf_store16_coherent(BufRsrc r, uint32_t off, u32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, off, 0, 17);
+}
+__device__ __forceinline__ void buf_store8_coherent(BufRsrc r, uint32_t off, u32x2 v) {
+    __builtin_amdgcn_raw_buffer_store_b64(v, r, off, 0, 17);
+}
+typedef __attribute__((address_space(3))) void* LdsPtr;
+
+// All vector memory operations issued so far by this wave (loads, stores and buffer-to-LDS copies)
+// have completed; nothing may be moved across.
+__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// One K-slice of T = X V^T, then (last arriver only) the sum over slices.
+__device__ __forceinline__ void decode_t_worker(const DecodeArgs& a, unsigned char* smem) {
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int j16 = lane & 15, q = lane >> 4;
+    const int M = a.M, r = a.w.r;
+    const int64_t K = a.K;
+    const BufRsrc xb = make_rsrc(a.X, (uint64_t)M * (uint64_t)K * 2u);
+    const BufRsrc vb = make_rsrc(a.w.V, (uint64_t)r * (uint64_t)K * 2u);
+    const BufRsrc pb = make_rsrc(a.t_partial, (uint64_t)a.nt * a.rblocks * 64 * 16);
+    const BufRsrc tb = make_rsrc(a.T, (uint64_t)16 * a.ldt * 2u);
+    const int64_t k_lo = (int64_t)blockIdx.x * a.slice;
+    const int64_t k_hi = (k_lo + a.slice < K) ? k_lo + a.slice : K;
+    f32x4* red = reinterpret_cast<f32x4*>(smem);            // [wave][8 blocks][64 lanes] = 128 KB
+
+    for (int jp = 0; jp < r; jp += kDecRankPass) {
+        f32x4 tacc[8];
+#pragma unroll
+        for (int jb = 0; jb < 8; ++jb) tacc[jb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        const int nblk = (r - jp + 15) / 16 < 8 ? (r - jp + 15) / 16 : 8;
+        // wave w takes the 32-wide k-steps w, w+16, ... of the slice
+        for (int64_t k0 = k_lo + 32 * wave; k0 < k_hi; k0 += 32 * kDecWaves) {
+            const int64_t k = k0 + 8 * q;
+            const f16x8 xv = __builtin_bit_cast(
+                f16x8, buf_load16(xb, j16 < M ? (uint32_t)(((int64_t)j16 * K + k) * 2) : kOobOffset));
+            f16x8 vv[8];
+#pragma unroll
+            for (int jb = 0; jb < 8; ++jb) {
+                // rows >= r lie past the end of V and read as zero
+                const int64_t row = jp + 16 * jb + j16;
+                vv[jb] = __builtin_bit_cast(
+                    f16x8, buf_load16(vb, jb < nblk ? (uint32_t)((row * K + k) * 2) : kOobOffset));
+            }
+#pragma unroll
+            for (int jb = 0; jb < 8; ++jb)
+                if (jb < nblk) tacc[jb] = mfma16(vv[jb], xv, tacc[jb]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int jb = 0; jb < 8; ++jb)
+            if (jb < nblk) red[(wave * 8 + jb) * 64 + lane] = tacc[jb];
+        __syncthreads();
+        // partial[slice][rank block][lane] keeps the MFMA D layout:
+        // element v of lane l = rank 16*jb + 4*(l/16) + v, token l%16.
+        const uint32_t pbase = (uint32_t)(((int64_t)blockIdx.x * a.rblocks + jp / 16) * 64 * 16);
+        for (int e = tid; e < nblk * 64; e += kDecThreads) {
+            f32x4 sum = red[e];
+#pragma unroll
+            for (int p = 1; p < kDecWaves; ++p) {
+                const f32x4 v = red[p * 8 * 64 + e];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) sum[x] += v[x];
+            }
+            buf_store16_coherent(pb, pbase + (uint32_t)e * 16u, __builtin_bit_cast(u32x4, sum));
+        }
+    }
+    // all partial stores of this workgroup are complete before it is counted
+    wait_vmem();
+    __syncthreads();
+    int last = 0;
+    if (tid == 0) last = (atomicAdd(a.ctrl + 0, 1u) == (uint32_t)a.nt - 1u) ? 1 : 0;
+    if (!__syncthreads_or(last)) return;
+
+    // Last slice to arrive: add the partials in slice order and write T as fp16 [16 x ldt].
+    // All loads of a batch of entries are issued together, then summed through LDS.
+    const int entries = a.rblocks * 64;
+    const int per_batch = (kDecLdsBytes / 16) / a.nt;        // entries whose nt partials fit in LDS
+    for (int e0 = 0; e0 < entries; e0 += per_batch) {
+        const int ne = (entries - e0) < per_batch ? (entries - e0) : per_batch;
+        __syncthreads();
+        for (int i = tid; i < ne * a.nt; i += kDecThreads) {
+            const int s = i / ne, e = i - s * ne;
+            red[i] = __builtin_bit_cast(
+                f32x4, buf_load16_coherent(pb, (uint32_t)((((int64_t)s * a.rblocks) * 64 + e0 + e) * 16)));
+        }
+        __syncthreads();
+        for (int e = tid; e < ne; e += kDecThreads) {
+            f32x4 sum = red[e];
+            for (int s = 1; s < a.nt; ++s) {
+                const f32x4 v = red[s * ne + e];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) sum[x] += v[x];
+            }
+            const int jb = (e0 + e) >> 6, l = (e0 + e) & 63;
+            f16x4 o;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) o[x] = (f16)sum[x];
+            buf_store8_coherent(tb, (uint32_t)(((l & 15) * a.ldt + 16 * jb + 4 * (l >> 4)) * 2),
+                                __builtin_bit_cast(u32x2, o));
+        }
+    }
+    wait_vmem();
+    __syncthreads();
+    if (tid == 0) __hip_atomic_store(a.ctrl + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-struct DecTask {
-    RawUnit u[2];
-};
-
+template <int R>
 __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeArgs a) {
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * kDecStageBytes];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int j16 = lane & 15, q = lane >> 4;
     const int M = a.M;
     const int64_t N = a.N, K = a.K;
     const int G = (int)(K / kGroup);
-    const int nstages = (int)((K + kDecStageK - 1) / kDecStageK);
-    const int64_t n0 = (int64_t)blockIdx.x * kDecRows;
+    const int nchunks = (G + 3) / 4;
+    const int npieces = (nchunks + kDecPiece - 1) / kDecPiece;
+    const int r = a.w.r;
+    const int nworkers = r > 0 ? a.nt : 0;
+    constexpr int ROWS = 16 * R;                // output features per workgroup
+    constexpr int CPW = kDecPiece / kDecWaves;  // chunks of a piece per wave
 
-    const W3View view = make_view(a.w.q3, a.w.scales, a.w.zeros, N, K);
-    int64_t ubase[2];
-    bool nvalid[2];
+    if ((int)blockIdx.x < nworkers) {
+        decode_t_worker(a, smem);
+    } else {
+        const W3Buf wb = make_w3buf(a.w.q3, a.w.scales, a.w.zeros, N, K);
+        const BufRsrc xb = make_rsrc(a.X, (uint64_t)M * (uint64_t)K * 2u);
+        // Staging: copy i of a chunk moves rows 2i, 2i+1: lane l -> row 2i + l/32, slot position
+        // p = l%32, which receives segment p ^ row of the row's 32 segments of 8 columns.
+        const int crow = lane >> 5, cp = lane & 31;
+        bool t_seen = false;        // this workgroup has already waited for T
+
+        for (int64_t blk = (int64_t)blockIdx.x - nworkers; blk * ROWS < N;
+             blk += (int64_t)gridDim.x - nworkers) {
+            const int64_t n0 = blk * ROWS;
+            uint32_t ubase[R];
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int64_t n = n0 + 16 * b + j16;
-        nvalid[b] = n < N;
-        ubase[b] = unit_index(nvalid[b] ? n : 0, 0, G);
-    }
-
-    auto load_w = [&](int stage, DecTask& t) {
-        const int g = (stage * 4 + wave) * 4 + q;
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            if (nvalid[b] && g < G)
-                t.u[b] = load_unit<true>(view, ubase[b] + (int64_t)g * 16);
-            else
-                t.u[b] = zero_unit();
-        }
-    };
-
-    // X staging: slice id = tid + 256*it over (row, 128 slices of 8 columns); only rows < M.
-    constexpr int XIT = 16 * 128 / kDecThreads;   // 8 slices per thread at M = 16
-    auto load_x = [&](int stage, u32x4 (&xr)[XIT]) {
-#pragma unroll
-        for (int it = 0; it < XIT; ++it) {
-            const int id = tid + kDecThreads * it;
-            const int row = id >> 7, seg = id & 127;
-            const int64_t k = (int64_t)stage * kDecStageK + seg * 8;
-            if (row < M && k < K)
-                xr[it] = *reinterpret_cast<const u32x4*>(a.X + (int64_t)row * K + k);
-            else
-                xr[it] = u32x4{0u, 0u, 0u, 0u};
-        }
-    };
-    auto store_x = [&](int buf, const u32x4 (&xr)[XIT]) {
-#pragma unroll
-        for (int it = 0; it < XIT; ++it) {
-            const int id = tid + kDecThreads * it;
-            const int row = id >> 7, seg = id & 127;
-            if (row < M)
-                *reinterpret_cast<u32x4*>(smem + buf * kDecStageBytes +
-                                          dec_xs_offset(seg >> 5, seg & 7, (seg >> 3) & 3, row)) = xr[it];
-        }
-    };
-
-    f32x4 acc[2];
-    acc[0] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    acc[1] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-
-    // Weight ring: stages s .. s+kDecAhead are in registers (slot = stage % ring size).
-    DecTask ring[kDecAhead + 1];
-#pragma unroll
-    for (int i = 0; i <= kDecAhead; ++i) {
-        if (i < nstages)
-            load_w(i, ring[i]);
-        else
-            ring[i].u[0] = ring[i].u[1] = zero_unit();
-    }
-    {
-        u32x4 xr[XIT];
-        load_x(0, xr);
-        store_x(0, xr);
-    }
-    __syncthreads();
-
-    // The stage loop is unrolled by the ring depth so that ring slots are compile-time names
-    // (no register shuffling): stage s lives in slot s % (kDecAhead + 1).
-    for (int s0 = 0; s0 < nstages; s0 += kDecAhead + 1) {
-#pragma unroll
-        for (int slot = 0; slot <= kDecAhead; ++slot) {
-            const int s = s0 + slot;
-            if (s >= nstages) break;
-            const int cur = s & 1;
-            const bool more = (s + 1) < nstages;
-            u32x4 xr[XIT];
-            if (more) load_x(s + 1, xr);
-
-            uint32_t wv[2][32];
-            dequant_unit(ring[slot].u[0], wv[0]);
-            dequant_unit(ring[slot].u[1], wv[1]);
-            if (s + 1 + kDecAhead < nstages) load_w(s + 1 + kDecAhead, ring[slot]);
-
-            const unsigned char* xs = smem + cur * kDecStageBytes;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                f16x8 b = zero_f16x8();
-                if (j16 < M)
-                    b = __builtin_bit_cast(
-                        f16x8,
-                        *reinterpret_cast<const u32x4*>(xs + dec_xs_offset(wave, t, q, j16)));
-                acc[0] = mfma16(unit_frag(wv[0], t), b, acc[0]);
-                acc[1] = mfma16(unit_frag(wv[1], t), b, acc[1]);
+            for (int b = 0; b < R; ++b) {
+                const int64_t n = n0 + 16 * b + j16;
+                ubase[b] = (n < N) ? (uint32_t)unit_index(n, 0, G) : kOobUnit;
             }
-            if (more) store_x(cur ^ 1, xr);
+            f32x4 acc[R];
+#pragma unroll
+            for (int b = 0; b < R; ++b) acc[b] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+            for (int p = 0; p < npieces; ++p) {
+                if (p > 0) __syncthreads();         // the previous piece has been read by everyone
+                // This wave's chunks of the piece (wave, wave + 8): their activations go straight from
+                // L2 into LDS (buffer-to-LDS copies, no registers), issued before the weight loads so
+                // that they complete first ...
+#pragma unroll
+                for (int ci = 0; ci < CPW; ++ci) {
+                    const int cw = wave + kDecWaves * ci;           // chunk within the piece
+                    const int64_t kc = ((int64_t)p * kDecPiece + cw) * 256;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int row = 2 * i + crow;
+                        const int seg = cp ^ row;
+                        const bool in = row < M && kc + seg * 8 < K;
+                        const uint32_t off = in ? (uint32_t)(((int64_t)row * K + kc + seg * 8) * 2) : kOobOffset;
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                            xb, (LdsPtr)(smem + cw * kDecSlotBytes + i * 1024), 16, off, 0, 0, 0);
+                    }
+                }
+                asm volatile("" ::: "memory");
+                // ... then their weights: lane quad q takes group 4c + q of chunk c
+                RawUnit u[CPW][R];
+#pragma unroll
+                for (int ci = 0; ci < CPW; ++ci) {
+                    const int g = 4 * (p * kDecPiece + wave + kDecWaves * ci) + q;
+#pragma unroll
+                    for (int b = 0; b < R; ++b)
+                        u[ci][b] = load_unit_buf(wb, (g < G && ubase[b] != kOobUnit) ? ubase[b] + (uint32_t)g * 16u
+                                                                                      : kOobUnit);
+                }
+                // Vector memory operations complete in order: once at most the CPW*R*4 weight loads
+                // are outstanding, the copies issued before them have landed in LDS.  (This count
+                // relies on the compiler adding no memory operation of its own in between; the build
+                // script checks the generated code for that.)
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CPW * R * 4) : "memory");
+                __syncthreads();
+#pragma unroll
+                for (int ci = 0; ci < CPW; ++ci) {
+                    const unsigned char* slot = smem + (wave + kDecWaves * ci) * kDecSlotBytes;
+                    f16x8 bfrag[8];
+#pragma unroll
+                    for (int t = 0; t < 8; ++t)
+                        bfrag[t] = __builtin_bit_cast(
+                            f16x8,
+                            *reinterpret_cast<const u32x4*>(slot + j16 * 512 + (((8 * q + t) ^ j16) << 4)));
+#pragma unroll
+                    for (int b = 0; b < R; ++b)
+                        dequant_unit_steps(u[ci][b], [&](int t, f16x8 frag) {
+                            acc[b] = mfma16(frag, bfrag[t], acc[b]);
+                        });
+                }
+            }
+
+            // ------------------------------------------------------------ reduce + low rank + store
+            __syncthreads();                                       // everyone is done with the slots
+            f32x4* red = reinterpret_cast<f32x4*>(smem);          // [wave][block][lane]
+#pragma unroll
+            for (int b = 0; b < R; ++b) red[(wave * R + b) * 64 + lane] = acc[b];
+            if (r > 0 && !t_seen) {
+                if (tid == 0)
+                    while (__hip_atomic_load(a.ctrl + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u)
+                        __builtin_amdgcn_s_sleep(1);
+                t_seen = true;
+            }
             __syncthreads();
+            if (wave < R) {
+                const int b = wave;
+                f32x4 sum = red[b * 64 + lane];
+#pragma unroll
+                for (int pw = 1; pw < kDecWaves; ++pw) {
+                    const f32x4 v = red[(pw * R + b) * 64 + lane];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) sum[e] += v[e];
+                }
+                const int64_t nb = n0 + 16 * b;
+                const int64_t nrow = nb + j16;
+                if (r > 0) {
+                    const BufRsrc ub = make_rsrc(a.w.U, (uint64_t)N * (uint64_t)r * 2u);
+                    const BufRsrc tb = make_rsrc(a.T, (uint64_t)16 * a.ldt * 2u);
+                    const bool fast = (r & 7) == 0;
+                    for (int ks = 0; ks < r; ks += 32) {
+                        const int k0 = ks + 8 * q;
+                        f16x8 av;
+                        if (fast) {
+                            av = __builtin_bit_cast(
+                                f16x8, buf_load16(ub, (nrow < N && k0 < r) ? (uint32_t)((nrow * r + k0) * 2)
+                                                                           : kOobOffset));
+                        } else {
+                            av = zero_f16x8();
+                            if (nrow < N) av = load_row8(a.w.U + nrow * r, k0, r, false);
+                        }
+                        // T was written by another workgroup during this launch: read it coherently
+                        const f16x8 bv = __builtin_bit_cast(
+                            f16x8,
+                            buf_load16_coherent(tb, k0 < a.ldt ? (uint32_t)((j16 * a.ldt + k0) * 2) : kOobOffset));
+                        sum = mfma16(av, bv, sum);
+                    }
+                }
+                // D[v]: feature nb + 4q + v, token j16
+                const int64_t n = nb + 4 * q;
+                if (j16 < M && n < N) {
+                    f16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = (f16)sum[e];
+                    *reinterpret_cast<f16x4*>(a.Y + (int64_t)j16 * N + n) = o;
+                }
+            }
+            __syncthreads();        // smem is reused by the next block of this workgroup
         }
     }
 
-    // Cross-wave reduction (fixed order) + low-rank term + store: wave b finishes row block b.
-    f32x4* red = reinterpret_cast<f32x4*>(smem);          // [wave][block][lane]
-    red[(wave * 2 + 0) * 64 + lane] = acc[0];
-    red[(wave * 2 + 1) * 64 + lane] = acc[1];
-    __syncthreads();
-    if (wave < 2) {
-        const int b = wave;
-        f32x4 sum = red[(0 * 2 + b) * 64 + lane];
-#pragma unroll
-        for (int p = 1; p < 4; ++p) {
-            const f32x4 v = red[(p * 2 + b) * 64 + lane];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) sum[e] += v[e];
-        }
-        const int r = a.w.r;
-        if (r > 0) {
-            const bool ualigned = (r & 7) == 0;
-            const f16* urow = a.w.U + (nvalid[b] ? (n0 + 16 * b + j16) : 0) * (int64_t)r;
-            for (int ks = 0; ks < r; ks += 32) {
-                const int k0 = ks + 8 * q;
-                f16x8 av = zero_f16x8(), bv = zero_f16x8();
-                if (nvalid[b] && k0 < r) av = load_row8(urow, k0, r, ualigned);
-                if (j16 < M && k0 < a.ldt) bv = load_f16x8(a.T + (int64_t)j16 * a.ldt + k0);
-                sum = mfma16(av, bv, sum);
+    // Leave: the last workgroup restores the control words for the next launch.  Every streaming
+    // workgroup has read T before it gets here, and every worker has written its share.
+    if (r > 0) {
+        __syncthreads();
+        if (tid == 0) {
+            const uint32_t old = atomicAdd(a.ctrl + 2, 1u);
+            if (old == gridDim.x - 1u) {
+                __hip_atomic_store(a.ctrl + 0, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.ctrl + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.ctrl + 2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-        }
-        // D[v]: feature n0 + 16b + 4q + v, token j16
-        const int64_t n = n0 + 16 * b + 4 * q;
-        if (j16 < M && n < N) {
-            f16x4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (f16)sum[e];
-            *reinterpret_cast<f16x4*>(a.Y + (int64_t)j16 * N + n) = o;
         }
     }
 }
 
-int launch_decode(const DecodeArgs& a, hipStream_t stream) {
-    const int64_t blocks = (a.N + kDecRows - 1) / kDecRows;
-    if (blocks > 0x7fffffff) return MILO_ERR_SHAPE;
-    w3lr_decode_kernel<<<dim3((unsigned)blocks), dim3(kDecThreads), 0, stream>>>(a);
+// Workgroups the device keeps resident at once (one 512-thread, 128-KB-LDS workgroup per CU),
+// cached per device; also raises the kernels' dynamic LDS limit once.
+typedef void (*DecodeKernel)(const DecodeArgs);
+static DecodeKernel decode_variant(int R) {
+    if (R == 4) return w3lr_decode_kernel<4>;
+    if (R == 2) return w3lr_decode_kernel<2>;
+    return w3lr_decode_kernel<1>;
+}
+static int decode_capacity() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+        for (int R = 1; R <= 4; R *= 2)
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_variant(R)),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kDecLdsBytes) != hipSuccess)
+                return 0;
+        cached[dev] = cus;
+    }
+    return cached[dev];
+}
+
+size_t decode_workspace_bytes(int r) {
+    if (r <= 0) return 256;
+    const size_t rblocks = ((size_t)r + 15) / 16;
+    // control words | T fp16 [16 x ldt] | partials [kDecMaxSlices][rblocks][64] f32x4
+    return 256 + align_up(16 * rblocks * 16 * 2, 256) + (size_t)kDecMaxSlices * rblocks * 64 * 16;
+}
+
+int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream) {
+    const int cap = decode_capacity();
+    if (cap <= 0) return MILO_ERR_HIP;
+    const int r = a.w.r;
+    a.rblocks = (r + 15) / 16;
+    a.ldt = (int64_t)a.rblocks * 16;
+    char* ws = reinterpret_cast<char*>(workspace);
+    a.ctrl = reinterpret_cast<uint32_t*>(ws);
+    a.T = reinterpret_cast<f16*>(ws + 256);
+    a.t_partial = reinterpret_cast<f32x4*>(ws + 256 + align_up((size_t)16 * a.rblocks * 16 * 2, 256));
+    // K-slices of T: about 512 columns each (one 32-wide step per wave of a worker), at most
+    // kDecMaxSlices and never more than a quarter of the resident workgroups
+    int nt = (int)((a.K + 511) / 512);
+    if (nt > kDecMaxSlices) nt = kDecMaxSlices;
+    if (nt > cap / 4) nt = cap / 4 > 0 ? cap / 4 : 1;
+    int64_t slice = (a.K + nt - 1) / nt;
+    slice = (slice + 63) / 64 * 64;
+    nt = (int)((a.K + slice - 1) / slice);
+    a.nt = nt;
+    a.slice = (int)slice;
+    const int workers = r > 0 ? nt : 0;
+    if (cap <= workers) return MILO_ERR_HIP;
+    // Rows per workgroup (16*R): as many as still leave about one workgroup per CU, because every
+    // workgroup stages all of X once.
+    int R = 4;
+    const int64_t want = (int64_t)(cap - workers) * 3 / 4;
+    while (R > 1 && (a.N + 16 * R - 1) / (16 * R) < want) R >>= 1;
+    if (const char* e = getenv("MILO_DEC_R")) R = atoi(e);      // tuning override
+    const int rows = 16 * R;
+    const int64_t blocks = (a.N + rows - 1) / rows;
+    const int grid = (int)(blocks < cap - workers ? blocks : cap - workers) + workers;
+    decode_variant(R)<<<dim3((unsigned)grid), dim3(kDecThreads), kDecLdsBytes, stream>>>(a);
     return launch_status();
 }
 

@@ -169,22 +169,17 @@ __global__ __launch_bounds__(kTiledThreads) void w3lr_tiled_kernel(const TiledAr
             load_x(c + 1, xr);
             load_w(c + 1, rawn);
         }
-        uint32_t wv[2][32];
-        dequant_unit(raw[0], wv[0]);
-        dequant_unit(raw[1], wv[1]);
         const unsigned char* xs = smem + cur * STAGE;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const f16x8 a0 = unit_frag(wv[0], t);
-            const f16x8 a1 = unit_frag(wv[1], t);
+        for (int s = 0; s < 2; ++s)
+            dequant_unit_steps(raw[s], [&](int t, f16x8 frag) {
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                const f16x8 b = __builtin_bit_cast(
-                    f16x8, *reinterpret_cast<const u32x4*>(xs + xs_offset(mb, t, h, i32)));
-                acc[0][mb] = mfma32(a0, b, acc[0][mb]);
-                acc[1][mb] = mfma32(a1, b, acc[1][mb]);
-            }
-        }
+                for (int mb = 0; mb < MB; ++mb) {
+                    const f16x8 b = __builtin_bit_cast(
+                        f16x8, *reinterpret_cast<const u32x4*>(xs + xs_offset(mb, t, h, i32)));
+                    acc[s][mb] = mfma32(frag, b, acc[s][mb]);
+                }
+            });
         if (more) {
             store_x(cur ^ 1, xr);
             raw[0] = rawn[0];

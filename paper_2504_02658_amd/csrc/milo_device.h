@@ -83,6 +83,58 @@ __device__ __forceinline__ RawUnit load_unit(const W3View& w, int64_t u) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Raw buffer access.  A buffer descriptor carries the byte size of the array, and a load whose
+// offset falls outside returns zero without any branch: kernels mark a lane as "no data" by
+// giving it an out-of-range offset instead of diverging.  Offsets are 32-bit, so every array
+// addressed this way must be smaller than 4 GiB (checked on the host).
+typedef __amdgpu_buffer_rsrc_t BufRsrc;
+constexpr uint32_t kOobOffset = 0xFFFFFFF0u;
+
+__device__ __forceinline__ BufRsrc make_rsrc(const void* p, uint64_t bytes) {
+    const uint32_t n = bytes > 0xFFFFFFF0ull ? 0xFFFFFFF0u : (uint32_t)bytes;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, n, 0x00020000);
+}
+__device__ __forceinline__ u32x4 buf_load16(BufRsrc r, uint32_t off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+}
+// Device-coherent variant (sc0 sc1): for data another workgroup wrote during this launch.
+__device__ __forceinline__ u32x4 buf_load16_coherent(BufRsrc r, uint32_t off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 17);
+}
+__device__ __forceinline__ u32x2 buf_load8(BufRsrc r, uint32_t off) {
+    return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+}
+__device__ __forceinline__ f16 buf_load2(BufRsrc r, uint32_t off) {
+    const unsigned short v = __builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
+    return __builtin_bit_cast(f16, v);
+}
+
+// The four arrays of a packed weight as buffers.
+struct W3Buf {
+    BufRsrc a, b, s, z;
+};
+__device__ __forceinline__ W3Buf make_w3buf(const void* q3, const void* scales, const void* zeros,
+                                            int64_t N, int64_t K) {
+    const uint64_t units = (uint64_t)N * (uint64_t)(K / kGroup);
+    W3Buf w;
+    w.a = make_rsrc(q3, units * 16);
+    w.b = make_rsrc(reinterpret_cast<const char*>(q3) + units * 16, units * 8);
+    w.s = make_rsrc(scales, units * 2);
+    w.z = make_rsrc(zeros, units * 2);
+    return w;
+}
+// Unit u, or an all-zero unit (which dequantizes to zeros) when u is kOobUnit.
+constexpr uint32_t kOobUnit = 0x0FFFFFFFu;
+__device__ __forceinline__ RawUnit load_unit_buf(const W3Buf& w, uint32_t u) {
+    RawUnit r;
+    r.a = buf_load16(w.a, u * 16u);
+    r.b = buf_load8(w.b, u * 8u);
+    r.s = buf_load2(w.s, u * 2u);
+    r.z = buf_load2(w.z, u * 2u);
+    return r;
+}
+
+// ---------------------------------------------------------------------------------------------
 // (a & mask) | orv in one VALU op.  The mask sits in an SGPR: on gfx9-family encodings a VOP3
 // instruction cannot carry a 32-bit literal, and without this the compiler emits and + or.
 __device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t orv) {
@@ -91,53 +143,117 @@ __device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t o
     return r;
 }
 
-// Two fp16 values h (low, high half of a register) -> two fp16 values S*h + C, evaluated as an
-// fp32 fused multiply-add with one rounding to fp16 (compiles to v_fma_mixlo/mixhi_f16).
-__device__ __forceinline__ uint32_t scale_pair(uint32_t h, float S, float C) {
-    f16x2 v = __builtin_bit_cast(f16x2, h);
-    f16x2 r;
-    r.x = (f16)__builtin_fmaf((float)v.x, S, C);
-    r.y = (f16)__builtin_fmaf((float)v.y, S, C);
-    return __builtin_bit_cast(uint32_t, r);
-}
-
 // 3-bit -> fp16 conversion of one unit (Section 3.3 of the paper, "MiLo Dequant", reworked for
-// this layout): a 3-bit field sitting at mantissa bit b of an fp16 whose exponent field says
-// 2^10 reads as 1024 + 2^b * e, so OR-ing 0x6400 over the masked field converts the integer
-// without any int->float instruction, two codes per 32-bit register.  Fields at b = 0, 3, 6
-// are usable without a shift.  The bias and the field's 2^b factor are then removed together
-// with the zero-point and the scale by one fp32 fma per element:
-//      w = (s / 2^b) * h - (1024 / 2^b + z) * s  =  s * (e - z)
-// which is exact up to the single final rounding to fp16 for any real-valued z.
+// this layout and for packed fp16 arithmetic).  A 3-bit field e sitting at mantissa bit b of an
+// fp16 whose exponent says 2^(10-b) reads as 2^(10-b) + e, so OR-ing the right exponent pattern
+// over the masked field converts the integer without any int->float instruction, two codes per
+// 32-bit register: fields at b = 0, 3, 6 need no shift (patterns 0x6400 = 1024, 0x5800 = 128,
+// 0x4C00 = 16).  With zr = the zero-point rounded to an integer (clamped to -8..15), the value
+//      w = s * ((h - (2^(10-b) + zr)) + (zr - z))  =  s * (e - z)
+// is formed by one packed subtraction, which is exact (small integers), and one packed fma with
+// the per-unit constants s and c = (zr - z) * s; for integer zero-points c is 0 and the only
+// rounding is the final one, for real-valued ones c adds an error below 2^-12 s.
 // Output: w[P] = packed fp16 (W_dq[2P], W_dq[2P+1]) for the unit's 32 code pairs.
-__device__ __forceinline__ void dequant_unit(const RawUnit& ru, uint32_t (&w)[32]) {
+__device__ __forceinline__ uint32_t pack2(f16 v) {
+    f16x2 p = {v, v};
+    return __builtin_bit_cast(uint32_t, p);
+}
+__device__ __forceinline__ f16x8 unit_frag(const uint32_t (&w)[32], int t);
+
+// The conversion is written in groups of five independent operations of one kind (five field
+// extractions, five subtractions, five fmas) pinned with scheduling barriers: a dependent packed
+// op can only issue about three slots after its producer, and left alone the compiler serialises
+// extract -> subtract -> fma per pair through one temporary, which halves the VALU rate.
+// `on_step(t, frag)` is called as soon as the eight codes 8t .. 8t+7 (the A operand of MFMA step
+// t, t = 0..7 in order) are ready, so the caller's MFMAs interleave with the rest of the unit.
+struct UnitConsts {
+    uint32_t A0, A3, A6, S2, C2;
+};
+__device__ __forceinline__ UnitConsts unit_consts(const RawUnit& ru) {
     const float s = (float)ru.s;
     const float z = (float)ru.z;
-    const float S1 = s, S8 = s * 0.125f, S64 = s * 0.015625f;
-    const float C1 = -(1024.0f + z) * s;
-    const float C8 = -(128.0f + z) * s;
-    const float C64 = -(16.0f + z) * s;
-    const uint32_t kBias = 0x64006400u;
+    const float zr = __builtin_fminf(__builtin_fmaxf(__builtin_rintf(z), -8.0f), 15.0f);
+    UnitConsts c;
+    c.A0 = pack2((f16)(1024.0f + zr));
+    c.A3 = pack2((f16)(128.0f + zr));
+    c.A6 = pack2((f16)(16.0f + zr));
+    c.S2 = pack2(ru.s);
+    c.C2 = pack2((f16)((zr - z) * s));
+    return c;
+}
+__device__ __forceinline__ uint32_t pk_sub(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(f16x2, a) - __builtin_bit_cast(f16x2, b));
+}
+__device__ __forceinline__ uint32_t pk_fma(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_bit_cast(
+        uint32_t, __builtin_elementwise_fma(__builtin_bit_cast(f16x2, a), __builtin_bit_cast(f16x2, b),
+                                            __builtin_bit_cast(f16x2, c)));
+}
+
+template <typename OnStep>
+__device__ __forceinline__ void dequant_unit_steps(const RawUnit& ru, OnStep&& on_step) {
+    const UnitConsts c = unit_consts(ru);
+    const uint32_t B0 = 0x64006400u, B3 = 0x58005800u, B6 = 0x4C004C00u;
     const uint32_t d[6] = {ru.a.x, ru.a.y, ru.a.z, ru.a.w, ru.b.x, ru.b.y};
-    uint32_t sh[6];
+    uint32_t w[32];
+    int next = 0;
 #pragma unroll
     for (int j = 0; j < 6; ++j) {
-        sh[j] = d[j] >> 9;
-        w[5 * j + 0] = scale_pair(and_or(d[j], 0x00070007u, kBias), S1, C1);
-        w[5 * j + 1] = scale_pair(and_or(d[j], 0x00380038u, kBias), S8, C8);
-        w[5 * j + 2] = scale_pair(and_or(d[j], 0x01C001C0u, kBias), S64, C64);
-        w[5 * j + 3] = scale_pair(and_or(sh[j], 0x00070007u, kBias), S1, C1);
-        w[5 * j + 4] = scale_pair(and_or(sh[j], 0x00380038u, kBias), S8, C8);
+        const uint32_t sh = d[j] >> 9;
+        uint32_t h[5];
+        h[0] = and_or(d[j], 0x00070007u, B0);
+        h[1] = and_or(d[j], 0x00380038u, B3);
+        h[2] = and_or(d[j], 0x01C001C0u, B6);
+        h[3] = and_or(sh, 0x00070007u, B0);
+        h[4] = and_or(sh, 0x00380038u, B3);
+        __builtin_amdgcn_sched_barrier(0);
+        h[0] = pk_sub(h[0], c.A0);
+        h[1] = pk_sub(h[1], c.A3);
+        h[2] = pk_sub(h[2], c.A6);
+        h[3] = pk_sub(h[3], c.A0);
+        h[4] = pk_sub(h[4], c.A3);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 5; ++i) w[5 * j + i] = pk_fma(h[i], c.S2, c.C2);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 7; ++t) {
+            if (t == next && 4 * t + 3 <= 5 * j + 4) {
+                on_step(t, unit_frag(w, t));
+                ++next;
+            }
+        }
     }
     // Pairs 30 and 31 are spread over the spare bits 15 / 31 of three words each; shifting the
-    // words by 9, 8 and 7 lines the three bits up at mantissa bits 6, 7, 8 (a 2^6 field).
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        uint32_t t = and_or(sh[3 * p], 0x00400040u, kBias);
-        t = and_or(d[3 * p + 1] >> 8, 0x00800080u, t);
-        t = and_or(d[3 * p + 2] >> 7, 0x01000100u, t);
-        w[30 + p] = scale_pair(t, S64, C64);
-    }
+    // words by 9, 8 and 7 lines the three bits up at mantissa bits 6, 7, 8.
+    uint32_t t0 = and_or(d[0] >> 9, 0x00400040u, B6);
+    uint32_t t1 = and_or(d[3] >> 9, 0x00400040u, B6);
+    const uint32_t x0 = d[1] >> 8, x1 = d[4] >> 8, y0 = d[2] >> 7, y1 = d[5] >> 7;
+    __builtin_amdgcn_sched_barrier(0);
+    t0 = and_or(x0, 0x00800080u, t0);
+    t1 = and_or(x1, 0x00800080u, t1);
+    __builtin_amdgcn_sched_barrier(0);
+    t0 = and_or(y0, 0x01000100u, t0);
+    t1 = and_or(y1, 0x01000100u, t1);
+    __builtin_amdgcn_sched_barrier(0);
+    t0 = pk_sub(t0, c.A6);
+    t1 = pk_sub(t1, c.A6);
+    __builtin_amdgcn_sched_barrier(0);
+    w[30] = pk_fma(t0, c.S2, c.C2);
+    w[31] = pk_fma(t1, c.S2, c.C2);
+    __builtin_amdgcn_sched_barrier(0);
+    on_step(7, unit_frag(w, 7));
+}
+
+// All 32 pairs of a unit at once (for the dense dequantization kernel).
+__device__ __forceinline__ void dequant_unit(const RawUnit& ru, uint32_t (&w)[32]) {
+    dequant_unit_steps(ru, [&](int t, f16x8 frag) {
+        const u32x4 v = __builtin_bit_cast(u32x4, frag);
+        w[4 * t + 0] = v.x;
+        w[4 * t + 1] = v.y;
+        w[4 * t + 2] = v.z;
+        w[4 * t + 3] = v.w;
+    });
 }
 
 // The A operand of MFMA step t (t = 0..7) of a dequantized unit: codes 8t .. 8t+7.

@@ -71,15 +71,24 @@ enum { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_SCALE_SCATTER = 2 };
 int launch_t_kernel(const TArgs& a, int nw, int m_tiles, hipStream_t stream);
 int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipStream_t stream);
 
+constexpr int kDecMaxSlices = 32;   // K-slices of T = X V^T in the decode kernel
+
 struct DecodeArgs {
     const f16* X;       // [M x K], M <= 16
     int M;
     int64_t N, K;
     WeightDev w;
-    const f16* T;       // [M x ldt] fp16 (X V^T), zero beyond the rank
-    int64_t ldt;
     f16* Y;             // [M x N]
+    // filled in by launch_decode from the workspace
+    uint32_t* ctrl;     // [0] T slices arrived, [1] T ready, [2] workgroups done; zero between launches
+    f16* T;             // [16 x ldt] fp16 (X V^T), zero beyond the rank
+    int64_t ldt;
+    f32x4* t_partial;   // [nt][rblocks][64] fp32 partials of T in MFMA D layout
+    int rblocks;        // ceil(r / 16)
+    int nt;             // number of K-slices / T workers
+    int slice;          // columns per slice (multiple of 64)
 };
-int launch_decode(const DecodeArgs& a, hipStream_t stream);
+size_t decode_workspace_bytes(int r);
+int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream);
 
 }  // namespace milo

@@ -131,7 +131,7 @@ def test_gpu_argument_errors():
         api.pack_w3(W, group_size=128)
     assert ei.value.status == 3
     with pytest.raises(api.MiloError) as ei:
-        api.w3lr_gemm(X, pw, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+        api.w3lr_gemm(X, pw, workspace=torch.zeros(16, dtype=torch.uint8, device="cuda"))
     assert ei.value.status == 5
     with pytest.raises(ValueError):
         api.w3lr_gemm(torch.zeros((4, 64), dtype=torch.float16, device="cuda"), pw)
