@@ -1,4 +1,6 @@
 // Status text, version and the single-linear entry point milo_w3lr_gemm.
+#include <stdlib.h>
+
 #include "milo_host.h"
 #include "milo_kernels.h"
 
@@ -22,15 +24,20 @@ extern "C" const char* milo_status_string(int status) {
 extern "C" int milo_version(void) { return 100; }
 
 namespace milo {
-__global__ void clear_control_kernel(uint32_t* p) { p[threadIdx.x] = 0u; }
+__global__ void clear_kernel(u32x4* p, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = u32x4{0u, 0u, 0u, 0u};
+}
 }  // namespace milo
 
 extern "C" int milo_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
     if (!workspace) return MILO_ERR_NULL;
     if (workspace_bytes < 256) return MILO_ERR_WORKSPACE;
     if (!aligned16(workspace)) return MILO_ERR_ALIGN;
-    clear_control_kernel<<<dim3(1), dim3(64), 0, (hipStream_t)stream>>>(
-        reinterpret_cast<uint32_t*>(workspace));
+    const size_t n16 = workspace_bytes / 16;
+    const size_t blocks = (n16 + 255) / 256;
+    clear_kernel<<<dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, (hipStream_t)stream>>>(
+        reinterpret_cast<u32x4*>(workspace), n16);
     return launch_status();
 }
 
@@ -43,8 +50,9 @@ static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
 extern "C" size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int r) {
     if (!gemm_shape_ok(M, N, K) || r < 0) return 0;
     if (M <= 16) return decode_workspace_bytes(r);
-    // T = X V^T as fp16 [M x pad16(r)] behind a 256-byte control block
-    return 256 + align_up((size_t)M * (size_t)rank_pad(r) * 2 + 256, 256);
+    // control words | two flag words per 32-row tile | T = X V^T as fp16 [M x pad16(r)]
+    return 256 + align_up((size_t)((M + 31) / 32) * 8, 256) +
+           align_up((size_t)M * (size_t)rank_pad(r) * 2 + 256, 256);
 }
 
 extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t K, const void* q3,
@@ -81,30 +89,32 @@ extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t 
         da.w = w; da.Y = reinterpret_cast<f16*>(Y);
         return launch_decode(da, workspace, stream);
     }
-    f16* T = reinterpret_cast<f16*>(reinterpret_cast<char*>(workspace) + 256);
+    char* ws = reinterpret_cast<char*>(workspace);
+    uint32_t* ctrl = reinterpret_cast<uint32_t*>(ws);
+    uint32_t* flags = reinterpret_cast<uint32_t*>(ws + 256);
+    f16* T = reinterpret_cast<f16*>(ws + 256 + align_up((size_t)((M + 31) / 32) * 8, 256));
     const int64_t ldt = rank_pad(r);
 
-    const int mb = M <= 32 ? 1 : (M <= 64 ? 2 : 4);
+    int mb = M <= 32 ? 1 : (M <= 64 ? 2 : 4);
+    if (const char* e = getenv("MILO_GEMM_MB")) mb = atoi(e);           // tuning override
     const int bm = 32 * mb;
     const int64_t m_tiles = (M + bm - 1) / bm;
     if (m_tiles > 65535) return MILO_ERR_SHAPE;
+    if ((uint64_t)M * K * 2 >= 0x80000000ull || ((uint64_t)r + 256) * K * 2 >= 0xFFFFFFF0ull ||
+        (uint64_t)M * ldt * 2 >= 0xFFFFFFF0ull)
+        return MILO_ERR_SHAPE;                                          // 32-bit offsets in the kernel
 
     RowSpace rs;
     rs.tiles = nullptr; rs.n_tiles = nullptr; rs.experts = nullptr;
     rs.which[0] = rs.which[1] = 0;
     rs.w[0] = rs.w[1] = w;
-    rs.M = M; rs.x_rows = nullptr; rs.x_row_div = 1;
+    rs.M = M; rs.x_rows = nullptr;
 
-    if (r > 0) {
-        TArgs ta;
-        ta.rs = rs; ta.X = reinterpret_cast<const f16*>(X); ta.ldx = K; ta.K = K;
-        ta.T[0] = ta.T[1] = T; ta.ldt = ldt; ta.bm = bm;
-        const int st = launch_t_kernel(ta, 1, (int)m_tiles, stream);
-        if (st != MILO_OK) return st;
-    }
     TiledArgs ga;
-    ga.rs = rs; ga.X = reinterpret_cast<const f16*>(X); ga.ldx = K; ga.N = N; ga.K = K;
-    ga.T[0] = ga.T[1] = T; ga.ldt = ldt;
+    ga.rs = rs; ga.X = reinterpret_cast<const f16*>(X); ga.ldx = K; ga.x_bytes = (uint64_t)M * K * 2;
+    ga.N = N; ga.K = K;
+    ga.T[0] = ga.T[1] = T; ga.ldt = ldt; ga.t_bytes = (uint64_t)M * ldt * 2;
+    ga.v_tiles = r > 0 ? 1 : 0; ga.flags = flags; ga.flags_status = ctrl + 3;
     ga.out = Y; ga.ldo = N; ga.out_rows = nullptr; ga.out_scale = nullptr;
     return launch_tiled(ga, 1, mb, EPI_STORE, (int)m_tiles, stream);
 }

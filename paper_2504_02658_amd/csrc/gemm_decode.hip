@@ -15,8 +15,8 @@
 // each, no registers involved); the
 // 16-byte segment that sits at slot position p of row j is segment p ^ j of the row, which makes
 // the later per-lane ds_read_b128 of the B fragments conflict free although the 16 lanes of a
-// quad read 16 rows.  One barrier per piece; the waves' partial sums are added in a fixed order
-// at the very end.
+// quad read 16 rows.  A slot is written and read by one wave only, so the main loop takes no
+// barrier; the waves' partial sums are added in a fixed order at the very end.
 //
 // Low-rank term.  The first `nt` workgroups do no streaming: each computes one K-slice of
 // T = X V^T (fp32 partial in the workspace); whichever of them finishes last adds the partials in
@@ -48,9 +48,6 @@ __device__ __forceinline__ void buf_store8_coherent(BufRsrc r, uint32_t off, u32
 }
 typedef __attribute__((address_space(3))) void* LdsPtr;
 
-// All vector memory operations issued so far by this wave (loads, stores and buffer-to-LDS copies)
-// have completed; nothing may be moved across.
-__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // One K-slice of T = X V^T, then (last arriver only) the sum over slices.
 __device__ __forceinline__ void decode_t_worker(const DecodeArgs& a, unsigned char* smem) {
@@ -171,6 +168,7 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
         // Staging: copy i of a chunk moves rows 2i, 2i+1: lane l -> row 2i + l/32, slot position
         // p = l%32, which receives segment p ^ row of the row's 32 segments of 8 columns.
         const int crow = lane >> 5, cp = lane & 31;
+        const int rot = (int)(blockIdx.x * 5u) & (kDecPiece - 1);
         bool t_seen = false;        // this workgroup has already waited for T
 
         for (int64_t blk = (int64_t)blockIdx.x - nworkers; blk * ROWS < N;
@@ -187,13 +185,15 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
             for (int b = 0; b < R; ++b) acc[b] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
             for (int p = 0; p < npieces; ++p) {
-                if (p > 0) __syncthreads();         // the previous piece has been read by everyone
-                // This wave's chunks of the piece (wave, wave + 8): their activations go straight from
-                // L2 into LDS (buffer-to-LDS copies, no registers), issued before the weight loads so
-                // that they complete first ...
+                // This wave's two chunks of the piece.  For each: its activations go straight from L2
+                // into the wave's LDS slot (buffer-to-LDS copies, no registers), then its weights
+                // are loaded; lane quad q takes group 4c + q of chunk c.  The chunk order is rotated
+                // per workgroup so that the workgroups, which all read the same X, do not walk the
+                // same L2 channels in step.
+                RawUnit u[CPW][R];
 #pragma unroll
                 for (int ci = 0; ci < CPW; ++ci) {
-                    const int cw = wave + kDecWaves * ci;           // chunk within the piece
+                    const int cw = (wave + kDecWaves * ci + rot) & (kDecPiece - 1);   // chunk within the piece
                     const int64_t kc = ((int64_t)p * kDecPiece + cw) * 256;
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
@@ -202,28 +202,28 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
                         const bool in = row < M && kc + seg * 8 < K;
                         const uint32_t off = in ? (uint32_t)(((int64_t)row * K + kc + seg * 8) * 2) : kOobOffset;
                         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                            xb, (LdsPtr)(smem + cw * kDecSlotBytes + i * 1024), 16, off, 0, 0, 0);
+                            xb, (LdsPtr)(smem + (wave + kDecWaves * ci) * kDecSlotBytes + i * 1024), 16, off, 0, 0,
+                            0);
                     }
-                }
-                asm volatile("" ::: "memory");
-                // ... then their weights: lane quad q takes group 4c + q of chunk c
-                RawUnit u[CPW][R];
-#pragma unroll
-                for (int ci = 0; ci < CPW; ++ci) {
-                    const int g = 4 * (p * kDecPiece + wave + kDecWaves * ci) + q;
+                    asm volatile("" ::: "memory");
+                    const int g = 4 * (p * kDecPiece + cw) + q;
 #pragma unroll
                     for (int b = 0; b < R; ++b)
                         u[ci][b] = load_unit_buf(wb, (g < G && ubase[b] != kOobUnit) ? ubase[b] + (uint32_t)g * 16u
                                                                                       : kOobUnit);
+                    asm volatile("" ::: "memory");
                 }
-                // Vector memory operations complete in order: once at most the CPW*R*4 weight loads
-                // are outstanding, the copies issued before them have landed in LDS.  (This count
-                // relies on the compiler adding no memory operation of its own in between; the build
-                // script checks the generated code for that.)
-                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CPW * R * 4) : "memory");
-                __syncthreads();
 #pragma unroll
                 for (int ci = 0; ci < CPW; ++ci) {
+                    // Vector memory operations complete in order: once at most the operations issued
+                    // after this chunk's copies are outstanding (its R*4 weight loads and everything
+                    // of the later chunks), the copies have landed in LDS.  The slot is private to
+                    // the wave, so no barrier is involved.  (The count relies on the compiler adding
+                    // no memory operation of its own in between; the build script checks that.)
+                    if (ci == 0)
+                        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(R * 4 + (CPW - 1) * (8 + R * 4)) : "memory");
+                    else
+                        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(R * 4) : "memory");
                     const unsigned char* slot = smem + (wave + kDecWaves * ci) * kDecSlotBytes;
                     f16x8 bfrag[8];
 #pragma unroll

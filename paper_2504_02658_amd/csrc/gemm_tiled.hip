@@ -6,9 +6,9 @@
 // entirely in registers: it loads their packed units straight from HBM, converts them to fp16
 // with the bit trick (milo_device.h) and feeds them as the A operand of v_mfma_f32_32x32x16_f16.
 // Weights therefore never pass through LDS.  The activations are the B operand; the workgroup
-// stages a [BM x 128] slice per step in LDS (double buffered) in exactly the order the MFMA
-// lanes read it, so every ds_read_b128 is conflict free, and each B fragment read from LDS is
-// used by both streams of the wave.
+// stages a [BM x 128] slice per step in LDS (double buffered) with coalesced buffer-to-LDS copies
+// (no registers, no ds_write), swizzled so that every ds_read_b128 of a B fragment is conflict
+// free, and each B fragment read from LDS is used by both streams of the wave.
 //   NW = 1: the two streams are rows n0+64*wave.. and +32 of one weight (band of 256 features).
 //   NW = 2: the streams are the same 32 rows of two weights (gate and up projection, band of
 //           128 features) and the epilogue applies SiLU(gate) * up.
@@ -19,6 +19,7 @@
 namespace milo {
 
 constexpr int kTiledThreads = 256;
+constexpr int kTiledStages = 3;      // chunks in flight per workgroup (LDS stages / register ring)
 
 struct TileInfo {
     int row0;
@@ -56,28 +57,199 @@ __device__ __forceinline__ TileInfo resolve_tile(const RowSpace& rs, int tile, i
 }
 
 __device__ __forceinline__ int64_t input_row(const RowSpace& rs, int64_t R) {
-    return rs.x_rows ? (int64_t)(rs.x_rows[R] / rs.x_row_div) : R;
+    return rs.x_rows ? (int64_t)rs.x_rows[R] : R;
 }
 
-// LDS offset (bytes) of the 16-byte slice "row block mb, MFMA step t, k-half h, row j" inside a
-// stage.  For a fixed (mb, t) the 64 lanes (h, j) read one contiguous KB; the xor spreads the
-// writer's lanes (same row, different t and h) over all 16 bank groups.
-__device__ __forceinline__ int xs_offset(int mb, int t, int h, int j) {
-    return ((mb * 8 + t) * 64 + h * 32 + (j ^ t ^ (h << 3))) * 16;
+// Pins a loaded unit at this point of the program: nothing computed from it can be scheduled
+// earlier.  Without it the compiler converts the scale and zero-point of the NEXT chunk right
+// after issuing their loads and puts the wait for them in the middle of the current chunk.
+__device__ __forceinline__ void pin_unit(RawUnit& u) {
+    uint32_t sz = (uint32_t)__builtin_bit_cast(unsigned short, u.s) |
+                  ((uint32_t)__builtin_bit_cast(unsigned short, u.z) << 16);
+    asm volatile("" : "+v"(u.a.x), "+v"(u.a.y), "+v"(u.a.z), "+v"(u.a.w), "+v"(u.b.x), "+v"(u.b.y), "+v"(sz));
+    u.s = __builtin_bit_cast(f16, (unsigned short)(sz & 0xffffu));
+    u.z = __builtin_bit_cast(f16, (unsigned short)(sz >> 16));
 }
 
 __device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a)); }
 
+typedef __attribute__((address_space(3))) void* LdsPtr;
+// Offset that lies outside every activation buffer (they are kept below 2 GiB) and stays outside
+// when a column offset is added to it.
+constexpr uint32_t kOobHalf = 0x80000000u;
+
+// Spin until *flag becomes non-zero.  The producer never waits and was dispatched earlier, so the
+// wait ends; the bound only turns a broken assumption into an error code instead of a hang.
+__device__ __forceinline__ void wait_flag(const uint32_t* flag, uint32_t* status) {
+    for (uint32_t spins = 0; __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u; ++spins) {
+        __builtin_amdgcn_s_sleep(2);
+        if (spins > (1u << 24)) {
+            if (status) atomicOr(status, 1u);
+            break;
+        }
+    }
+}
+
+// T = X V^T for one M-tile, computed with the same pipeline as the weight tiles: the activations
+// are staged in LDS, the A operand is V read as plain fp16 (rank row = lane % 32, 64 columns per
+// lane and chunk).  NW = 1: wave w, stream s take ranks 64w + 32s ..; NW = 2: stream s is weight s,
+// ranks 32w ..; larger ranks take further passes.  T is written with device-coherent stores and
+// published through the tile's flag.
+template <int NW, int MB>
+__device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& ti, unsigned char* smem) {
+    constexpr int BM = 32 * MB;
+    constexpr int STAGE = BM * 256;
+    constexpr int NCP = BM / 16;
+    constexpr int PASS = (NW == 1) ? 256 : 128;     // ranks per weight covered by one pass
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int i32 = lane & 31, h = lane >> 5;
+    const int64_t K = a.K;
+    const int G = (int)(K / kGroup);
+    const int nchunks = (G + 1) / 2;
+
+    const BufRsrc xb = make_rsrc(a.X, a.x_bytes);
+    uint32_t xoff[NCP];
+    bool xhi[NCP];
+    {
+        int32_t src[NCP];
+#pragma unroll
+        for (int i = 0; i < NCP; ++i) {
+            const int row = 4 * (wave * NCP + i) + (lane >> 4);
+            const int R = ti.row0 + (row < ti.rows ? row : 0);
+            src[i] = a.rs.x_rows ? a.rs.x_rows[R] : R;
+        }
+#pragma unroll
+        for (int i = 0; i < NCP; ++i) {
+            const int row = 4 * (wave * NCP + i) + (lane >> 4);
+            const int seg = (lane & 15) ^ (row & 15);
+            xhi[i] = seg >= 8;
+            xoff[i] = (row < ti.rows) ? (uint32_t)src[i] * (uint32_t)(a.ldx * 2) + (uint32_t)(seg * 16) : kOobHalf;
+        }
+    }
+    const bool ktail = (G & 1) != 0;
+    auto issue_x = [&](int c) {
+        unsigned char* stage = smem + (c & 1) * STAGE;
+        const bool last_half = ktail && c == nchunks - 1;
+#pragma unroll
+        for (int i = 0; i < NCP; ++i) {
+            uint32_t off = xoff[i] + (uint32_t)c * 256u;
+            if (last_half && xhi[i]) off = kOobHalf;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (LdsPtr)(stage + (wave * NCP + i) * 1024), 16, off, 0, 0,
+                                                     0);
+        }
+    };
+
+    const int rmax = ti.w[0].r > ti.w[1].r ? ti.w[0].r : ti.w[1].r;
+    for (int pass0 = 0; pass0 < rmax; pass0 += PASS) {
+        // rank row of each stream of this wave, and its V as a buffer (rows >= r read as zero)
+        BufRsrc vb[2];
+        uint32_t voff[2];
+        int rank0[2];
+        bool active[2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const WeightDev& w = ti.w[NW == 1 ? 0 : s];
+            rank0[s] = pass0 + ((NW == 1) ? 64 * wave + 32 * s : 32 * wave);
+            active[s] = rank0[s] < w.r;
+            vb[s] = make_rsrc(w.V, (uint64_t)(w.r > 0 ? w.r : 0) * (uint64_t)K * 2u);
+            voff[s] = active[s] ? (uint32_t)(((int64_t)(rank0[s] + i32) * K + 64 * h) * 2) : kOobOffset;
+        }
+        f32x16 acc[2][MB];
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[s][mb][v] = 0.0f;
+
+        // V fragment of step t of chunk c; out of range (inactive stream, ragged K tail) reads zero
+        auto load_v = [&](int c, int s, int t) -> u32x4 {
+            const bool out = !active[s] || c >= nchunks || (ktail && c == nchunks - 1 && h == 1);
+            return buf_load16(vb[s], out ? kOobOffset : voff[s] + (uint32_t)c * 256u + 16u * t);
+        };
+
+        u32x4 va[2][8];
+        __syncthreads();            // a previous pass is done with the stages
+        issue_x(0);
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int t = 0; t < 8; ++t) va[s][t] = load_v(0, s, t);
+        for (int c = 0; c < nchunks; ++c) {
+            wait_vmem();
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    asm volatile("" : "+v"(va[s][t].x), "+v"(va[s][t].y), "+v"(va[s][t].z), "+v"(va[s][t].w));
+            __syncthreads();
+            if (c + 1 < nchunks) issue_x(c + 1);
+            const unsigned char* xs = smem + (c & 1) * STAGE + i32 * 256;
+            const int sx = i32 & 15;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const f16x8 b = __builtin_bit_cast(
+                        f16x8, *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h + t) ^ sx) << 4)));
+                    acc[0][mb] = mfma32(__builtin_bit_cast(f16x8, va[0][t]), b, acc[0][mb]);
+                    acc[1][mb] = mfma32(__builtin_bit_cast(f16x8, va[1][t]), b, acc[1][mb]);
+                }
+                // the registers of this step are free again: fetch the next chunk's fragment into them
+                va[0][t] = load_v(c + 1, 0, t);
+                va[1][t] = load_v(c + 1, 1, t);
+            }
+        }
+        // D[v] of (s, mb): rank rank0 + 8*(v/4) + 4*h + v%4, row 32*mb + i32; ranks up to the next
+        // multiple of 16 are written (they are exact zeros) because the consumers read that far.
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            if (NW == 1 && s == 1 && false) continue;
+            const WeightDev& w = ti.w[NW == 1 ? 0 : s];
+            const int rpad = (w.r + 15) & ~15;
+            const BufRsrc tb = make_rsrc(a.T[NW == 1 ? 0 : s], a.t_bytes);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                const int m = 32 * mb + i32;
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int rank = rank0[s] + 8 * vq + 4 * h;
+                    f16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = (f16)acc[s][mb][4 * vq + e];
+                    const bool ok = m < ti.rows && rank < rpad;
+                    __builtin_amdgcn_raw_buffer_store_b64(
+                        __builtin_bit_cast(u32x2, o), tb,
+                        ok ? (uint32_t)(((ti.row0 + m) * a.ldt + rank) * 2) : kOobOffset, 0, 17);
+                }
+            }
+        }
+    }
+    wait_vmem();
+    __syncthreads();
+    if (tid == 0)
+        __hip_atomic_store(a.flags + 2 * blockIdx.y, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <int NW, int MB, int EPI>
-__global__ __launch_bounds__(kTiledThreads) void w3lr_tiled_kernel(const TiledArgs a) {
+__global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const TiledArgs a) {
     constexpr int BM = 32 * MB;
     constexpr int BN = (NW == 1) ? 256 : 128;
-    constexpr int STAGE = MB * 8 * 1024;         // bytes of one X stage
-    constexpr int IT = 2 * MB;                   // 16-byte X slices per thread per stage
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
+    constexpr int STAGE = BM * 256;              // bytes of one X stage: BM rows x 128 columns
+    constexpr int NCP = BM / 16;                 // 1-KB copies per wave and stage (4 rows each)
+    constexpr int PD = MB == 4 ? 2 : kTiledStages;   // chunks in flight, the one being computed included
+    constexpr int PER = NCP + 8;                 // vector memory instructions a wave issues per chunk
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];      // PD stages
 
     const TileInfo ti = resolve_tile<NW>(a.rs, blockIdx.y, BM);
     if (!ti.valid) return;
+    const bool any_rank = ti.w[0].r > 0 || ti.w[1].r > 0;
+    if ((int)blockIdx.x < a.v_tiles) {
+        // leading workgroup column: forms T = X V^T for this M-tile (see v_tile_body)
+        if (any_rank) v_tile_body<NW, MB>(a, ti, smem);
+        return;
+    }
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
@@ -87,35 +259,46 @@ __global__ __launch_bounds__(kTiledThreads) void w3lr_tiled_kernel(const TiledAr
     const int64_t N = a.N, K = a.K;
     const int G = (int)(K / kGroup);
     const int nchunks = (G + 1) / 2;
-    const int64_t n0 = (int64_t)blockIdx.x * BN;
+    const int64_t n0 = (int64_t)((int)blockIdx.x - a.v_tiles) * BN;
 
-    // Weight streams of this wave.
-    W3View view[2];
-    int64_t nrow[2];        // output feature this lane feeds into the A operand
-    int64_t ubase[2];       // unit index of (nrow, group 0)
-    bool nvalid[2];
+    // Weight streams of this wave: lane (i32, h) feeds row nrow of the stream, group 2c + h.
+    W3Buf wbuf[2];
+    int64_t nrow[2];
+    uint32_t ubase[2];
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
         const WeightDev& w = ti.w[NW == 1 ? 0 : s];
-        view[s] = make_view(w.q3, w.scales, w.zeros, N, K);
+        wbuf[s] = make_w3buf(w.q3, w.scales, w.zeros, N, K);
         const int64_t nb = (NW == 1) ? n0 + 64 * wave + 32 * s : n0 + 32 * wave;
         nrow[s] = nb + i32;
-        nvalid[s] = nrow[s] < N;
-        ubase[s] = unit_index(nvalid[s] ? nrow[s] : 0, 0, G);
+        ubase[s] = (nrow[s] < N) ? (uint32_t)unit_index(nrow[s], 0, G) : kOobUnit;
     }
 
-    // Activation rows this thread stages: slice q = tid + 256*it -> row q/16, 8 columns (q%16)*8.
-    const f16* xrow[IT];
-    int xoff[IT];
-    int xseg[IT];
+    // Activation staging.  A stage is [BM rows][256 bytes]; copy ci of the workgroup moves rows
+    // 4ci .. 4ci+3 (1 KB, coalesced): lane l -> row 4ci + l/16, position p = l%16, which receives
+    // segment p ^ (row%16) of the row's 16 segments of 8 columns.  The xor makes the per-lane
+    // ds_read_b128 of the B fragments conflict free (16 lanes read 16 different rows).
+    const BufRsrc xb = make_rsrc(a.X, a.x_bytes);
+    uint32_t xoff[NCP];
+    bool xhi[NCP];
+    {
+        // gather indices first, all loads in flight together (rows past the tile re-read row 0)
+        int32_t src[NCP];
 #pragma unroll
-    for (int it = 0; it < IT; ++it) {
-        const int q = tid + kTiledThreads * it;
-        const int row = q >> 4, seg = q & 15;
-        xseg[it] = seg;
-        xoff[it] = xs_offset(row >> 5, seg & 7, seg >> 3, row & 31);
-        xrow[it] = (row < ti.rows) ? a.X + input_row(a.rs, ti.row0 + row) * a.ldx : nullptr;
+        for (int i = 0; i < NCP; ++i) {
+            const int row = 4 * (wave * NCP + i) + (lane >> 4);
+            const int R = ti.row0 + (row < ti.rows ? row : 0);
+            src[i] = a.rs.x_rows ? a.rs.x_rows[R] : R;
+        }
+#pragma unroll
+        for (int i = 0; i < NCP; ++i) {
+            const int row = 4 * (wave * NCP + i) + (lane >> 4);
+            const int seg = (lane & 15) ^ (row & 15);
+            xhi[i] = seg >= 8;
+            xoff[i] = (row < ti.rows) ? (uint32_t)src[i] * (uint32_t)(a.ldx * 2) + (uint32_t)(seg * 16) : kOobHalf;
+        }
     }
+    const bool ktail = (G & 1) != 0;            // the last chunk has only its first 64 columns
 
     f32x16 acc[2][MB];
 #pragma unroll
@@ -125,88 +308,137 @@ __global__ __launch_bounds__(kTiledThreads) void w3lr_tiled_kernel(const TiledAr
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[s][mb][v] = 0.0f;
 
-    auto load_x = [&](int c, u32x4 (&xr)[IT]) {
-#pragma unroll
-        for (int it = 0; it < IT; ++it) {
-            const int64_t k = (int64_t)c * 128 + xseg[it] * 8;
-            if (xrow[it] != nullptr && k < K)
-                xr[it] = *reinterpret_cast<const u32x4*>(xrow[it] + k);
-            else
-                xr[it] = u32x4{0u, 0u, 0u, 0u};
-        }
-    };
-    auto store_x = [&](int stage, const u32x4 (&xr)[IT]) {
-#pragma unroll
-        for (int it = 0; it < IT; ++it)
-            *reinterpret_cast<u32x4*>(smem + stage * STAGE + xoff[it]) = xr[it];
-    };
-    auto load_w = [&](int c, RawUnit (&ru)[2]) {
+    // One chunk's loads of this wave, always PER instructions (chunks past the end read out of
+    // range, which costs no memory traffic): the two weight units, then the NCP activation copies
+    // into stage `slot`.
+    auto issue = [&](int c, int slot, RawUnit (&ru)[2]) {
         const int g = 2 * c + h;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            if (nvalid[s] && g < G)
-                ru[s] = load_unit<false>(view[s], ubase[s] + (int64_t)g * 16);
-            else
-                ru[s] = zero_unit();
+        for (int s = 0; s < 2; ++s)
+            ru[s] = load_unit_buf(wbuf[s], (g < G && ubase[s] != kOobUnit) ? ubase[s] + (uint32_t)g * 16u : kOobUnit);
+        asm volatile("" ::: "memory");
+        unsigned char* stage = smem + slot * STAGE;
+        const bool past = c >= nchunks;
+        const bool last_half = ktail && c == nchunks - 1;
+#pragma unroll
+        for (int i = 0; i < NCP; ++i) {
+            uint32_t off = xoff[i] + (uint32_t)c * 256u;
+            if (past || (last_half && xhi[i])) off = kOobHalf;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (LdsPtr)(stage + (wave * NCP + i) * 1024), 16, off, 0, 0,
+                                                     0);
+        }
+        asm volatile("" ::: "memory");
+    };
+    const int mb_used = (ti.rows + 31) / 32;
+    auto compute = [&](int slot, RawUnit (&ru)[2]) {
+        pin_unit(ru[0]);
+        pin_unit(ru[1]);
+        // B fragment of step t, row block mb: row 32mb + i32, segment 8h + t.
+        const unsigned char* xs = smem + slot * STAGE + i32 * 256;
+        const int sx = i32 & 15;
+        if (MB == 4) {
+            // 128 accumulator registers leave no room for a prefetched fragment set if two waves
+            // are to share a SIMD; the second wave hides the read latency instead.
+            dequant_units2_steps(ru[0], ru[1], [&](int t, f16x8 a0, f16x8 a1) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    if (mb < mb_used) {     // row blocks past the tile's rows are skipped (uniform)
+                        const f16x8 b = __builtin_bit_cast(
+                            f16x8,
+                            *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h + t) ^ sx) << 4)));
+                        acc[0][mb] = mfma32(a0, b, acc[0][mb]);
+                        acc[1][mb] = mfma32(a1, b, acc[1][mb]);
+                    }
+                }
+            });
+        } else {
+            f16x8 bc[MB], bn[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                bc[mb] = __builtin_bit_cast(
+                    f16x8, *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h) ^ sx) << 4)));
+            dequant_units2_steps(ru[0], ru[1], [&](int t, f16x8 a0, f16x8 a1) {
+                if (t < 7) {
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+                        bn[mb] = __builtin_bit_cast(
+                            f16x8,
+                            *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h + t + 1) ^ sx) << 4)));
+                }
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    acc[0][mb] = mfma32(a0, bc[mb], acc[0][mb]);
+                    acc[1][mb] = mfma32(a1, bc[mb], acc[1][mb]);
+                }
+                if (t < 7) {
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) bc[mb] = bn[mb];
+                }
+            });
         }
     };
 
-    RawUnit raw[2];
-    {
-        u32x4 xr[IT];
-        load_x(0, xr);
-        load_w(0, raw);
-        store_x(0, xr);
-    }
-    __syncthreads();
-
-    for (int c = 0; c < nchunks; ++c) {
-        const int cur = c & 1;
-        const bool more = (c + 1) < nchunks;
-        u32x4 xr[IT];
-        RawUnit rawn[2];
-        if (more) {
-            load_x(c + 1, xr);
-            load_w(c + 1, rawn);
-        }
-        const unsigned char* xs = smem + cur * STAGE;
+    // PD-deep pipeline: chunk c lives in ring slot c % PD (registers for the weights, LDS stage
+    // for the activations).  Vector memory operations complete in order, so once at most the
+    // (PD - 2) * PER instructions of the younger chunks are outstanding, chunk c has arrived.
+    // (The count relies on the compiler adding no memory operation of its own, i.e. on the
+    // kernel not using scratch memory; the build script checks that.)
+    RawUnit ring[PD][2];
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
-            dequant_unit_steps(raw[s], [&](int t, f16x8 frag) {
+    for (int i = 0; i < PD - 1; ++i) issue(i, i, ring[i]);
+    for (int c0 = 0; c0 < nchunks; c0 += PD) {
+#pragma unroll
+        for (int slot = 0; slot < PD; ++slot) {
+            const int c = c0 + slot;
+            if (c >= nchunks) break;
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PD - 2) * PER) : "memory");
+            __syncthreads();        // everyone's copies of chunk c landed; everyone left chunk c-1
+            issue(c + PD - 1, (slot + PD - 1) % PD, ring[(slot + PD - 1) % PD]);
+            compute(slot, ring[slot]);
+        }
+    }
+
+    bool nvalid[2];
+    nvalid[0] = nrow[0] < N;
+    nvalid[1] = nrow[1] < N;
+
+    // Low-rank term: r extra k-steps with A = U rows and B = T rows.  T of this M-tile is formed
+    // by the leading workgroup of the same grid row during this launch: wait for its flag (it was
+    // dispatched before this workgroup and never waits itself), then read T coherently.
+    if (any_rank) {
+        if (tid == 0) wait_flag(a.flags + 2 * blockIdx.y, a.flags_status);
+        __syncthreads();
+        const BufRsrc tb0 = make_rsrc(a.T[0], a.t_bytes);
+        const BufRsrc tb1 = make_rsrc(a.T[1], a.t_bytes);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const WeightDev& w = ti.w[NW == 1 ? 0 : s];
+            const int r = w.r;
+            if (r <= 0) continue;
+            const BufRsrc tb = (NW == 1 || s == 0) ? tb0 : tb1;
+            const f16* urow = w.U + (nvalid[s] ? nrow[s] : 0) * (int64_t)r;
+            const bool ualigned = (r & 7) == 0;
+            for (int ks = 0; ks < r; ks += 16) {
+                const int k0 = ks + 8 * h;
+                f16x8 av = zero_f16x8();
+                if (nvalid[s] && k0 < r) av = load_row8(urow, k0, r, ualigned);
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
-                    const f16x8 b = __builtin_bit_cast(
-                        f16x8, *reinterpret_cast<const u32x4*>(xs + xs_offset(mb, t, h, i32)));
-                    acc[s][mb] = mfma32(frag, b, acc[s][mb]);
+                    const int m = 32 * mb + i32;
+                    const f16x8 bv = __builtin_bit_cast(
+                        f16x8, buf_load16_coherent(tb, m < ti.rows ? (uint32_t)(((ti.row0 + m) * a.ldt + k0) * 2)
+                                                                   : kOobOffset));
+                    acc[s][mb] = mfma32(av, bv, acc[s][mb]);
                 }
-            });
-        if (more) {
-            store_x(cur ^ 1, xr);
-            raw[0] = rawn[0];
-            raw[1] = rawn[1];
+            }
         }
+        // the last reader of this M-tile's T clears its two control words for the next launch
         __syncthreads();
-    }
-
-    // Low-rank term: r extra k-steps with A = U rows and B = T rows.
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const WeightDev& w = ti.w[NW == 1 ? 0 : s];
-        const int r = w.r;
-        if (r <= 0) continue;
-        const f16* Tm = a.T[NW == 1 ? 0 : s];
-        const f16* urow = w.U + (nvalid[s] ? nrow[s] : 0) * (int64_t)r;
-        const bool ualigned = (r & 7) == 0;
-        for (int ks = 0; ks < r; ks += 16) {
-            const int k0 = ks + 8 * h;
-            f16x8 av = zero_f16x8();
-            if (nvalid[s] && k0 < r) av = load_row8(urow, k0, r, ualigned);
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                const int m = 32 * mb + i32;
-                f16x8 bv = zero_f16x8();
-                if (m < ti.rows) bv = load_f16x8(Tm + (int64_t)(ti.row0 + m) * a.ldt + k0);
-                acc[s][mb] = mfma32(av, bv, acc[s][mb]);
+        if (tid == 0) {
+            const uint32_t readers = gridDim.x - (uint32_t)a.v_tiles;
+            if (atomicAdd(a.flags + 2 * blockIdx.y + 1, 1u) == readers - 1u) {
+                __hip_atomic_store(a.flags + 2 * blockIdx.y, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.flags + 2 * blockIdx.y + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
@@ -345,21 +577,38 @@ int launch_t_kernel(const TArgs& a, int nw, int m_tiles, hipStream_t stream) {
     return launch_status();
 }
 
+template <int NW, int MB, int EPI>
+static int launch_one(const TiledArgs& a, dim3 grid, hipStream_t stream) {
+    constexpr int lds = (MB == 4 ? 2 : kTiledStages) * 32 * MB * 256;
+    static bool raised[64] = {false};
+    if (lds > 64 * 1024) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MILO_ERR_HIP;
+        if (!raised[dev]) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(w3lr_tiled_kernel<NW, MB, EPI>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+                return MILO_ERR_HIP;
+            raised[dev] = true;
+        }
+    }
+    w3lr_tiled_kernel<NW, MB, EPI><<<grid, dim3(kTiledThreads), lds, stream>>>(a);
+    return launch_status();
+}
+
 template <int NW, int EPI>
 static int launch_tiled_mb(const TiledArgs& a, int mb, dim3 grid, hipStream_t stream) {
     switch (mb) {
-        case 1: w3lr_tiled_kernel<NW, 1, EPI><<<grid, dim3(kTiledThreads), 0, stream>>>(a); break;
-        case 2: w3lr_tiled_kernel<NW, 2, EPI><<<grid, dim3(kTiledThreads), 0, stream>>>(a); break;
-        case 4: w3lr_tiled_kernel<NW, 4, EPI><<<grid, dim3(kTiledThreads), 0, stream>>>(a); break;
+        case 1: return launch_one<NW, 1, EPI>(a, grid, stream);
+        case 2: return launch_one<NW, 2, EPI>(a, grid, stream);
+        case 4: return launch_one<NW, 4, EPI>(a, grid, stream);
         default: return MILO_ERR_SHAPE;
     }
-    return launch_status();
 }
 
 int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipStream_t stream) {
     if (m_tiles <= 0) return MILO_OK;
     const int bn = (nw == 1) ? 256 : 128;
-    const int64_t n_tiles = (a.N + bn - 1) / bn;
+    const int64_t n_tiles = (a.N + bn - 1) / bn + a.v_tiles;
     if (n_tiles > 0x7fffffff || m_tiles > 65535) return MILO_ERR_SHAPE;
     dim3 grid((unsigned)n_tiles, (unsigned)m_tiles, 1);
     if (nw == 2 && epi == EPI_SWIGLU) return launch_tiled_mb<2, EPI_SWIGLU>(a, mb, grid, stream);

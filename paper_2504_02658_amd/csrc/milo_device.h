@@ -109,6 +109,10 @@ __device__ __forceinline__ f16 buf_load2(BufRsrc r, uint32_t off) {
     return __builtin_bit_cast(f16, v);
 }
 
+// All vector memory operations issued so far by this wave (loads, stores and buffer-to-LDS copies)
+// have completed; nothing may be moved across.
+__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // The four arrays of a packed weight as buffers.
 struct W3Buf {
     BufRsrc a, b, s, z;
@@ -135,12 +139,20 @@ __device__ __forceinline__ RawUnit load_unit_buf(const W3Buf& w, uint32_t u) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// (a & mask) | orv in one VALU op.  The mask sits in an SGPR: on gfx9-family encodings a VOP3
-// instruction cannot carry a 32-bit literal, and without this the compiler emits and + or.
+// (a & mask) | orv in one VALU op (v_and_or_b32).  On gfx9-family encodings a VOP3 instruction
+// cannot carry a 32-bit literal, so with literal operands the compiler emits and + or; hiding
+// the constants behind an empty asm puts them in registers once and lets the and-or pattern
+// match, while the instruction itself stays visible to the scheduler.
+__device__ __forceinline__ uint32_t in_sgpr(uint32_t v) {
+    asm("" : "+s"(v));
+    return v;
+}
+__device__ __forceinline__ uint32_t in_vgpr(uint32_t v) {
+    asm("" : "+v"(v));
+    return v;
+}
 __device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t orv) {
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(orv));
-    return r;
+    return (a & mask) | orv;
 }
 
 // 3-bit -> fp16 conversion of one unit (Section 3.3 of the paper, "MiLo Dequant", reworked for
@@ -193,7 +205,8 @@ __device__ __forceinline__ uint32_t pk_fma(uint32_t a, uint32_t b, uint32_t c) {
 template <typename OnStep>
 __device__ __forceinline__ void dequant_unit_steps(const RawUnit& ru, OnStep&& on_step) {
     const UnitConsts c = unit_consts(ru);
-    const uint32_t B0 = 0x64006400u, B3 = 0x58005800u, B6 = 0x4C004C00u;
+    const uint32_t B0 = in_vgpr(0x64006400u), B3 = in_vgpr(0x58005800u), B6 = in_vgpr(0x4C004C00u);
+    const uint32_t M0 = in_sgpr(0x00070007u), M3 = in_sgpr(0x00380038u), M6 = in_sgpr(0x01C001C0u);
     const uint32_t d[6] = {ru.a.x, ru.a.y, ru.a.z, ru.a.w, ru.b.x, ru.b.y};
     uint32_t w[32];
     int next = 0;
@@ -201,11 +214,11 @@ __device__ __forceinline__ void dequant_unit_steps(const RawUnit& ru, OnStep&& o
     for (int j = 0; j < 6; ++j) {
         const uint32_t sh = d[j] >> 9;
         uint32_t h[5];
-        h[0] = and_or(d[j], 0x00070007u, B0);
-        h[1] = and_or(d[j], 0x00380038u, B3);
-        h[2] = and_or(d[j], 0x01C001C0u, B6);
-        h[3] = and_or(sh, 0x00070007u, B0);
-        h[4] = and_or(sh, 0x00380038u, B3);
+        h[0] = and_or(d[j], M0, B0);
+        h[1] = and_or(d[j], M3, B3);
+        h[2] = and_or(d[j], M6, B6);
+        h[3] = and_or(sh, M0, B0);
+        h[4] = and_or(sh, M3, B3);
         __builtin_amdgcn_sched_barrier(0);
         h[0] = pk_sub(h[0], c.A0);
         h[1] = pk_sub(h[1], c.A3);
@@ -226,15 +239,16 @@ __device__ __forceinline__ void dequant_unit_steps(const RawUnit& ru, OnStep&& o
     }
     // Pairs 30 and 31 are spread over the spare bits 15 / 31 of three words each; shifting the
     // words by 9, 8 and 7 lines the three bits up at mantissa bits 6, 7, 8.
-    uint32_t t0 = and_or(d[0] >> 9, 0x00400040u, B6);
-    uint32_t t1 = and_or(d[3] >> 9, 0x00400040u, B6);
+    const uint32_t S6 = in_sgpr(0x00400040u), S7 = in_sgpr(0x00800080u), S8 = in_sgpr(0x01000100u);
+    uint32_t t0 = and_or(d[0] >> 9, S6, B6);
+    uint32_t t1 = and_or(d[3] >> 9, S6, B6);
     const uint32_t x0 = d[1] >> 8, x1 = d[4] >> 8, y0 = d[2] >> 7, y1 = d[5] >> 7;
     __builtin_amdgcn_sched_barrier(0);
-    t0 = and_or(x0, 0x00800080u, t0);
-    t1 = and_or(x1, 0x00800080u, t1);
+    t0 = and_or(x0, S7, t0);
+    t1 = and_or(x1, S7, t1);
     __builtin_amdgcn_sched_barrier(0);
-    t0 = and_or(y0, 0x01000100u, t0);
-    t1 = and_or(y1, 0x01000100u, t1);
+    t0 = and_or(y0, S8, t0);
+    t1 = and_or(y1, S8, t1);
     __builtin_amdgcn_sched_barrier(0);
     t0 = pk_sub(t0, c.A6);
     t1 = pk_sub(t1, c.A6);
@@ -243,6 +257,72 @@ __device__ __forceinline__ void dequant_unit_steps(const RawUnit& ru, OnStep&& o
     w[31] = pk_fma(t1, c.S2, c.C2);
     __builtin_amdgcn_sched_barrier(0);
     on_step(7, unit_frag(w, 7));
+}
+
+// Two units converted in lock step (ten independent operations per group): the tiled kernel
+// feeds two weight streams from one set of B fragments.  on_step(t, frag0, frag1), t = 0..7.
+template <typename OnStep>
+__device__ __forceinline__ void dequant_units2_steps(const RawUnit& r0, const RawUnit& r1, OnStep&& on_step) {
+    const UnitConsts c0 = unit_consts(r0), c1 = unit_consts(r1);
+    const uint32_t B0 = in_vgpr(0x64006400u), B3 = in_vgpr(0x58005800u), B6 = in_vgpr(0x4C004C00u);
+    const uint32_t M0 = in_sgpr(0x00070007u), M3 = in_sgpr(0x00380038u), M6 = in_sgpr(0x01C001C0u);
+    const uint32_t S6 = in_sgpr(0x00400040u), S7 = in_sgpr(0x00800080u), S8 = in_sgpr(0x01000100u);
+    const uint32_t d0[6] = {r0.a.x, r0.a.y, r0.a.z, r0.a.w, r0.b.x, r0.b.y};
+    const uint32_t d1[6] = {r1.a.x, r1.a.y, r1.a.z, r1.a.w, r1.b.x, r1.b.y};
+    uint32_t w0[32], w1[32];
+    int next = 0;
+#pragma unroll
+    for (int j = 0; j < 6; ++j) {
+        const uint32_t s0 = d0[j] >> 9, s1 = d1[j] >> 9;
+        uint32_t h0[5], h1[5];
+        h0[0] = and_or(d0[j], M0, B0);
+        h1[0] = and_or(d1[j], M0, B0);
+        h0[1] = and_or(d0[j], M3, B3);
+        h1[1] = and_or(d1[j], M3, B3);
+        h0[2] = and_or(d0[j], M6, B6);
+        h1[2] = and_or(d1[j], M6, B6);
+        h0[3] = and_or(s0, M0, B0);
+        h1[3] = and_or(s1, M0, B0);
+        h0[4] = and_or(s0, M3, B3);
+        h1[4] = and_or(s1, M3, B3);
+        h0[0] = pk_sub(h0[0], c0.A0);
+        h1[0] = pk_sub(h1[0], c1.A0);
+        h0[1] = pk_sub(h0[1], c0.A3);
+        h1[1] = pk_sub(h1[1], c1.A3);
+        h0[2] = pk_sub(h0[2], c0.A6);
+        h1[2] = pk_sub(h1[2], c1.A6);
+        h0[3] = pk_sub(h0[3], c0.A0);
+        h1[3] = pk_sub(h1[3], c1.A0);
+        h0[4] = pk_sub(h0[4], c0.A3);
+        h1[4] = pk_sub(h1[4], c1.A3);
+#pragma unroll
+        for (int i = 0; i < 5; ++i) {
+            w0[5 * j + i] = pk_fma(h0[i], c0.S2, c0.C2);
+            w1[5 * j + i] = pk_fma(h1[i], c1.S2, c1.C2);
+        }
+#pragma unroll
+        for (int t = 0; t < 7; ++t) {
+            if (t == next && 4 * t + 3 <= 5 * j + 4) {
+                on_step(t, unit_frag(w0, t), unit_frag(w1, t));
+                ++next;
+            }
+        }
+    }
+    uint32_t p0 = and_or(d0[0] >> 9, S6, B6), q0 = and_or(d0[3] >> 9, S6, B6);
+    uint32_t p1 = and_or(d1[0] >> 9, S6, B6), q1 = and_or(d1[3] >> 9, S6, B6);
+    p0 = and_or(d0[1] >> 8, S7, p0);
+    q0 = and_or(d0[4] >> 8, S7, q0);
+    p1 = and_or(d1[1] >> 8, S7, p1);
+    q1 = and_or(d1[4] >> 8, S7, q1);
+    p0 = and_or(d0[2] >> 7, S8, p0);
+    q0 = and_or(d0[5] >> 7, S8, q0);
+    p1 = and_or(d1[2] >> 7, S8, p1);
+    q1 = and_or(d1[5] >> 7, S8, q1);
+    w0[30] = pk_fma(pk_sub(p0, c0.A6), c0.S2, c0.C2);
+    w0[31] = pk_fma(pk_sub(q0, c0.A6), c0.S2, c0.C2);
+    w1[30] = pk_fma(pk_sub(p1, c1.A6), c1.S2, c1.C2);
+    w1[31] = pk_fma(pk_sub(q1, c1.A6), c1.S2, c1.C2);
+    on_step(7, unit_frag(w0, 7), unit_frag(w1, 7));
 }
 
 // All 32 pairs of a unit at once (for the dense dequantization kernel).

@@ -30,7 +30,7 @@ struct TileDesc {
 //   Ungrouped (tiles == nullptr): tile y covers rows [y*BM, min(M, (y+1)*BM)), weights = w[].
 //   Grouped: tile y = tiles[y] if y < *n_tiles (else the workgroup exits); the weights are
 //   experts[tile.expert].{w1,w3,w2}[which[a]].
-//   Input row of tile row R:  x_rows ? x_rows[R] / x_row_div : R.
+//   Input row of tile row R:  x_rows ? x_rows[R] : R.
 struct RowSpace {
     const TileDesc* tiles;
     const int32_t* n_tiles;
@@ -39,16 +39,20 @@ struct RowSpace {
     WeightDev w[2];
     int64_t M;
     const int32_t* x_rows;
-    int32_t x_row_div;
 };
 
 struct TiledArgs {
     RowSpace rs;
     const f16* X;       // input rows, leading dimension ldx
     int64_t ldx;
+    uint64_t x_bytes;   // size of the X buffer in bytes (< 2 GiB: it is addressed with 32-bit offsets)
     int64_t N, K;       // weight shape (out x in)
-    const f16* T[2];    // X V^T per weight stream, [rows x ldt] fp16, zero beyond the rank
-    int64_t ldt;
+    f16* T[2];          // X V^T per weight stream, [rows x ldt] fp16, zero beyond the rank; written
+    int64_t ldt;        // by the launch's leading workgroup column, read by the others
+    uint64_t t_bytes;   // size of each T buffer in bytes
+    int v_tiles;        // 1 when a leading workgroup column forms T (some rank > 0), else 0
+    uint32_t* flags;    // per M-tile: [2t] T ready, [2t+1] readers done; zero between launches
+    uint32_t* flags_status;  // set non-zero if a wait ever gave up
     void* out;          // EPI 0/1: fp16 [rows x ldo];  EPI 2: fp32 [.. x ldo]
     int64_t ldo;
     const int32_t* out_rows;   // EPI 2: output row of tile row R (nullptr: R)

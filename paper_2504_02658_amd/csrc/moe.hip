@@ -7,6 +7,8 @@
 //   T2        T2 = H V2^T
 //   down      O[pair] = gate_weight * lin_w2(H)       (fp32, one row per routed pair)
 //   combine   y_t = fp16( sum over the token's slots, in slot order, of O )
+#include <stdlib.h>
+
 #include "milo_host.h"
 #include "milo_kernels.h"
 
@@ -19,9 +21,13 @@ struct RouteArgs {
     int32_t P;
     int32_t E;
     int32_t bm;             // rows per M-tile
+    int32_t topk;
     int32_t* sorted;        // [P] pair indices grouped by expert, original order inside a group
+    int32_t* sorted_token;  // [P] token of each sorted pair (pair / topk)
     TileDesc* tiles;
-    int32_t* header;        // [0] routing status, [1] number of tiles
+    int32_t* header;        // [0] routing status, [1] number of tiles, [2] wait status
+    uint32_t* flags;        // per-tile control words of the GEMM kernels, cleared here
+    int32_t n_flags;
 };
 
 // One workgroup per expert.  Every workgroup histograms all ids itself (integer LDS atomics),
@@ -66,7 +72,11 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const RouteArgs a)
         __syncthreads();
         int before = s_running;
         for (int w = 0; w < wave; ++w) before += wcount[w];
-        if (mine) a.sorted[off_e + before + __popcll(bal & ((1ull << lane) - 1ull))] = i;
+        if (mine) {
+            const int pos = off_e + before + __popcll(bal & ((1ull << lane) - 1ull));
+            a.sorted[pos] = i;
+            a.sorted_token[pos] = i / a.topk;
+        }
         __syncthreads();
         if (tid == 0) {
             int tot = 0;
@@ -85,9 +95,13 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const RouteArgs a)
         td.pad = 0;
         a.tiles[tile0 + i] = td;
     }
-    if (e == 0 && tid == 0) {
-        a.header[0] = s_bad ? MILO_ERR_ROUTING : MILO_OK;
-        a.header[1] = s_tiles_total;
+    if (e == 0) {
+        for (int i = tid; i < a.n_flags; i += kRouteThreads) a.flags[i] = 0u;
+        if (tid == 0) {
+            a.header[0] = s_bad ? MILO_ERR_ROUTING : MILO_OK;
+            a.header[1] = s_tiles_total;
+            a.header[2] = 0;
+        }
     }
 }
 
@@ -117,7 +131,8 @@ struct MoeLayout {
     int bm;
     int max_tiles;
     int64_t ldt;
-    size_t off_header, off_sorted, off_tiles, off_t1, off_t3, off_h, off_o, total;
+    size_t off_header, off_flags, off_sorted, off_token, off_tiles, off_t1, off_t3, off_h, off_o, total;
+    int64_t max_tiles32;
 };
 
 static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_max, MoeLayout* L) {
@@ -126,16 +141,24 @@ static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_m
     if (H % 4 != 0) return false;
     const int64_t P = T * topk;
     if (P > (int64_t)0x3fffffff || E > 65536) return false;
+    if (((uint64_t)r_max + 256) * (uint64_t)(H > F ? H : F) * 2 >= 0xFFFFFFF0ull) return false;
+    // activations are addressed with 32-bit offsets inside the kernels
+    if ((uint64_t)T * H * 2 >= 0x80000000ull || (uint64_t)P * F * 2 >= 0x80000000ull) return false;
     const int64_t avg = P / E;
     L->bm = avg >= 96 ? 128 : (avg >= 48 ? 64 : 32);
+    if (const char* e = getenv("MILO_MOE_BM")) L->bm = atoi(e);        // tuning override
     const int64_t max_tiles32 = (P + 31) / 32 + E;      // bound for the smallest tile height
     const int64_t max_tiles = (P + L->bm - 1) / L->bm + E;
     if (max_tiles > 65535) return false;
     L->max_tiles = (int)max_tiles;
     L->ldt = ((int64_t)r_max + 15) / 16 * 16;
+    if ((uint64_t)P * (uint64_t)L->ldt * 2 >= 0xFFFFFFF0ull) return false;
     size_t off = 0;
     L->off_header = off; off = align_up(off + 64, 256);
+    L->max_tiles32 = max_tiles32;
+    L->off_flags = off;  off = align_up(off + (size_t)max_tiles32 * 8, 256);
     L->off_sorted = off; off = align_up(off + (size_t)P * 4, 256);
+    L->off_token = off;  off = align_up(off + (size_t)P * 4, 256);
     L->off_tiles = off;  off = align_up(off + (size_t)max_tiles32 * sizeof(TileDesc), 256);
     L->off_t1 = off;     off = align_up(off + (size_t)P * L->ldt * 2, 256);
     L->off_t3 = off;     off = align_up(off + (size_t)P * L->ldt * 2, 256);
@@ -201,6 +224,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
     char* ws = reinterpret_cast<char*>(workspace);
     int32_t* header = reinterpret_cast<int32_t*>(ws + L.off_header);
     int32_t* sorted = reinterpret_cast<int32_t*>(ws + L.off_sorted);
+    int32_t* sorted_token = reinterpret_cast<int32_t*>(ws + L.off_token);
     TileDesc* tiles = reinterpret_cast<TileDesc*>(ws + L.off_tiles);
     f16* T1 = reinterpret_cast<f16*>(ws + L.off_t1);
     f16* T3 = reinterpret_cast<f16*>(ws + L.off_t3);
@@ -210,7 +234,9 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
 
     RouteArgs ra;
     ra.ids = topk_ids; ra.P = P; ra.E = E; ra.bm = L.bm;
-    ra.sorted = sorted; ra.tiles = tiles; ra.header = header;
+    ra.topk = topk; ra.sorted = sorted; ra.sorted_token = sorted_token; ra.tiles = tiles; ra.header = header;
+    uint32_t* flags = reinterpret_cast<uint32_t*>(ws + L.off_flags);
+    ra.flags = flags; ra.n_flags = (int32_t)(2 * L.max_tiles32);
     route_kernel<<<dim3((unsigned)E), dim3(kRouteThreads), (size_t)E * sizeof(int32_t), stream>>>(ra);
     int st = launch_status();
     if (st != MILO_OK) return st;
@@ -222,36 +248,28 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
 
     // gate / up projection
     rs.which[0] = 0; rs.which[1] = 1;
-    rs.x_rows = sorted; rs.x_row_div = topk;
-    if (r_max > 0) {
-        TArgs ta;
-        ta.rs = rs; ta.X = reinterpret_cast<const f16*>(X); ta.ldx = H; ta.K = H;
-        ta.T[0] = T1; ta.T[1] = T3; ta.ldt = L.ldt; ta.bm = L.bm;
-        st = launch_t_kernel(ta, 2, L.max_tiles, stream);
-        if (st != MILO_OK) return st;
-    }
+    rs.x_rows = sorted_token;
     {
         TiledArgs ga;
-        ga.rs = rs; ga.X = reinterpret_cast<const f16*>(X); ga.ldx = H; ga.N = F; ga.K = H;
-        ga.T[0] = T1; ga.T[1] = T3; ga.ldt = L.ldt;
+        ga.rs = rs; ga.X = reinterpret_cast<const f16*>(X); ga.ldx = H; ga.x_bytes = (uint64_t)T * H * 2;
+        ga.N = F; ga.K = H;
+        ga.T[0] = T1; ga.T[1] = T3; ga.ldt = L.ldt; ga.t_bytes = (uint64_t)P * L.ldt * 2;
+        ga.v_tiles = r_max > 0 ? 1 : 0; ga.flags = flags;
+        ga.flags_status = reinterpret_cast<uint32_t*>(header + 2);
         ga.out = Hbuf; ga.ldo = F; ga.out_rows = nullptr; ga.out_scale = nullptr;
         st = launch_tiled(ga, 2, mb, EPI_SWIGLU, L.max_tiles, stream);
         if (st != MILO_OK) return st;
     }
     // down projection (T2 reuses the T1 buffer: T1 is dead once the gate/up kernel has run)
     rs.which[0] = 2; rs.which[1] = 2;
-    rs.x_rows = nullptr; rs.x_row_div = 1;
-    if (r_max > 0) {
-        TArgs ta;
-        ta.rs = rs; ta.X = Hbuf; ta.ldx = F; ta.K = F;
-        ta.T[0] = T1; ta.T[1] = T1; ta.ldt = L.ldt; ta.bm = L.bm;
-        st = launch_t_kernel(ta, 1, L.max_tiles, stream);
-        if (st != MILO_OK) return st;
-    }
+    rs.x_rows = nullptr;
     {
         TiledArgs da;
-        da.rs = rs; da.X = Hbuf; da.ldx = F; da.N = H; da.K = F;
-        da.T[0] = T1; da.T[1] = T1; da.ldt = L.ldt;
+        da.rs = rs; da.X = Hbuf; da.ldx = F; da.x_bytes = (uint64_t)P * F * 2;
+        da.N = H; da.K = F;
+        da.T[0] = T1; da.T[1] = T1; da.ldt = L.ldt; da.t_bytes = (uint64_t)P * L.ldt * 2;
+        da.v_tiles = r_max > 0 ? 1 : 0; da.flags = flags;
+        da.flags_status = reinterpret_cast<uint32_t*>(header + 2);
         da.out = O; da.ldo = H; da.out_rows = sorted; da.out_scale = topk_weights;
         st = launch_tiled(da, 1, mb, EPI_SCALE_SCATTER, L.max_tiles, stream);
         if (st != MILO_OK) return st;
@@ -277,10 +295,11 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
 
 extern "C" int milo_moe_w3lr_routing_status(const void* workspace, void* stream) {
     if (!workspace) return MILO_ERR_NULL;
-    int32_t header[2] = {0, 0};
+    int32_t header[4] = {0, 0, 0, 0};
     if (hipMemcpyAsync(header, workspace, sizeof(header), hipMemcpyDeviceToHost,
                        (hipStream_t)stream) != hipSuccess)
         return MILO_ERR_HIP;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return MILO_ERR_HIP;
+    if (header[2] != 0) return MILO_ERR_HIP;        // a wait inside a kernel gave up
     return header[0] == MILO_OK ? MILO_OK : MILO_ERR_ROUTING;
 }
