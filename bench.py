@@ -24,6 +24,19 @@ HBM_PEAK_GBS = 8000.0
 MFMA_FP16_PEAK_TFLOPS = 2500.0
 
 
+def measured_traffic():
+    """HBM bytes per launch of the decode kernel on this workload, from the rocprofv3 --pmc runs
+    summarised in profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy); None if absent."""
+    path = os.path.join(ROOT, "profiles", "w3lr_decode_kernel_c1_pmc.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":", 1)[1].strip()))
+    except OSError:
+        pass
+    return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -32,6 +45,11 @@ def parse():
     ap.add_argument("--copies", type=int, default=24)
     ap.add_argument("--extra", action="store_true", help="also measure M=1/4, hot, c2, c3, c4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 256 MiB elementwise copy kernel 20 times (counter "
+                         "calibration for --pmc runs)")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0,
+                    help="CPU time to spend on the oracle baseline")
     return ap.parse_args()
 
 
@@ -86,6 +104,17 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 
+    if args.calibrate_copy:
+        # A plain elementwise copy kernel of known size (reads 256 MiB, writes 256 MiB per launch):
+        # what FETCH_SIZE / WRITE_SIZE read for it gives the counters' scale.
+        src = torch.zeros(64 << 20, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": 256 << 20, "launches": 20}))
+        return
+
     def build_linear(case):
         W = torch.from_numpy(wl.gen_weight(case.N, case.K, case.seed, case.outlier_frac,
                                            case.outlier_gain)).to(dev)
@@ -130,7 +159,7 @@ def main():
         "us_per_call": round(ms_step * 1e3, 3),
         "tflops": round(flops / (ms_step * 1e-3) / 1e12, 3),
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic(),
                      "kernel": "w3lr_decode_kernel",
                      "bytes_per_launch": wbytes, "weight_only_bytes": code_bytes,
                      "weight_only_frac": round(code_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
@@ -142,7 +171,7 @@ def main():
             ms, _ = decode_bench(M, copies, args.steps, args.warmup)
             extra[f"c1_M{M}_cold"] = {"us": round(ms * 1e3, 3),
                                       "GBps": round(wbytes / (ms * 1e-3) / 1e9, 1)}
-        ms, _ = decode_bench(16, copies[:1], args.steps, args.warmup)
+        ms, _ = decode_bench(16, copies[:1] * 24, args.steps, args.warmup)
         extra["c1_M16_hot"] = {"us": round(ms * 1e3, 3), "GBps": round(wbytes / (ms * 1e-3) / 1e9, 1)}
         del copies[1:]
         torch.cuda.empty_cache()
@@ -154,7 +183,7 @@ def main():
         X2 = torch.from_numpy(wl.gen_activations(c2.M, c2.K, c2.seed)).to(dev)
         Y2 = torch.empty((c2.M, c2.N), dtype=torch.float16, device=dev)
         ws2 = api.new_workspace(api.gemm_workspace_bytes(c2.M, c2.N, c2.K, c2.r), dev)
-        ms, _ = time_steps(lambda i: api.w3lr_gemm(X2, pw2, out=Y2, workspace=ws2), 50, 1, 5)
+        ms, _ = time_steps(lambda i: api.w3lr_gemm(X2, pw2, out=Y2, workspace=ws2), 50, 10, 10)
         ms /= 50
         f2 = 2.0 * c2.M * (c2.N * c2.K + c2.r * (c2.N + c2.K))
         extra["c2_prefill"] = {"us": round(ms * 1e3, 2), "TFLOPs": round(f2 / ms / 1e9, 1),
@@ -181,7 +210,7 @@ def main():
             ids, gates = torch.from_numpy(ids_np).to(dev), torch.from_numpy(gates_np).to(dev)
             Ym = torch.empty((mc.T, mc.H), dtype=torch.float16, device=dev)
             wsm = api.new_workspace(layer.workspace_bytes(mc.T, ids.shape[1]), dev)
-            ms, _ = time_steps(lambda i: layer.forward(Xm, ids, gates, out=Ym, workspace=wsm), 30, 1, 3)
+            ms, _ = time_steps(lambda i: layer.forward(Xm, ids, gates, out=Ym, workspace=wsm), 30, 10, 10)
             ms /= 30
             pairs = np.bincount(ids_np.reshape(-1), minlength=mc.E + mc.n_shared)
             fl = sum(2.0 * int(pairs[e]) * (3 * mc.H * mc.F + 3 * ranks[e] * (mc.H + mc.F))
@@ -193,7 +222,7 @@ def main():
         result["extra"] = extra
 
     if not args.no_cpu_baseline:
-        # The fp64 oracle on the host cores, on the same c1 workload (one full call at M = 16):
+        # The fp64 oracle on the host cores, on the same c1 workload (full calls at M = 16):
         # dequantize + X W_dq^T + (X V^T) U^T.  A reported baseline, not a target.
         import oracle
         try:
@@ -206,17 +235,18 @@ def main():
         U = pw.U.cpu().numpy()
         V = pw.V.cpu().numpy()
         Xh = wl.gen_activations(16, case.K, case.seed)
-        best = None
-        for _ in range(3):
-            t0 = time.perf_counter()
+        calls, t0 = 0, time.perf_counter()
+        while True:
             oracle.w3lr_linear(Xh, q, s, z, U, V)
-            dt = time.perf_counter() - t0
-            best = dt if best is None else min(best, dt)
-        result["cpu_baseline"] = {"value": round(wbytes / best / 1e9, 4), "unit": "GB/s",
+            calls += 1
+            total = time.perf_counter() - t0
+            if total >= args.cpu_seconds or calls >= 1000:
+                break
+        result["cpu_baseline"] = {"value": round(wbytes * calls / total / 1e9, 4), "unit": "GB/s",
                                   "cores": int(blas_threads), "kind": "oracle",
-                                  "sample": "one full c1 call at M=16 (fp64 dequantize + GEMM + "
-                                            "low-rank term), best of 3",
-                                  "seconds_per_call": round(best, 4)}
+                                  "sample": f"{calls} full c1 calls at M=16 (fp64 dequantize + GEMM "
+                                            f"+ low-rank term) in {total:.1f} s, mean rate",
+                                  "seconds_per_call": round(total / calls, 4)}
     print(json.dumps(result))
 
 

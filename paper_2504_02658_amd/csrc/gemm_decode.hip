@@ -241,43 +241,75 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
 
             // ------------------------------------------------------------ reduce + low rank + store
             __syncthreads();                                       // everyone is done with the slots
-            f32x4* red = reinterpret_cast<f32x4*>(smem);          // [wave][block][lane]
+            f32x4* red = reinterpret_cast<f32x4*>(smem);          // [wave][block][lane], <= 32 KB
+            u32x4* tbuf = reinterpret_cast<u32x4*>(smem + 64 * 1024);   // T fragments [k-step][lane]
+            constexpr int KS = 4;                   // k-steps of 32 kept as fragments (r <= 128)
+            const bool fast = r > 0 && (r & 7) == 0 && r <= 32 * KS;
 #pragma unroll
             for (int b = 0; b < R; ++b) red[(wave * R + b) * 64 + lane] = acc[b];
-            if (r > 0 && !t_seen) {
-                if (tid == 0)
-                    while (__hip_atomic_load(a.ctrl + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u)
-                        __builtin_amdgcn_s_sleep(1);
-                t_seen = true;
-            }
             __syncthreads();
+            f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+            f16x8 uf[KS];
+            if (wave == kDecWaves - 1 && r > 0) {
+                // One wave fetches T for the whole workgroup: T is written by the worker workgroups
+                // during this launch, so it is read with device-coherent loads, after its flag has
+                // been seen up, and handed to the others through LDS.
+                if (!t_seen) {
+                    for (uint32_t spins = 0;
+                         __hip_atomic_load(a.ctrl + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u; ++spins) {
+                        __builtin_amdgcn_s_sleep(1);
+                        if (spins > (1u << 24)) { atomicOr(a.ctrl + 3, 1u); break; }
+                    }
+                }
+                if (fast) {
+                    const BufRsrc tb = make_rsrc(a.T, (uint64_t)16 * a.ldt * 2u);
+#pragma unroll
+                    for (int i = 0; i < KS; ++i) {
+                        const int k0 = 32 * i + 8 * q;
+                        tbuf[i * 64 + lane] =
+                            buf_load16_coherent(tb, (k0 < a.ldt) ? (uint32_t)((j16 * a.ldt + k0) * 2) : kOobOffset);
+                    }
+                }
+            }
+            t_seen = true;
+            if (wave < R) {
+                // wave b finishes row block b: sum of the eight waves' partials in wave order, with
+                // the U rows of the block requested first so that their latency overlaps the sum
+                const int b = wave;
+                const int64_t nrow = n0 + 16 * b + j16;
+                if (fast) {
+                    const BufRsrc ub = make_rsrc(a.w.U, (uint64_t)N * (uint64_t)r * 2u);
+#pragma unroll
+                    for (int i = 0; i < KS; ++i) {
+                        const int k0 = 32 * i + 8 * q;
+                        uf[i] = __builtin_bit_cast(
+                            f16x8, buf_load16(ub, (nrow < N && k0 < r) ? (uint32_t)((nrow * r + k0) * 2) : kOobOffset));
+                    }
+                }
+                f32x4 part[kDecWaves];
+#pragma unroll
+                for (int pw = 0; pw < kDecWaves; ++pw) part[pw] = red[(pw * R + b) * 64 + lane];
+                sum = part[0];
+#pragma unroll
+                for (int pw = 1; pw < kDecWaves; ++pw)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) sum[e] += part[pw][e];
+            }
+            __syncthreads();                                       // T fragments are in LDS
             if (wave < R) {
                 const int b = wave;
-                f32x4 sum = red[b * 64 + lane];
-#pragma unroll
-                for (int pw = 1; pw < kDecWaves; ++pw) {
-                    const f32x4 v = red[(pw * R + b) * 64 + lane];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) sum[e] += v[e];
-                }
                 const int64_t nb = n0 + 16 * b;
                 const int64_t nrow = nb + j16;
-                if (r > 0) {
-                    const BufRsrc ub = make_rsrc(a.w.U, (uint64_t)N * (uint64_t)r * 2u);
+                if (fast) {
+#pragma unroll
+                    for (int i = 0; i < KS; ++i)
+                        if (32 * i < r) sum = mfma16(uf[i], __builtin_bit_cast(f16x8, tbuf[i * 64 + lane]), sum);
+                } else if (r > 0) {
                     const BufRsrc tb = make_rsrc(a.T, (uint64_t)16 * a.ldt * 2u);
-                    const bool fast = (r & 7) == 0;
                     for (int ks = 0; ks < r; ks += 32) {
                         const int k0 = ks + 8 * q;
-                        f16x8 av;
-                        if (fast) {
-                            av = __builtin_bit_cast(
-                                f16x8, buf_load16(ub, (nrow < N && k0 < r) ? (uint32_t)((nrow * r + k0) * 2)
-                                                                           : kOobOffset));
-                        } else {
-                            av = zero_f16x8();
-                            if (nrow < N) av = load_row8(a.w.U + nrow * r, k0, r, false);
-                        }
-                        // T was written by another workgroup during this launch: read it coherently
+                        f16x8 av = zero_f16x8();
+                        if (nrow < N) av = load_row8(a.w.U + nrow * r, k0, r, (r & 7) == 0);
                         const f16x8 bv = __builtin_bit_cast(
                             f16x8,
                             buf_load16_coherent(tb, k0 < a.ldt ? (uint32_t)((j16 * a.ldt + k0) * 2) : kOobOffset));
