@@ -99,11 +99,12 @@ int milo_dequant_w3(const void* q3, const milo_half* scales, const milo_half* ze
                     int64_t N, int64_t K, milo_half* W_dq, void* stream);
 
 /*
- * Prepare a freshly allocated workspace (for milo_w3lr_gemm or milo_moe_w3lr_forward): clears the
- * 256-byte control block at its start with a small fill kernel on `stream`.  Call it once after
- * allocating the workspace and again after a call on it returned an error; the kernels leave the
- * control block cleared when they finish, so successive calls need no further preparation and no
- * memset (which makes them safe to capture in a HIP graph and replay).
+ * Prepare a freshly allocated workspace (for milo_w3lr_gemm or milo_moe_w3lr_forward): zero-fills
+ * all `workspace_bytes` with a small fill kernel on `stream` (the kernels synchronise through
+ * counters and flags in it that must start at zero).  Call it once after allocating the workspace
+ * and again after a call on it returned an error or reported a wait that gave up; the kernels leave
+ * their counters and flags cleared when they finish, so successive calls need no further
+ * preparation and no memset (which makes them safe to capture in a HIP graph and replay).
  * Errors: NULL, WORKSPACE (fewer than 256 bytes), ALIGN, HIP.
  */
 int milo_workspace_init(void* workspace, size_t workspace_bytes, void* stream);

@@ -496,87 +496,6 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// T = X V^T, fp16 [rows x ldt], columns >= r written as zero up to the next multiple of 16.
-// One workgroup per 32 rows and weight; its four waves split K (k-step 16*w, 16*(w+4), ...)
-// and are summed in a fixed order through LDS.  Ranks are processed 128 at a time.
-__global__ __launch_bounds__(kTiledThreads) void t_kernel(const TArgs a) {
-    __shared__ __attribute__((aligned(16))) float red[4][64][16];
-
-    const int s = blockIdx.x;                 // weight stream
-    const TileInfo ti = resolve_tile<2>(a.rs, blockIdx.y, a.bm);
-    if (!ti.valid) return;
-    const int sub0 = 32 * blockIdx.z;
-    const int rows = ti.rows - sub0 < 32 ? ti.rows - sub0 : 32;
-    if (rows <= 0) return;
-    const WeightDev w = (s == 0) ? ti.w[0] : ti.w[1];
-    const int r = w.r;
-    if (r <= 0) return;
-    const int rpad = (r + 15) & ~15;
-
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int i32 = lane & 31, h = lane >> 5;
-    const int64_t K = a.K;
-    const int64_t R0 = (int64_t)ti.row0 + sub0;
-    const f16* xrow = (i32 < rows) ? a.X + input_row(a.rs, R0 + i32) * a.ldx : nullptr;
-    f16* Tm = (s == 0) ? a.T[0] : a.T[1];
-
-    for (int jc = 0; jc < r; jc += 128) {
-        const int left = r - jc;
-        const int nb = left >= 128 ? 4 : (left + 31) / 32;
-        f32x16 acc[4];
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[b][v] = 0.0f;
-        const f16* vrow[4];
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int j = jc + 32 * b + i32;
-            vrow[b] = (j < r) ? w.V + (int64_t)j * K : nullptr;
-        }
-        for (int64_t k0 = 16 * wave; k0 < K; k0 += 64) {
-            const int64_t k = k0 + 8 * h;
-            const f16x8 bv = xrow ? load_f16x8(xrow + k) : zero_f16x8();
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                if (b < nb) {
-                    const f16x8 av = vrow[b] ? load_f16x8(vrow[b] + k) : zero_f16x8();
-                    acc[b] = mfma32(av, bv, acc[b]);
-                }
-            }
-        }
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            if (b >= nb) continue;
-            __syncthreads();
-#pragma unroll
-            for (int v = 0; v < 16; ++v) red[wave][lane][v] = acc[b][v];
-            __syncthreads();
-            // thread (wave, lane) sums quarter vq = wave of D: rank 32b + 8*wave + 4h + e, row i32
-            f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-            for (int p = 0; p < 4; ++p)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) sum[e] += red[p][lane][4 * wave + e];
-            const int j = jc + 32 * b + 8 * wave + 4 * h;
-            if (i32 < rows && j < rpad) {
-                f16x4 o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (f16)sum[e];
-                *reinterpret_cast<f16x4*>(Tm + (R0 + i32) * a.ldt + j) = o;
-            }
-        }
-    }
-}
-
-int launch_t_kernel(const TArgs& a, int nw, int m_tiles, hipStream_t stream) {
-    if (m_tiles <= 0) return MILO_OK;
-    dim3 grid((unsigned)nw, (unsigned)m_tiles, (unsigned)(a.bm / 32));
-    t_kernel<<<grid, dim3(kTiledThreads), 0, stream>>>(a);
-    return launch_status();
-}
-
 template <int NW, int MB, int EPI>
 static int launch_one(const TiledArgs& a, dim3 grid, hipStream_t stream) {
     constexpr int lds = (MB == 4 ? 2 : kTiledStages) * 32 * MB * 256;

@@ -26,7 +26,7 @@ struct TileDesc {
     int32_t pad;
 };
 
-// Row-space conventions shared by the tiled kernel and the T kernel.
+// Row-space conventions of the tiled kernel.
 //   Ungrouped (tiles == nullptr): tile y covers rows [y*BM, min(M, (y+1)*BM)), weights = w[].
 //   Grouped: tile y = tiles[y] if y < *n_tiles (else the workgroup exits); the weights are
 //   experts[tile.expert].{w1,w3,w2}[which[a]].
@@ -59,20 +59,9 @@ struct TiledArgs {
     const float* out_scale;    // EPI 2: factor per output row (nullptr: 1)
 };
 
-struct TArgs {
-    RowSpace rs;
-    const f16* X;
-    int64_t ldx;
-    int64_t K;
-    f16* T[2];
-    int64_t ldt;
-    int bm;             // rows per tile of the row space (multiple of 32)
-};
-
 enum { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_SCALE_SCATTER = 2 };
 
 // Launchers.  mb = tile rows / 32 (1, 2 or 4); m_tiles = grid extent over tiles.
-int launch_t_kernel(const TArgs& a, int nw, int m_tiles, hipStream_t stream);
 int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipStream_t stream);
 
 constexpr int kDecMaxSlices = 32;   // K-slices of T = X V^T in the decode kernel
