@@ -49,7 +49,7 @@ static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
 
 extern "C" size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int r) {
     if (!gemm_shape_ok(M, N, K) || r < 0) return 0;
-    if (M <= 16) return decode_workspace_bytes(r);
+    if (M <= 16) return decode_workspace_bytes(r, K);
     // control words | two flag words per 32-row tile | T = X V^T as fp16 [M x pad16(r)]
     return 256 + align_up((size_t)((M + 31) / 32) * 8, 256) +
            align_up((size_t)M * (size_t)rank_pad(r) * 2 + 256, 256);

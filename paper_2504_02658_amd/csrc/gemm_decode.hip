@@ -18,14 +18,14 @@
 // quad read 16 rows.  A slot is written and read by one wave only, so the main loop takes no
 // barrier; the waves' partial sums are added in a fixed order at the very end.
 //
-// Low-rank term.  The first `nt` workgroups do no streaming: each computes one K-slice of
-// T = X V^T (fp32 partial in the workspace); whichever of them finishes last adds the partials in
-// slice order (so the result does not depend on which one that was), writes T as fp16 and
-// raises a flag.  The streaming workgroups only need T in their epilogue, where they add T U^T
-// with a few more MFMAs.  The workers never wait for anything, they have the lowest workgroup
-// ids, and the grid never exceeds what the device keeps resident, so the epilogue's wait always
-// ends.  Data that crosses workgroups is written and read with device-coherent accesses, and
-// the last workgroup to leave restores the control words to zero for the next launch.
+// Low-rank term.  The first `nt` workgroups do no streaming: each computes whole blocks of 16
+// ranks of T = X V^T over all of K (so no sum crosses workgroups), writes them as fp16 and is
+// counted.  The streaming workgroups only need T in their epilogue, where they add T U^T with a
+// few more MFMAs once all workers have been counted.  The workers never wait for anything, they
+// have the lowest workgroup ids, and the grid never exceeds what the device keeps resident, so the
+// epilogue's wait always ends.  Data that crosses workgroups is written and read with
+// device-coherent accesses, and the last workgroup to leave restores the control words to zero
+// for the next launch.
 #include <stdlib.h>
 
 #include "milo_host.h"
@@ -38,7 +38,6 @@ constexpr int kDecThreads = 64 * kDecWaves;
 constexpr int kDecPiece = 16;                               // chunks of 256 k staged at a time
 constexpr int kDecSlotBytes = 16 * 512;                     // one chunk of X: 16 rows x 256 k
 constexpr int kDecLdsBytes = kDecPiece * kDecSlotBytes;     // 128 KB
-constexpr int kDecRankPass = 128;       // ranks a T worker handles per pass (8 MFMA blocks)
 
 __device__ __forceinline__ void buf_store16_coherent(BufRsrc r, uint32_t off, u32x4 v) {
     __builtin_amdgcn_raw_buffer_store_b128(v, r, off, 0, 17);
@@ -49,182 +48,225 @@ __device__ __forceinline__ void buf_store8_coherent(BufRsrc r, uint32_t off, u32
 typedef __attribute__((address_space(3))) void* LdsPtr;
 
 
-// One K-slice of T = X V^T, then (last arriver only) the sum over slices.
+// T worker.  Work item (jb, h) = rank block jb (16 ranks) over K part h (kDecWaves chunks of 256
+// columns, one per wave): T_h[m][j] = sum over the part of X[m][k] V[j][k].  The parts are NOT
+// added up: the streaming workgroups multiply every T_h with U, which gives the same sum without
+// a reduction across workgroups.  Both operands are staged like the activations of the main
+// path (coalesced 1-KB buffer-to-LDS copies into a wave-private slot, xor-swizzled), and all
+// copies of an item are requested at once: the streaming workgroups fill the memory system's
+// queues within a microsecond of the launch, and a request made later waits behind all of theirs.
 __device__ __forceinline__ void decode_t_worker(const DecodeArgs& a, unsigned char* smem) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int j16 = lane & 15, q = lane >> 4;
     const int M = a.M, r = a.w.r;
-    const int64_t K = a.K;
-    const BufRsrc xb = make_rsrc(a.X, (uint64_t)M * (uint64_t)K * 2u);
-    const BufRsrc vb = make_rsrc(a.w.V, (uint64_t)r * (uint64_t)K * 2u);
-    const BufRsrc pb = make_rsrc(a.t_partial, (uint64_t)a.nt * a.rblocks * 64 * 16);
-    const BufRsrc tb = make_rsrc(a.T, (uint64_t)16 * a.ldt * 2u);
-    const int64_t k_lo = (int64_t)blockIdx.x * a.slice;
-    const int64_t k_hi = (k_lo + a.slice < K) ? k_lo + a.slice : K;
-    f32x4* red = reinterpret_cast<f32x4*>(smem);            // [wave][8 blocks][64 lanes] = 128 KB
+    const uint32_t K = (uint32_t)a.K;
+    const BufRsrc xb = make_rsrc(a.X, (uint64_t)M * K * 2u);
+    const BufRsrc vb = make_rsrc(a.w.V, (uint64_t)r * K * 2u);      // < 4 GiB (checked on the host)
+    const BufRsrc tb = make_rsrc(a.T, (uint64_t)a.kh * 16u * (uint64_t)a.ldt * 2u);
+    unsigned char* const xs = smem + wave * 2 * kDecSlotBytes;      // X chunk, then V chunk
+    unsigned char* const vs = xs + kDecSlotBytes;
+    f32x4* const red = reinterpret_cast<f32x4*>(smem);              // [wave][64 lanes], after a barrier
+    const uint32_t crow = (uint32_t)lane >> 5, cp = (uint32_t)lane & 31u;
+    const uint32_t xseg = (cp ^ crow) << 4;
+    const uint32_t xrow = crow * 2u * K;
 
-    for (int jp = 0; jp < r; jp += kDecRankPass) {
-        f32x4 tacc[8];
+    for (int item = blockIdx.x; item < a.rblocks * a.kh; item += a.nt) {
+        const int jb = item / a.kh, h = item - jb * a.kh;
+        const uint32_t kc = (uint32_t)(h * kDecWaves + wave) * 256u;
+        const uint32_t lim = (kc >= K) ? 0u : (K - kc >= 256u ? 512u : 2u * (K - kc));
+        const bool ok_lo = (xseg & 0x180u) < lim;
+        const bool ok_hi = ((xseg & 0x180u) ^ 0x80u) < lim;
+        // rows >= M lie past the end of X, rows >= r past the end of V: they read as zero
+        const uint32_t vbase = (uint32_t)(16 * jb) * K * 2u;
 #pragma unroll
-        for (int jb = 0; jb < 8; ++jb) tacc[jb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        const int nblk = (r - jp + 15) / 16 < 8 ? (r - jp + 15) / 16 : 8;
-        // wave w takes the 32-wide k-steps w, w+16, ... of the slice
-        for (int64_t k0 = k_lo + 32 * wave; k0 < k_hi; k0 += 32 * kDecWaves) {
-            const int64_t k = k0 + 8 * q;
-            const f16x8 xv = __builtin_bit_cast(
-                f16x8, buf_load16(xb, j16 < M ? (uint32_t)(((int64_t)j16 * K + k) * 2) : kOobOffset));
-            f16x8 vv[8];
-#pragma unroll
-            for (int jb = 0; jb < 8; ++jb) {
-                // rows >= r lie past the end of V and read as zero
-                const int64_t row = jp + 16 * jb + j16;
-                vv[jb] = __builtin_bit_cast(
-                    f16x8, buf_load16(vb, jb < nblk ? (uint32_t)((row * K + k) * 2) : kOobOffset));
-            }
-#pragma unroll
-            for (int jb = 0; jb < 8; ++jb)
-                if (jb < nblk) tacc[jb] = mfma16(vv[jb], xv, tacc[jb]);
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t off = ((xseg ^ (32u * i)) + xrow) + (4u * i * K + 2u * kc);
+            const bool ok = i < 4 ? ok_lo : ok_hi;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (LdsPtr)(xs + i * 1024), 16, ok ? off : kOobOffset, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(vb, (LdsPtr)(vs + i * 1024), 16, ok ? off + vbase : kOobOffset, 0,
+                                                     0, 0);
         }
-        __syncthreads();
+        wait_vmem();
+        f32x4 tacc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int jb = 0; jb < 8; ++jb)
-            if (jb < nblk) red[(wave * 8 + jb) * 64 + lane] = tacc[jb];
+        for (int t = 0; t < 8; ++t) {
+            const int pos = j16 * 512 + (((8 * q + t) ^ j16) << 4);
+            tacc = mfma16(__builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(vs + pos)),
+                          __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4*>(xs + pos)), tacc);
+        }
+        __syncthreads();                                    // every wave has read its slots
+        red[wave * 64 + lane] = tacc;
         __syncthreads();
-        // partial[slice][rank block][lane] keeps the MFMA D layout:
-        // element v of lane l = rank 16*jb + 4*(l/16) + v, token l%16.
-        const uint32_t pbase = (uint32_t)(((int64_t)blockIdx.x * a.rblocks + jp / 16) * 64 * 16);
-        for (int e = tid; e < nblk * 64; e += kDecThreads) {
-            f32x4 sum = red[e];
+        if (wave == 0) {
+            f32x4 sum = red[lane];
 #pragma unroll
             for (int p = 1; p < kDecWaves; ++p) {
-                const f32x4 v = red[p * 8 * 64 + e];
+                const f32x4 v = red[p * 64 + lane];
 #pragma unroll
                 for (int x = 0; x < 4; ++x) sum[x] += v[x];
             }
-            buf_store16_coherent(pb, pbase + (uint32_t)e * 16u, __builtin_bit_cast(u32x4, sum));
-        }
-    }
-    // all partial stores of this workgroup are complete before it is counted
-    wait_vmem();
-    __syncthreads();
-    int last = 0;
-    if (tid == 0) last = (atomicAdd(a.ctrl + 0, 1u) == (uint32_t)a.nt - 1u) ? 1 : 0;
-    if (!__syncthreads_or(last)) return;
-
-    // Last slice to arrive: add the partials in slice order and write T as fp16 [16 x ldt].
-    // All loads of a batch of entries are issued together, then summed through LDS.
-    const int entries = a.rblocks * 64;
-    const int per_batch = (kDecLdsBytes / 16) / a.nt;        // entries whose nt partials fit in LDS
-    for (int e0 = 0; e0 < entries; e0 += per_batch) {
-        const int ne = (entries - e0) < per_batch ? (entries - e0) : per_batch;
-        __syncthreads();
-        for (int i = tid; i < ne * a.nt; i += kDecThreads) {
-            const int s = i / ne, e = i - s * ne;
-            red[i] = __builtin_bit_cast(
-                f32x4, buf_load16_coherent(pb, (uint32_t)((((int64_t)s * a.rblocks) * 64 + e0 + e) * 16)));
-        }
-        __syncthreads();
-        for (int e = tid; e < ne; e += kDecThreads) {
-            f32x4 sum = red[e];
-            for (int s = 1; s < a.nt; ++s) {
-                const f32x4 v = red[s * ne + e];
-#pragma unroll
-                for (int x = 0; x < 4; ++x) sum[x] += v[x];
-            }
-            const int jb = (e0 + e) >> 6, l = (e0 + e) & 63;
+            // element v of lane l = rank 16*jb + 4*(l/16) + v, token l%16
             f16x4 o;
 #pragma unroll
             for (int x = 0; x < 4; ++x) o[x] = (f16)sum[x];
-            buf_store8_coherent(tb, (uint32_t)(((l & 15) * a.ldt + 16 * jb + 4 * (l >> 4)) * 2),
+            buf_store8_coherent(tb, (uint32_t)(((h * 16 + j16) * a.ldt + 16 * jb + 4 * q) * 2),
                                 __builtin_bit_cast(u32x2, o));
         }
+        __syncthreads();                                    // red is read before the slots are refilled
     }
+    // all T stores of this workgroup are complete before it is counted
     wait_vmem();
     __syncthreads();
-    if (tid == 0) __hip_atomic_store(a.ctrl + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) atomicAdd(a.ctrl + 0, 1u);
 }
 
-template <int R>
+// Bounded wait until every T worker has been counted; a wait that gives up sets an error word.
+__device__ __forceinline__ void decode_wait_t(const DecodeArgs& a) {
+    for (uint32_t spins = 0;
+         __hip_atomic_load(a.ctrl + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)a.nt; ++spins) {
+        __builtin_amdgcn_s_sleep(1);
+        if (spins > (1u << 24)) {
+            atomicOr(a.ctrl + 3, 1u);
+            break;
+        }
+    }
+}
+
+// LR: 0 = no low-rank term, 1 = rank a multiple of 8 and at most 128 (U fragments are copied into
+// LDS at the start of the kernel, T comes through LDS), 2 = any other rank (plain loads).
+constexpr int kDecKS = 4;                                       // k-steps of 32 ranks, LR == 1
+constexpr int kDecULds = kDecLdsBytes;                          // U fragments [R][kDecKS][64] x 16 B
+constexpr int kDecTLds = kDecULds + 4 * kDecKS * 1024;          // T fragments [kDecTFrags][64] x 16 B
+constexpr int kDecTFrags = 8;                                   // (K parts) x (k-steps used) at most, LR == 1
+constexpr int kDecLdsTotal = kDecTLds + kDecTFrags * 1024;      // 152 KB
+
+template <int R, int LR>
 __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int j16 = lane & 15, q = lane >> 4;
-    const int M = a.M;
-    const int64_t N = a.N, K = a.K;
-    const int G = (int)(K / kGroup);
-    const int nchunks = (G + 3) / 4;
-    const int npieces = (nchunks + kDecPiece - 1) / kDecPiece;
-    const int r = a.w.r;
-    const int nworkers = r > 0 ? a.nt : 0;
-    constexpr int ROWS = 16 * R;                // output features per workgroup
-    constexpr int CPW = kDecPiece / kDecWaves;  // chunks of a piece per wave
-
-    if ((int)blockIdx.x < nworkers) {
+    const int nworkers = LR > 0 ? a.nt : 0;
+    if (LR > 0 && (int)blockIdx.x < nworkers) {
         decode_t_worker(a, smem);
     } else {
-        const W3Buf wb = make_w3buf(a.w.q3, a.w.scales, a.w.zeros, N, K);
-        const BufRsrc xb = make_rsrc(a.X, (uint64_t)M * (uint64_t)K * 2u);
+        constexpr int CPW = kDecPiece / kDecWaves;  // chunks of a piece per wave
+        const int j16 = lane & 15, q = lane >> 4;
+        const int M = a.M;
+        const uint32_t K = (uint32_t)a.K;                   // < 2^27 (checked on the host)
+        const uint32_t G = K / kGroup;
+        const uint32_t NB = (uint32_t)(a.N >> 4);           // 16-row blocks
+        const uint32_t nchunks = (G + 3) / 4;
+        const uint32_t npieces = (nchunks + kDecPiece - 1) / kDecPiece;
+        const int r = a.w.r;
+        const W3Buf wb = make_w3buf(a.w.q3, a.w.scales, a.w.zeros, a.N, a.K);
+        const BufRsrc xb = make_rsrc(a.X, (uint64_t)M * K * 2u);
         // Staging: copy i of a chunk moves rows 2i, 2i+1: lane l -> row 2i + l/32, slot position
         // p = l%32, which receives segment p ^ row of the row's 32 segments of 8 columns.
-        const int crow = lane >> 5, cp = lane & 31;
-        const int rot = (int)(blockIdx.x * 5u) & (kDecPiece - 1);
-        bool t_seen = false;        // this workgroup has already waited for T
-
-        for (int64_t blk = (int64_t)blockIdx.x - nworkers; blk * ROWS < N;
-             blk += (int64_t)gridDim.x - nworkers) {
-            const int64_t n0 = blk * ROWS;
-            uint32_t ubase[R];
+        // Byte offset of that segment = row*2K + 16*(p ^ row) + 2*kc, split into a per-lane part
+        // that does not depend on i (the xor with 2i is applied to the segment bits) and a
+        // uniform part.  Rows >= M lie past the end of X and read as zero.
+        const uint32_t crow = (uint32_t)lane >> 5, cp = (uint32_t)lane & 31u;
+        const uint32_t xseg = (cp ^ crow) << 4;
+        const uint32_t xrow = crow * 2u * K;
+        const uint32_t rot = (blockIdx.x * 5u) & (kDecPiece - 1);
+        bool t_fetched = false;     // T is (being) copied into this workgroup's LDS
+        // Tells worker 0 that this workgroup needs the control words and T no more.
+        auto sign_off = [&]() {
+            if (lane == 0)
+                __hip_atomic_store(a.done + (blockIdx.x - nworkers), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        };
+        const BufRsrc tb = make_rsrc(a.T, (uint64_t)a.kh * 16u * (uint64_t)a.ldt * 2u);
+        const int ksu = (r + 31) >> 5;                  // k-steps of 32 ranks in use
+        const int nfrag = a.kh * ksu;                   // T fragments: K part h, k-step i -> h * ksu + i
+        // Copies T (device-coherent reads: the workers wrote it during this launch) into LDS as
+        // MFMA B fragments; only to be called once all workers have been seen done.
+        auto fetch_t = [&]() {
+            int h = 0, i = 0;
 #pragma unroll
-            for (int b = 0; b < R; ++b) {
-                const int64_t n = n0 + 16 * b + j16;
-                ubase[b] = (n < N) ? (uint32_t)unit_index(n, 0, G) : kOobUnit;
+            for (int f = 0; f < kDecTFrags; ++f) {
+                if (f < nfrag) {
+                    const int k0 = 32 * i + 8 * q;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        tb, (LdsPtr)(smem + kDecTLds + f * 1024), 16,
+                        (k0 < a.ldt) ? (uint32_t)(((h * 16 + j16) * a.ldt + k0) * 2) : kOobOffset, 0, 0, 17);
+                    if (++i == ksu) { i = 0; ++h; }
+                }
             }
+        };
+        unsigned char* const myslot = smem + wave * kDecSlotBytes;      // slot of chunk ci: + 8*ci slots
+
+        for (uint32_t blk = blockIdx.x - nworkers; blk * R < NB; blk += gridDim.x - nworkers) {
+            const uint32_t rb0 = blk * R;
             f32x4 acc[R];
 #pragma unroll
             for (int b = 0; b < R; ++b) acc[b] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-            for (int p = 0; p < npieces; ++p) {
-                // This wave's two chunks of the piece.  For each: its activations go straight from L2
-                // into the wave's LDS slot (buffer-to-LDS copies, no registers), then its weights
-                // are loaded; lane quad q takes group 4c + q of chunk c.  The chunk order is rotated
-                // per workgroup so that the workgroups, which all read the same X, do not walk the
-                // same L2 channels in step.
+            for (uint32_t p = 0; p < npieces; ++p) {
+                // This wave's two chunks of the piece, everything requested up front: for each chunk
+                // the weights first (one unit per lane and row block: the 64 lanes of the wave read
+                // 64 consecutive units, lane quad q being group 4c + q), then its activations, which
+                // go straight from L2 into the wave's LDS slot.  The chunk order is rotated per
+                // workgroup so that the workgroups, which all read the same X, do not walk the same
+                // L2 channels in step.  A lane or block without data gets a unit index past the end.
                 RawUnit u[CPW][R];
+                uint32_t workers_done = 0;
 #pragma unroll
                 for (int ci = 0; ci < CPW; ++ci) {
-                    const int cw = (wave + kDecWaves * ci + rot) & (kDecPiece - 1);   // chunk within the piece
-                    const int64_t kc = ((int64_t)p * kDecPiece + cw) * 256;
+                    const uint32_t cw = (wave + kDecWaves * ci + rot) & (kDecPiece - 1);
+                    const uint32_t chunk = p * kDecPiece + cw;
+                    const uint32_t kc = chunk * 256u;
+                    // (an index >= 2^26 is past the end of every weight the host accepts, and the
+                    // sum of the two parts stays below 2^28, so 16 * index does not wrap)
+                    const uint32_t lane_u = (4u * chunk + (uint32_t)q < G) ? (uint32_t)lane : (1u << 26);
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int row = 2 * i + crow;
-                        const int seg = cp ^ row;
-                        const bool in = row < M && kc + seg * 8 < K;
-                        const uint32_t off = in ? (uint32_t)(((int64_t)row * K + kc + seg * 8) * 2) : kOobOffset;
-                        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                            xb, (LdsPtr)(smem + (wave + kDecWaves * ci) * kDecSlotBytes + i * 1024), 16, off, 0, 0,
-                            0);
+                    for (int b = 0; b < R; ++b) {
+                        const uint32_t base = (rb0 + b < NB) ? ((rb0 + b) * G + 4u * chunk) * 16u : (1u << 27);
+                        u[ci][b] = load_unit_buf(wb, base + lane_u);
                     }
                     asm volatile("" ::: "memory");
-                    const int g = 4 * (p * kDecPiece + cw) + q;
+                    if (LR == 1 && ci == 0 && p == 0 && wave < R) {
+                        // U rows of row block `wave` as MFMA A fragments, copied into LDS now so
+                        // that the epilogue finds them there: k-step i, lane (j16, q) = U[n][32i + 8q ..].
+                        const BufRsrc ub = make_rsrc(a.w.U, (uint64_t)a.N * (uint64_t)r * 2u);
+                        const uint32_t nrow = (rb0 + wave) * 16u + j16;
 #pragma unroll
-                    for (int b = 0; b < R; ++b)
-                        u[ci][b] = load_unit_buf(wb, (g < G && ubase[b] != kOobUnit) ? ubase[b] + (uint32_t)g * 16u
-                                                                                      : kOobUnit);
+                        for (int i = 0; i < kDecKS; ++i) {
+                            const uint32_t k0 = 32u * i + 8u * q;
+                            const uint32_t off = (rb0 + wave < NB && k0 < (uint32_t)r) ? (nrow * r + k0) * 2u : kOobOffset;
+                            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                                ub, (LdsPtr)(smem + kDecULds + (wave * kDecKS + i) * 1024), 16, off, 0, 0, 0);
+                        }
+                        asm volatile("" ::: "memory");
+                    }
+                    unsigned char* const slot = myslot + kDecWaves * ci * kDecSlotBytes;
+                    // A chunk that reaches beyond K (the last one when K is not a multiple of 256, or
+                    // one past the end) must not wrap into the next row: only the first `lim` bytes
+                    // of its 512-byte row pieces exist.  lim is a multiple of 128, so whether a
+                    // lane's segment exists depends on its 128-byte quarter only, which the xor
+                    // with 2i changes for i >= 4.
+                    const uint32_t lim = (kc >= K) ? 0u : (K - kc >= 256u ? 512u : 2u * (K - kc));
+                    const bool ok_lo = (xseg & 0x180u) < lim;
+                    const bool ok_hi = ((xseg & 0x180u) ^ 0x80u) < lim;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const uint32_t off = ((xseg ^ (32u * i)) + xrow) + (4u * i * K + 2u * kc);
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (LdsPtr)(slot + i * 1024), 16,
+                                                                 (i < 4 ? ok_lo : ok_hi) ? off : kOobOffset, 0, 0, 0);
+                    }
                     asm volatile("" ::: "memory");
                 }
 #pragma unroll
                 for (int ci = 0; ci < CPW; ++ci) {
                     // Vector memory operations complete in order: once at most the operations issued
-                    // after this chunk's copies are outstanding (its R*4 weight loads and everything
-                    // of the later chunks), the copies have landed in LDS.  The slot is private to
+                    // after this chunk's copies are outstanding (everything of the later chunks), its
+                    // weights have arrived and its copies have landed in LDS.  The slot is private to
                     // the wave, so no barrier is involved.  (The count relies on the compiler adding
                     // no memory operation of its own in between; the build script checks that.)
                     if (ci == 0)
-                        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(R * 4 + (CPW - 1) * (8 + R * 4)) : "memory");
+                        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((CPW - 1) * (8 + R * 4)) : "memory");
                     else
-                        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(R * 4) : "memory");
-                    const unsigned char* slot = smem + (wave + kDecWaves * ci) * kDecSlotBytes;
+                        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    const unsigned char* slot = myslot + kDecWaves * ci * kDecSlotBytes;
                     f16x8 bfrag[8];
 #pragma unroll
                     for (int t = 0; t < 8; ++t)
@@ -232,114 +274,141 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
                             f16x8,
                             *reinterpret_cast<const u32x4*>(slot + j16 * 512 + (((8 * q + t) ^ j16) << 4)));
 #pragma unroll
-                    for (int b = 0; b < R; ++b)
+                    for (int b = 0; b < R; ++b) {
                         dequant_unit_steps(u[ci][b], [&](int t, f16x8 frag) {
                             acc[b] = mfma16(frag, bfrag[t], acc[b]);
                         });
+                        // The wave that will hand T to the others looks for it while it still has
+                        // work (reads of data written during the launch cross the whole chip and
+                        // take a microsecond each): of the S units it converts, it requests the
+                        // count of finished workers after unit P1, looks at it two units later and,
+                        // if all are done, starts the copy of T into LDS, which then runs under the
+                        // remaining units; otherwise it asks once more.
+                        constexpr int S = CPW * R, P1 = S / 2 - 2 >= 0 ? S / 2 - 2 : 0, E1 = P1 + 2, E2 = E1 + 2;
+                        const int su = ci * R + b;
+                        if (LR == 1 && wave == kDecWaves - 1 && p == npieces - 1 && !t_fetched) {
+                            if (su == P1 && E1 < S)
+                                workers_done = __hip_atomic_load(a.ctrl + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            if ((su == E1 && E1 < S) || (su == E2 && E2 < S)) {
+                                if (__builtin_amdgcn_readfirstlane(workers_done) >= (uint32_t)a.nt) {
+                                    fetch_t();
+                                    t_fetched = true;
+                                    sign_off();
+                                } else if (su == E1 && E2 < S) {
+                                    workers_done =
+                                        __hip_atomic_load(a.ctrl + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                }
+                            }
+                        }
+                    }
                 }
             }
 
             // ------------------------------------------------------------ reduce + low rank + store
-            __syncthreads();                                       // everyone is done with the slots
-            f32x4* red = reinterpret_cast<f32x4*>(smem);          // [wave][block][lane], <= 32 KB
-            u32x4* tbuf = reinterpret_cast<u32x4*>(smem + 64 * 1024);   // T fragments [k-step][lane]
-            constexpr int KS = 4;                   // k-steps of 32 kept as fragments (r <= 128)
-            const bool fast = r > 0 && (r & 7) == 0 && r <= 32 * KS;
+            // Each wave leaves its partial sums in its own first slot, which it has finished reading.
+            f32x4* const red = reinterpret_cast<f32x4*>(smem);          // wave w, block b at 512 w + 64 b
+            u32x4* const ulds = reinterpret_cast<u32x4*>(smem + kDecULds);
+            u32x4* const tbuf = reinterpret_cast<u32x4*>(smem + kDecTLds);
 #pragma unroll
-            for (int b = 0; b < R; ++b) red[(wave * R + b) * 64 + lane] = acc[b];
-            __syncthreads();
-            f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
-            f16x8 uf[KS];
-            if (wave == kDecWaves - 1 && r > 0) {
-                // One wave fetches T for the whole workgroup: T is written by the worker workgroups
-                // during this launch, so it is read with device-coherent loads, after its flag has
-                // been seen up, and handed to the others through LDS.
-                if (!t_seen) {
-                    for (uint32_t spins = 0;
-                         __hip_atomic_load(a.ctrl + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u; ++spins) {
-                        __builtin_amdgcn_s_sleep(1);
-                        if (spins > (1u << 24)) { atomicOr(a.ctrl + 3, 1u); break; }
+            for (int b = 0; b < R; ++b) red[wave * (kDecSlotBytes / 16) + b * 64 + lane] = acc[b];
+            if (LR > 0 && wave == kDecWaves - 1) {
+                // One wave gets T for the whole workgroup and hands it over through LDS (LR == 1);
+                // if the early look above did not find the workers done, it waits for them here.
+                if (!t_fetched) {
+                    decode_wait_t(a);
+                    if (LR == 1) {
+                        fetch_t();
+                        sign_off();
                     }
+                    t_fetched = true;
                 }
-                if (fast) {
-                    const BufRsrc tb = make_rsrc(a.T, (uint64_t)16 * a.ldt * 2u);
-#pragma unroll
-                    for (int i = 0; i < KS; ++i) {
-                        const int k0 = 32 * i + 8 * q;
-                        tbuf[i * 64 + lane] =
-                            buf_load16_coherent(tb, (k0 < a.ldt) ? (uint32_t)((j16 * a.ldt + k0) * 2) : kOobOffset);
-                    }
-                }
+                wait_vmem();
             }
-            t_seen = true;
+            __syncthreads();                                       // partial sums and T are in LDS
             if (wave < R) {
-                // wave b finishes row block b: sum of the eight waves' partials in wave order, with
-                // the U rows of the block requested first so that their latency overlaps the sum
+                // wave b finishes row block b: sum of the eight waves' partials in wave order
                 const int b = wave;
-                const int64_t nrow = n0 + 16 * b + j16;
-                if (fast) {
-                    const BufRsrc ub = make_rsrc(a.w.U, (uint64_t)N * (uint64_t)r * 2u);
-#pragma unroll
-                    for (int i = 0; i < KS; ++i) {
-                        const int k0 = 32 * i + 8 * q;
-                        uf[i] = __builtin_bit_cast(
-                            f16x8, buf_load16(ub, (nrow < N && k0 < r) ? (uint32_t)((nrow * r + k0) * 2) : kOobOffset));
-                    }
-                }
                 f32x4 part[kDecWaves];
 #pragma unroll
-                for (int pw = 0; pw < kDecWaves; ++pw) part[pw] = red[(pw * R + b) * 64 + lane];
-                sum = part[0];
+                for (int pw = 0; pw < kDecWaves; ++pw) part[pw] = red[pw * (kDecSlotBytes / 16) + b * 64 + lane];
+                f32x4 sum = part[0];
 #pragma unroll
                 for (int pw = 1; pw < kDecWaves; ++pw)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) sum[e] += part[pw][e];
-            }
-            __syncthreads();                                       // T fragments are in LDS
-            if (wave < R) {
-                const int b = wave;
-                const int64_t nb = n0 + 16 * b;
-                const int64_t nrow = nb + j16;
-                if (fast) {
+                const uint32_t nb = (rb0 + b) * 16u;
+                if (LR == 1) {
+                    int i = 0;
 #pragma unroll
-                    for (int i = 0; i < KS; ++i)
-                        if (32 * i < r) sum = mfma16(uf[i], __builtin_bit_cast(f16x8, tbuf[i * 64 + lane]), sum);
-                } else if (r > 0) {
-                    const BufRsrc tb = make_rsrc(a.T, (uint64_t)16 * a.ldt * 2u);
+                    for (int f = 0; f < kDecTFrags; ++f) {
+                        if (f < nfrag) {
+                            sum = mfma16(__builtin_bit_cast(f16x8, ulds[(b * kDecKS + i) * 64 + lane]),
+                                         __builtin_bit_cast(f16x8, tbuf[f * 64 + lane]), sum);
+                            if (++i == ksu) i = 0;
+                        }
+                    }
+                } else if (LR == 2) {
+                    const int64_t nrow = (int64_t)nb + j16;
                     for (int ks = 0; ks < r; ks += 32) {
                         const int k0 = ks + 8 * q;
                         f16x8 av = zero_f16x8();
-                        if (nrow < N) av = load_row8(a.w.U + nrow * r, k0, r, (r & 7) == 0);
-                        const f16x8 bv = __builtin_bit_cast(
-                            f16x8,
-                            buf_load16_coherent(tb, k0 < a.ldt ? (uint32_t)((j16 * a.ldt + k0) * 2) : kOobOffset));
-                        sum = mfma16(av, bv, sum);
+                        if (nrow < a.N) av = load_row8(a.w.U + nrow * r, k0, r, (r & 7) == 0);
+                        for (int h = 0; h < a.kh; ++h) {
+                            const f16x8 bv = __builtin_bit_cast(
+                                f16x8, buf_load16_coherent(tb, k0 < a.ldt ? (uint32_t)(((h * 16 + j16) * a.ldt + k0) * 2)
+                                                                          : kOobOffset));
+                            sum = mfma16(av, bv, sum);
+                        }
                     }
                 }
                 // D[v]: feature nb + 4q + v, token j16
-                const int64_t n = nb + 4 * q;
-                if (j16 < M && n < N) {
+                const int64_t n = (int64_t)nb + 4 * q;
+                if (j16 < M && n < a.N) {
                     f16x4 o;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) o[e] = (f16)sum[e];
-                    *reinterpret_cast<f16x4*>(a.Y + (int64_t)j16 * N + n) = o;
+                    *reinterpret_cast<f16x4*>(a.Y + (int64_t)j16 * a.N + n) = o;
                 }
             }
-            __syncthreads();        // smem is reused by the next block of this workgroup
+            if (blk + (gridDim.x - nworkers) < (NB + R - 1) / R * 1u) __syncthreads();   // slots are reused
         }
     }
 
-    // Leave: the last workgroup restores the control words for the next launch.  Every streaming
-    // workgroup has read T before it gets here, and every worker has written its share.
-    if (r > 0) {
+    // LR == 2: the streaming workgroups read T from memory in their epilogue, so they sign off last.
+    if (LR == 2 && (int)blockIdx.x >= nworkers) {
         __syncthreads();
-        if (tid == 0) {
-            const uint32_t old = atomicAdd(a.ctrl + 2, 1u);
-            if (old == gridDim.x - 1u) {
-                __hip_atomic_store(a.ctrl + 0, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(a.ctrl + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(a.ctrl + 2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0)
+            __hip_atomic_store(a.done + (blockIdx.x - nworkers), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // Worker 0 stays until every streaming workgroup has signed off (which each does only after
+    // it has seen all workers counted), then restores the control words for the next launch.
+    // With LR == 1 the sign-offs come in the middle of the streaming work, so this wait ends
+    // before the kernel would have ended anyway.  No returning atomic on a shared word is
+    // involved: hundreds of those on one address serialize for several microseconds.
+    if (LR > 0 && blockIdx.x == 0 && wave == 0) {
+        const uint32_t nmain = gridDim.x - (uint32_t)nworkers;
+        bool all = false;
+        for (uint32_t spins = 0; !all; ++spins) {
+            all = true;
+            for (uint32_t base = 0; base < nmain; base += 64) {
+                const uint32_t idx = base + (uint32_t)lane;
+                const uint32_t v =
+                    idx < nmain ? __hip_atomic_load(a.done + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 1u;
+                all = all && (__builtin_amdgcn_ballot_w64(v != 0u) == ~0ull);
             }
+            if (!all) {
+                __builtin_amdgcn_s_sleep(8);
+                if (spins > (1u << 22)) {
+                    atomicOr(a.ctrl + 3, 2u);
+                    break;
+                }
+            }
+        }
+        if (all) {
+            for (uint32_t base = 0; base < nmain; base += 64)
+                if (base + (uint32_t)lane < nmain)
+                    __hip_atomic_store(a.done + base + lane, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0) __hip_atomic_store(a.ctrl + 0, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -347,10 +416,16 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
 // Workgroups the device keeps resident at once (one 512-thread, 128-KB-LDS workgroup per CU),
 // cached per device; also raises the kernels' dynamic LDS limit once.
 typedef void (*DecodeKernel)(const DecodeArgs);
-static DecodeKernel decode_variant(int R) {
-    if (R == 4) return w3lr_decode_kernel<4>;
-    if (R == 2) return w3lr_decode_kernel<2>;
-    return w3lr_decode_kernel<1>;
+template <int LR>
+static DecodeKernel decode_variant_lr(int R) {
+    if (R == 4) return w3lr_decode_kernel<4, LR>;
+    if (R == 2) return w3lr_decode_kernel<2, LR>;
+    return w3lr_decode_kernel<1, LR>;
+}
+static DecodeKernel decode_variant(int R, int lr) {
+    if (lr == 0) return decode_variant_lr<0>(R);
+    if (lr == 1) return decode_variant_lr<1>(R);
+    return decode_variant_lr<2>(R);
 }
 static int decode_capacity() {
     static int cached[64] = {0};
@@ -361,19 +436,23 @@ static int decode_capacity() {
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
         for (int R = 1; R <= 4; R *= 2)
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_variant(R)),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kDecLdsBytes) != hipSuccess)
-                return 0;
+            for (int lr = 0; lr < 3; ++lr)
+                if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_variant(R, lr)),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kDecLdsTotal) != hipSuccess)
+                    return 0;
         cached[dev] = cus;
     }
     return cached[dev];
 }
 
-size_t decode_workspace_bytes(int r) {
+// K parts of the T workers: kDecWaves chunks of 256 columns each.
+static int decode_k_parts(int64_t K) { return (int)((K + 256 * kDecWaves - 1) / (256 * kDecWaves)); }
+
+size_t decode_workspace_bytes(int r, int64_t K) {
     if (r <= 0) return 256;
     const size_t rblocks = ((size_t)r + 15) / 16;
-    // control words | T fp16 [16 x ldt] | partials [kDecMaxSlices][rblocks][64] f32x4
-    return 256 + align_up(16 * rblocks * 16 * 2, 256) + (size_t)kDecMaxSlices * rblocks * 64 * 16;
+    // control words | sign-off words of the streaming workgroups | T fp16 [K parts][16 x ldt]
+    return 256 + kDecDoneBytes + align_up((size_t)decode_k_parts(K) * 16 * rblocks * 16 * 2, 256);
 }
 
 int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream) {
@@ -382,22 +461,21 @@ int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream) {
     const int r = a.w.r;
     a.rblocks = (r + 15) / 16;
     a.ldt = (int64_t)a.rblocks * 16;
+    // V (padded to whole rank blocks) is addressed with 32-bit byte offsets
+    if ((uint64_t)a.ldt * (uint64_t)a.K * 2u >= 0xFFFFFFF0ull) return MILO_ERR_SHAPE;
     char* ws = reinterpret_cast<char*>(workspace);
     a.ctrl = reinterpret_cast<uint32_t*>(ws);
-    a.T = reinterpret_cast<f16*>(ws + 256);
-    a.t_partial = reinterpret_cast<f32x4*>(ws + 256 + align_up((size_t)16 * a.rblocks * 16 * 2, 256));
-    // K-slices of T: about 512 columns each (one 32-wide step per wave of a worker), at most
-    // kDecMaxSlices and never more than a quarter of the resident workgroups
-    int nt = (int)((a.K + 511) / 512);
-    if (nt > kDecMaxSlices) nt = kDecMaxSlices;
+    a.done = reinterpret_cast<uint32_t*>(ws + 256);
+    a.T = reinterpret_cast<f16*>(ws + 256 + kDecDoneBytes);
+    a.kh = decode_k_parts(a.K);
+    // T workers: one per block of 16 ranks and K part, at most kDecMaxWorkers and never more than
+    // a quarter of the resident workgroups (a worker then takes several items in turn)
+    int nt = a.rblocks * a.kh;
+    if (nt > kDecMaxWorkers) nt = kDecMaxWorkers;
     if (nt > cap / 4) nt = cap / 4 > 0 ? cap / 4 : 1;
-    int64_t slice = (a.K + nt - 1) / nt;
-    slice = (slice + 63) / 64 * 64;
-    nt = (int)((a.K + slice - 1) / slice);
     a.nt = nt;
-    a.slice = (int)slice;
     const int workers = r > 0 ? nt : 0;
-    if (cap <= workers) return MILO_ERR_HIP;
+    if (cap <= workers || (size_t)cap * 4 > kDecDoneBytes) return MILO_ERR_HIP;
     // Rows per workgroup (16*R): as many as still leave about one workgroup per CU, because every
     // workgroup stages all of X once.
     int R = 4;
@@ -407,7 +485,10 @@ int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream) {
     const int rows = 16 * R;
     const int64_t blocks = (a.N + rows - 1) / rows;
     const int grid = (int)(blocks < cap - workers ? blocks : cap - workers) + workers;
-    decode_variant(R)<<<dim3((unsigned)grid), dim3(kDecThreads), kDecLdsBytes, stream>>>(a);
+    const bool lds_path = (r & 7) == 0 && r <= 32 * kDecKS && a.kh * ((r + 31) / 32) <= kDecTFrags &&
+                          (uint64_t)a.N * (uint64_t)r * 2u < 0xFFFFFFF0ull;
+    const int lr = r == 0 ? 0 : lds_path ? 1 : 2;
+    decode_variant(R, lr)<<<dim3((unsigned)grid), dim3(kDecThreads), lr == 1 ? kDecLdsTotal : kDecLdsBytes, stream>>>(a);
     return launch_status();
 }
 

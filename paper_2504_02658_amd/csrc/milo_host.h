@@ -17,7 +17,9 @@ inline bool weight_shape_ok(int64_t N, int64_t K) {
     if ((K % 64) != 0 || (N % 16) != 0) return false;
     if (K > (int64_t(1) << 30) || N > (int64_t(1) << 30)) return false;
     if (N > (int64_t(1) << 56) / K) return false;
-    if (N * (K / 64) >= 0x0FFFFFFF) return false;     // units are indexed with 32-bit offsets
+    // units, and the bytes of 16 rows of activations, are addressed with 32-bit offsets; the
+    // kernels mark "no data" with unit indices from 2^26 up
+    if (N * (K / 64) > (int64_t(1) << 26) || K > (int64_t(1) << 26)) return false;
     return true;
 }
 

@@ -64,7 +64,8 @@ enum { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_SCALE_SCATTER = 2 };
 // Launchers.  mb = tile rows / 32 (1, 2 or 4); m_tiles = grid extent over tiles.
 int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipStream_t stream);
 
-constexpr int kDecMaxSlices = 32;   // K-slices of T = X V^T in the decode kernel
+constexpr int kDecDoneBytes = 8192;  // sign-off words: up to 2048 resident workgroups
+constexpr int kDecMaxWorkers = 32;  // workgroups forming T = X V^T in the decode kernel
 
 struct DecodeArgs {
     const f16* X;       // [M x K], M <= 16
@@ -73,15 +74,15 @@ struct DecodeArgs {
     WeightDev w;
     f16* Y;             // [M x N]
     // filled in by launch_decode from the workspace
-    uint32_t* ctrl;     // [0] T slices arrived, [1] T ready, [2] workgroups done; zero between launches
-    f16* T;             // [16 x ldt] fp16 (X V^T), zero beyond the rank
+    uint32_t* ctrl;     // [0] T workers done, [3] a wait gave up; zero between launches
+    uint32_t* done;     // one sign-off word per streaming workgroup; zero between launches
+    f16* T;             // [kh][16 x ldt] fp16: X V^T per K part, zero beyond the rank
     int64_t ldt;
-    f32x4* t_partial;   // [nt][rblocks][64] fp32 partials of T in MFMA D layout
     int rblocks;        // ceil(r / 16)
-    int nt;             // number of K-slices / T workers
-    int slice;          // columns per slice (multiple of 64)
+    int nt;             // number of T workers (the first nt workgroups)
+    int kh;             // K parts of T (2048 columns each)
 };
-size_t decode_workspace_bytes(int r);
+size_t decode_workspace_bytes(int r, int64_t K);
 int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream);
 
 }  // namespace milo
