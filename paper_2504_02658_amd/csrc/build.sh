@@ -12,39 +12,44 @@ hipcc $FLAGS -c gemm_decode.hip -o _build/gemm_decode.o & pids+=($!)
 hipcc $FLAGS -c moe.hip -o _build/moe.o & pids+=($!)
 hipcc $FLAGS -c api.hip -o _build/api.o & pids+=($!)
 for p in "${pids[@]}"; do wait $p; done
-# The decode kernel counts outstanding memory operations by hand (see gemm_decode.hip): between the
-# last buffer-to-LDS copy and the hand-written "s_waitcnt vmcnt(N)" there must be exactly N vector
-# memory instructions, all of them the weight loads, and none added by the compiler (spills).
+# The decode kernel counts outstanding memory operations by hand (see gemm_decode.hip): all loads
+# of a piece are issued in a fixed order (per chunk eight buffer-to-LDS copies, then per row block
+# a 16-byte, an 8-byte and two 2-byte loads) before the first hand-written "s_waitcnt vmcnt(N)",
+# and the compiler must neither reorder them nor add memory operations of its own (spills).
 hipcc $FLAGS -S --cuda-device-only gemm_decode.hip -o _build/gemm_decode.s
 python3 - <<'PY'
 import re, sys
 txt = open("_build/gemm_decode.s").read()
 checked = 0
-VMEM = re.compile(r"\s+(buffer_|global_|scratch_|flat_)")
-for m in re.finditer(r"^(_ZN4milo18w3lr_decode_kernel\S*):[^\n]*\n(.*?)s_endpgm", txt, re.S | re.M):
-    name, body = m.group(1), m.group(2).split("\n")
-    for i, line in enumerate(body):
-        w = re.search(r"s_waitcnt vmcnt\((\d+)\)", line)
-        if not (w and i > 0 and "ASMSTART" in body[i - 1]) or int(w.group(1)) == 0:
-            continue                      # only hand-written partial waits are of interest
-        n = int(w.group(1))
-        # walk back over exactly n vector memory instructions: none may be a spill or a store,
-        # and the one before them must be a buffer-to-LDS copy (the data this wait is for)
-        j, seen = i - 1, []
-        while j >= 0 and len(seen) < n:
-            if VMEM.match(body[j]):
-                seen.append(body[j].split()[0] + (" lds" if " lds" in body[j] else ""))
+VMEM = re.compile(r"\s+(buffer_|global_|scratch_|flat_)(\S+)")
+CPW = 2
+for m in re.finditer(r"^(_ZN4milo18w3lr_decode_kernelILi(\d+)ELi(\d+)\S*):[^\n]*\n(.*?)s_endpgm", txt, re.S | re.M):
+    name, R, body = m.group(1), int(m.group(2)), m.group(4).split("\n")
+    meta = re.search(r"\.name:\s+%s\b(.*?)\.wavefront_size" % re.escape(name), txt, re.S)
+    if int(re.search(r"\.private_segment_fixed_size:\s+(\d+)", meta.group(1)).group(1)):
+        sys.exit("%s uses scratch memory" % name)
+    total = CPW * (8 + 4 * R)
+    first = total - (8 + 4)
+    hits = [i for i, line in enumerate(body)
+            if i > 0 and "ASMSTART" in body[i - 1] and re.search(r"s_waitcnt vmcnt\(%d\)" % first, line)]
+    if not hits:
+        sys.exit("%s: no hand-written s_waitcnt vmcnt(%d) found" % (name, first))
+    for i in hits:
+        seen, j = [], i - 1
+        while j >= 0 and len(seen) < total:
+            v = VMEM.match(body[j])
+            if v:
+                seen.append(v.group(1) + v.group(2) + (" lds" if " lds" in body[j] else ""))
             j -= 1
-        while j >= 0 and not VMEM.match(body[j]):
-            j -= 1
-        bad = [v for v in seen if not v.startswith("buffer_load")]
-        if bad or j < 0 or " lds" not in body[j]:
-            sys.exit("%s: s_waitcnt vmcnt(%d) does not sit %d loads after an LDS copy: %r / %r"
-                     % (name, n, n, seen, body[j] if j >= 0 else None))
+        seen.reverse()
+        unit = ["buffer_load_dwordx4", "buffer_load_dwordx2", "buffer_load_ushort", "buffer_load_ushort"]
+        want = (["buffer_load_dwordx4 lds"] * 8 + unit * R) * CPW
+        if seen != want:
+            sys.exit("%s: the loads before s_waitcnt vmcnt(%d) are not in the counted order:\n%r" % (name, first, seen))
         checked += 1
 if checked == 0:
-    sys.exit("decode kernel: no guarded LDS copy found; the check is out of date")
-print("decode kernel: %d hand-counted waits verified" % checked)
+    sys.exit("decode kernel: nothing checked; the check is out of date")
+print("decode kernel: load order before %d hand-counted wait sequences verified" % checked)
 PY
 # The tiled kernel counts outstanding memory operations by hand too; it is safe as long as the
 # compiler adds none of its own, i.e. as long as no variant uses scratch memory.

@@ -28,6 +28,8 @@
 // for the next launch.
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "milo_host.h"
 #include "milo_kernels.h"
 
@@ -46,6 +48,15 @@ __device__ __forceinline__ void buf_store8_coherent(BufRsrc r, uint32_t off, u32
     __builtin_amdgcn_raw_buffer_store_b64(v, r, off, 0, 17);
 }
 typedef __attribute__((address_space(3))) void* LdsPtr;
+
+// Compile-time loop: f(std::integral_constant<int, I>) for I in [B, E).
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
 
 
 // T worker.  Work item (jb, h) = rank block jb (16 ranks) over K part h (kDecWaves chunks of 256
@@ -134,6 +145,9 @@ __device__ __forceinline__ void decode_wait_t(const DecodeArgs& a) {
 
 // LR: 0 = no low-rank term, 1 = rank a multiple of 8 and at most 128 (U fragments are copied into
 // LDS at the start of the kernel, T comes through LDS), 2 = any other rank (plain loads).
+// The wave that fetches T for its workgroup: the first one, whose loads are served first and
+// which therefore has time to spare at the end.
+constexpr int kDecTWave = 0;
 constexpr int kDecKS = 4;                                       // k-steps of 32 ranks, LR == 1
 constexpr int kDecULds = kDecLdsBytes;                          // U fragments [R][kDecKS][64] x 16 B
 constexpr int kDecTLds = kDecULds + 4 * kDecKS * 1024;          // T fragments [kDecTFrags][64] x 16 B
@@ -201,13 +215,29 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
 #pragma unroll
             for (int b = 0; b < R; ++b) acc[b] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
+            if (LR == 1 && wave < R) {
+                // U rows of row block `wave` as MFMA A fragments, copied into LDS now so that the
+                // epilogue finds them there: k-step i, lane (j16, q) = U[n][32i + 8q ..].
+                const BufRsrc ub = make_rsrc(a.w.U, (uint64_t)a.N * (uint64_t)r * 2u);
+                const uint32_t nrow = (rb0 + wave) * 16u + j16;
+#pragma unroll
+                for (int i = 0; i < kDecKS; ++i) {
+                    const uint32_t k0 = 32u * i + 8u * q;
+                    const uint32_t off = (rb0 + wave < NB && k0 < (uint32_t)r) ? (nrow * r + k0) * 2u : kOobOffset;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        ub, (LdsPtr)(smem + kDecULds + (wave * kDecKS + i) * 1024), 16, off, 0, 0, 0);
+                }
+                asm volatile("" ::: "memory");
+            }
+
             for (uint32_t p = 0; p < npieces; ++p) {
                 // This wave's two chunks of the piece, everything requested up front: for each chunk
-                // the weights first (one unit per lane and row block: the 64 lanes of the wave read
-                // 64 consecutive units, lane quad q being group 4c + q), then its activations, which
-                // go straight from L2 into the wave's LDS slot.  The chunk order is rotated per
-                // workgroup so that the workgroups, which all read the same X, do not walk the same
-                // L2 channels in step.  A lane or block without data gets a unit index past the end.
+                // its activations, which go straight from L2 into the wave's LDS slot, then the
+                // weights (one unit per lane and row block: the 64 lanes of the wave read 64
+                // consecutive units, lane quad q being group 4c + q).  The chunk order is rotated
+                // per workgroup so that the workgroups, which all read the same X, do not walk the
+                // same L2 channels in step.  A lane or block without data gets a unit index past
+                // the end.
                 RawUnit u[CPW][R];
                 uint32_t workers_done = 0;
 #pragma unroll
@@ -215,29 +245,6 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
                     const uint32_t cw = (wave + kDecWaves * ci + rot) & (kDecPiece - 1);
                     const uint32_t chunk = p * kDecPiece + cw;
                     const uint32_t kc = chunk * 256u;
-                    // (an index >= 2^26 is past the end of every weight the host accepts, and the
-                    // sum of the two parts stays below 2^28, so 16 * index does not wrap)
-                    const uint32_t lane_u = (4u * chunk + (uint32_t)q < G) ? (uint32_t)lane : (1u << 26);
-#pragma unroll
-                    for (int b = 0; b < R; ++b) {
-                        const uint32_t base = (rb0 + b < NB) ? ((rb0 + b) * G + 4u * chunk) * 16u : (1u << 27);
-                        u[ci][b] = load_unit_buf(wb, base + lane_u);
-                    }
-                    asm volatile("" ::: "memory");
-                    if (LR == 1 && ci == 0 && p == 0 && wave < R) {
-                        // U rows of row block `wave` as MFMA A fragments, copied into LDS now so
-                        // that the epilogue finds them there: k-step i, lane (j16, q) = U[n][32i + 8q ..].
-                        const BufRsrc ub = make_rsrc(a.w.U, (uint64_t)a.N * (uint64_t)r * 2u);
-                        const uint32_t nrow = (rb0 + wave) * 16u + j16;
-#pragma unroll
-                        for (int i = 0; i < kDecKS; ++i) {
-                            const uint32_t k0 = 32u * i + 8u * q;
-                            const uint32_t off = (rb0 + wave < NB && k0 < (uint32_t)r) ? (nrow * r + k0) * 2u : kOobOffset;
-                            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                                ub, (LdsPtr)(smem + kDecULds + (wave * kDecKS + i) * 1024), 16, off, 0, 0, 0);
-                        }
-                        asm volatile("" ::: "memory");
-                    }
                     unsigned char* const slot = myslot + kDecWaves * ci * kDecSlotBytes;
                     // A chunk that reaches beyond K (the last one when K is not a multiple of 256, or
                     // one past the end) must not wrap into the next row: only the first `lim` bytes
@@ -254,54 +261,64 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
                                                                  (i < 4 ? ok_lo : ok_hi) ? off : kOobOffset, 0, 0, 0);
                     }
                     asm volatile("" ::: "memory");
-                }
-#pragma unroll
-                for (int ci = 0; ci < CPW; ++ci) {
-                    // Vector memory operations complete in order: once at most the operations issued
-                    // after this chunk's copies are outstanding (everything of the later chunks), its
-                    // weights have arrived and its copies have landed in LDS.  The slot is private to
-                    // the wave, so no barrier is involved.  (The count relies on the compiler adding
-                    // no memory operation of its own in between; the build script checks that.)
-                    if (ci == 0)
-                        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((CPW - 1) * (8 + R * 4)) : "memory");
-                    else
-                        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                    const unsigned char* slot = myslot + kDecWaves * ci * kDecSlotBytes;
-                    f16x8 bfrag[8];
-#pragma unroll
-                    for (int t = 0; t < 8; ++t)
-                        bfrag[t] = __builtin_bit_cast(
-                            f16x8,
-                            *reinterpret_cast<const u32x4*>(slot + j16 * 512 + (((8 * q + t) ^ j16) << 4)));
+                    // (an index >= 2^26 is past the end of every weight the host accepts, and the
+                    // sum of the two parts stays below 2^28, so 16 * index does not wrap)
+                    const uint32_t lane_u = (4u * chunk + (uint32_t)q < G) ? (uint32_t)lane : (1u << 26);
 #pragma unroll
                     for (int b = 0; b < R; ++b) {
-                        dequant_unit_steps(u[ci][b], [&](int t, f16x8 frag) {
-                            acc[b] = mfma16(frag, bfrag[t], acc[b]);
-                        });
-                        // The wave that will hand T to the others looks for it while it still has
-                        // work (reads of data written during the launch cross the whole chip and
-                        // take a microsecond each): of the S units it converts, it requests the
-                        // count of finished workers after unit P1, looks at it two units later and,
-                        // if all are done, starts the copy of T into LDS, which then runs under the
-                        // remaining units; otherwise it asks once more.
-                        constexpr int S = CPW * R, P1 = S / 2 - 2 >= 0 ? S / 2 - 2 : 0, E1 = P1 + 2, E2 = E1 + 2;
-                        const int su = ci * R + b;
-                        if (LR == 1 && wave == kDecWaves - 1 && p == npieces - 1 && !t_fetched) {
-                            if (su == P1 && E1 < S)
-                                workers_done = __hip_atomic_load(a.ctrl + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            if ((su == E1 && E1 < S) || (su == E2 && E2 < S)) {
-                                if (__builtin_amdgcn_readfirstlane(workers_done) >= (uint32_t)a.nt) {
-                                    fetch_t();
-                                    t_fetched = true;
-                                    sign_off();
-                                } else if (su == E1 && E2 < S) {
-                                    workers_done =
-                                        __hip_atomic_load(a.ctrl + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                }
+                        const uint32_t base = (rb0 + b < NB) ? ((rb0 + b) * G + 4u * chunk) * 16u : (1u << 27);
+                        u[ci][b] = load_unit_buf(wb, base + lane_u);
+                        asm volatile("" ::: "memory");      // the loads keep this order (the waits count them)
+                    }
+                }
+                // Vector memory operations complete in order, so unit (ci, b) and the activations of
+                // its chunk have arrived once at most the operations issued after that unit's four
+                // loads are outstanding.  The slots are private to the wave, so no barrier is
+                // involved, and the first unit is converted while most of the rest is still on its
+                // way.  (The counts rely on the compiler adding no memory operation of its own in
+                // between; the build script checks that.)
+                f16x8 bfrag[8];
+                static_for<0, CPW * R>([&](auto su_c) {
+                    constexpr int su = decltype(su_c)::value;
+                    constexpr int ci = su / R, b = su % R;
+                    constexpr int kIssued = CPW * (8 + 4 * R);
+                    __builtin_amdgcn_sched_barrier(0);      // nothing of this unit moves above its wait
+                    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kIssued - (ci * (8 + 4 * R) + 8 + 4 * (b + 1))) : "memory");
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (b == 0) {
+                        const unsigned char* slot = myslot + kDecWaves * ci * kDecSlotBytes;
+#pragma unroll
+                        for (int t = 0; t < 8; ++t)
+                            bfrag[t] = __builtin_bit_cast(
+                                f16x8,
+                                *reinterpret_cast<const u32x4*>(slot + j16 * 512 + (((8 * q + t) ^ j16) << 4)));
+                    }
+                    pin_unit_params(u[ci][b]);  // nothing is computed from this unit before the wait
+                    dequant_unit_steps(u[ci][b], [&](int t, f16x8 frag) {
+                        acc[b] = mfma16(frag, bfrag[t], acc[b]);
+                    });
+                    // The wave that will hand T to the others looks for it while it still has
+                    // work (reads of data written during the launch cross the whole chip and
+                    // take a microsecond each): of the S units it converts, it requests the
+                    // count of finished workers after unit P1, looks at it two units later and,
+                    // if all are done, starts the copy of T into LDS, which then runs under the
+                    // remaining units; otherwise it asks once more.
+                    constexpr int S = CPW * R, P1 = S / 2 - 2 >= 0 ? S / 2 - 2 : 0, E1 = P1 + 2, E2 = E1 + 2;
+                    if (LR == 1 && wave == kDecTWave && p == npieces - 1 && !t_fetched) {
+                        if (su == P1 && E1 < S)
+                            workers_done = __hip_atomic_load(a.ctrl + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if ((su == E1 && E1 < S) || (su == E2 && E2 < S)) {
+                            if (__builtin_amdgcn_readfirstlane(workers_done) >= (uint32_t)a.nt) {
+                                fetch_t();
+                                t_fetched = true;
+                                sign_off();
+                            } else if (su == E1 && E2 < S) {
+                                workers_done =
+                                    __hip_atomic_load(a.ctrl + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             }
                         }
                     }
-                }
+                });
             }
 
             // ------------------------------------------------------------ reduce + low rank + store
@@ -311,7 +328,7 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
             u32x4* const tbuf = reinterpret_cast<u32x4*>(smem + kDecTLds);
 #pragma unroll
             for (int b = 0; b < R; ++b) red[wave * (kDecSlotBytes / 16) + b * 64 + lane] = acc[b];
-            if (LR > 0 && wave == kDecWaves - 1) {
+            if (LR > 0 && wave == kDecTWave) {
                 // One wave gets T for the whole workgroup and hands it over through LDS (LR == 1);
                 // if the early look above did not find the workers done, it waits for them here.
                 if (!t_fetched) {

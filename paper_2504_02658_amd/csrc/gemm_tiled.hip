@@ -60,17 +60,6 @@ __device__ __forceinline__ int64_t input_row(const RowSpace& rs, int64_t R) {
     return rs.x_rows ? (int64_t)rs.x_rows[R] : R;
 }
 
-// Pins a loaded unit at this point of the program: nothing computed from it can be scheduled
-// earlier.  Without it the compiler converts the scale and zero-point of the NEXT chunk right
-// after issuing their loads and puts the wait for them in the middle of the current chunk.
-__device__ __forceinline__ void pin_unit(RawUnit& u) {
-    uint32_t sz = (uint32_t)__builtin_bit_cast(unsigned short, u.s) |
-                  ((uint32_t)__builtin_bit_cast(unsigned short, u.z) << 16);
-    asm volatile("" : "+v"(u.a.x), "+v"(u.a.y), "+v"(u.a.z), "+v"(u.a.w), "+v"(u.b.x), "+v"(u.b.y), "+v"(sz));
-    u.s = __builtin_bit_cast(f16, (unsigned short)(sz & 0xffffu));
-    u.z = __builtin_bit_cast(f16, (unsigned short)(sz >> 16));
-}
-
 __device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a)); }
 
 typedef __attribute__((address_space(3))) void* LdsPtr;

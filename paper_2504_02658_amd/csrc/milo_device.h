@@ -51,15 +51,16 @@ __host__ __device__ inline int64_t unit_index(int64_t n, int64_t g, int64_t G) {
 struct RawUnit {
     u32x4 a;        // words 0..3
     u32x2 b;        // words 4, 5
-    f16 s, z;
+    uint32_t s, z;  // fp16 bit patterns of scale and zero-point, as the 16-bit loads left them
 };
+__device__ __forceinline__ f16 f16_bits(uint32_t v) { return __builtin_bit_cast(f16, (unsigned short)v); }
 
 __device__ __forceinline__ RawUnit zero_unit() {
     RawUnit r;
     r.a = u32x4{0u, 0u, 0u, 0u};
     r.b = u32x2{0u, 0u};
-    r.s = (f16)0.0f;
-    r.z = (f16)0.0f;
+    r.s = 0u;
+    r.z = 0u;
     return r;
 }
 
@@ -71,13 +72,13 @@ __device__ __forceinline__ RawUnit load_unit(const W3View& w, int64_t u) {
     if (STREAM) {
         r.a = __builtin_nontemporal_load(w.planeA + u);
         r.b = __builtin_nontemporal_load(w.planeB + u);
-        r.s = __builtin_nontemporal_load(w.scales + u);
-        r.z = __builtin_nontemporal_load(w.zeros + u);
+        r.s = __builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(w.scales) + u);
+        r.z = __builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(w.zeros) + u);
     } else {
         r.a = w.planeA[u];
         r.b = w.planeB[u];
-        r.s = w.scales[u];
-        r.z = w.zeros[u];
+        r.s = reinterpret_cast<const unsigned short*>(w.scales)[u];
+        r.z = reinterpret_cast<const unsigned short*>(w.zeros)[u];
     }
     return r;
 }
@@ -104,9 +105,8 @@ __device__ __forceinline__ u32x4 buf_load16_coherent(BufRsrc r, uint32_t off) {
 __device__ __forceinline__ u32x2 buf_load8(BufRsrc r, uint32_t off) {
     return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
 }
-__device__ __forceinline__ f16 buf_load2(BufRsrc r, uint32_t off) {
-    const unsigned short v = __builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
-    return __builtin_bit_cast(f16, v);
+__device__ __forceinline__ uint32_t buf_load2(BufRsrc r, uint32_t off) {
+    return (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
 }
 
 // All vector memory operations issued so far by this wave (loads, stores and buffer-to-LDS copies)
@@ -136,6 +136,19 @@ __device__ __forceinline__ RawUnit load_unit_buf(const W3Buf& w, uint32_t u) {
     r.s = buf_load2(w.s, u * 2u);
     r.z = buf_load2(w.z, u * 2u);
     return r;
+}
+
+// Pins a loaded unit at this point of the program: nothing computed from it can be scheduled
+// earlier.  Without it the compiler converts the scale and zero-point of the NEXT chunk right
+// after issuing their loads and puts the wait for them in the middle of the current chunk.
+__device__ __forceinline__ void pin_unit(RawUnit& u) {
+    asm volatile("" : "+v"(u.a.x), "+v"(u.a.y), "+v"(u.a.z), "+v"(u.a.w), "+v"(u.b.x), "+v"(u.b.y), "+v"(u.s), "+v"(u.z));
+}
+// The same for the scale and the zero-point alone (the values whose conversion the compiler likes
+// to start early); the code words stay untouched, which keeps them in the registers they were
+// loaded into.
+__device__ __forceinline__ void pin_unit_params(RawUnit& u) {
+    asm volatile("" : "+v"(u.s), "+v"(u.z));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -182,14 +195,14 @@ struct UnitConsts {
     uint32_t A0, A3, A6, S2, C2;
 };
 __device__ __forceinline__ UnitConsts unit_consts(const RawUnit& ru) {
-    const float s = (float)ru.s;
-    const float z = (float)ru.z;
+    const float s = (float)f16_bits(ru.s);
+    const float z = (float)f16_bits(ru.z);
     const float zr = __builtin_fminf(__builtin_fmaxf(__builtin_rintf(z), -8.0f), 15.0f);
     UnitConsts c;
     c.A0 = pack2((f16)(1024.0f + zr));
     c.A3 = pack2((f16)(128.0f + zr));
     c.A6 = pack2((f16)(16.0f + zr));
-    c.S2 = pack2(ru.s);
+    c.S2 = pack2(f16_bits(ru.s));
     c.C2 = pack2((f16)((zr - z) * s));
     return c;
 }
