@@ -52,19 +52,21 @@ if checked == 0:
 print("decode kernel: load order before %d hand-counted wait sequences verified" % checked)
 PY
 # The tiled kernel counts outstanding memory operations by hand too; it is safe as long as the
-# compiler adds none of its own, i.e. as long as no variant uses scratch memory.
+# compiler adds none of its own, i.e. as long as no variant spills to scratch memory.
 hipcc $FLAGS -S --cuda-device-only gemm_tiled.hip -o _build/gemm_tiled.s
 python3 - <<'PY'
 import re, sys
 txt = open("_build/gemm_tiled.s").read()
 bad = []
-for m in re.finditer(r"\.name:\s+(\S*w3lr_tiled_kernel\S*)(.*?)\.wavefront_size", txt, re.S):
-    scratch = int(re.search(r"\.private_segment_fixed_size:\s+(\d+)", m.group(2)).group(1))
-    if scratch:
-        bad.append((m.group(1), scratch))
-if bad:
-    sys.exit("tiled kernel variants use scratch memory: %r" % bad)
-print("tiled kernel: no scratch memory")
+n = 0
+for m in re.finditer(r"^(_ZN4milo17w3lr_tiled_kernel\S*):[^\n]*\n(.*?)s_endpgm", txt, re.S | re.M):
+    n += 1
+    spills = re.findall(r"^\s+scratch_\S+", m.group(2), re.M)
+    if spills:
+        bad.append((m.group(1), len(spills)))
+if bad or n == 0:
+    sys.exit("tiled kernel variants access scratch memory (or none found): %r" % bad)
+print("tiled kernel: no scratch memory access in %d variants" % n)
 PY
 hipcc --offload-arch=gfx950 -shared -fPIC -o "$OUT/libmilo.so" _build/pack.o _build/gemm_tiled.o _build/gemm_decode.o _build/moe.o _build/api.o
 echo "built $OUT/libmilo.so"

@@ -13,6 +13,8 @@
 //   NW = 2: the streams are the same 32 rows of two weights (gate and up projection, band of
 //           128 features) and the epilogue applies SiLU(gate) * up.
 // The low-rank term is appended as extra k-steps [X | T] [W_dq | U]^T with U read as plain fp16.
+#include <type_traits>
+
 #include "milo_host.h"
 #include "milo_kernels.h"
 
@@ -297,95 +299,120 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[s][mb][v] = 0.0f;
 
-    // One chunk's loads of this wave, always PER instructions (chunks past the end read out of
-    // range, which costs no memory traffic): the two weight units, then the NCP activation copies
-    // into stage `slot`.
-    auto issue = [&](int c, int slot, RawUnit (&ru)[2]) {
-        const int g = 2 * c + h;
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
-            ru[s] = load_unit_buf(wbuf[s], (g < G && ubase[s] != kOobUnit) ? ubase[s] + (uint32_t)g * 16u : kOobUnit);
-        asm volatile("" ::: "memory");
-        unsigned char* stage = smem + slot * STAGE;
-        const bool past = c >= nchunks;
-        const bool last_half = ktail && c == nchunks - 1;
-#pragma unroll
-        for (int i = 0; i < NCP; ++i) {
-            uint32_t off = xoff[i] + (uint32_t)c * 256u;
-            if (past || (last_half && xhi[i])) off = kOobHalf;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (LdsPtr)(stage + (wave * NCP + i) * 1024), 16, off, 0, 0,
-                                                     0);
+    // One chunk's loads of this wave are always PER instructions (chunks past the end read out of
+    // range, which costs no memory traffic), in eight parts: part t = piece t of the two weight
+    // units (16-byte words, 8-byte words, scale, zero-point of stream t % 2) and, while there are
+    // any left, activation copy t into stage `slot`.  All parts are issued when a chunk starts:
+    // a wave needs some eighty cycles to get one vector memory instruction out while its three
+    // neighbours do the same, and that time is best spent while the other workgroup on the CU
+    // multiplies (spreading the parts over the steps of the chunk was slower).
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);        // known to be uniform
+    auto issue_part = [&](int t, int c, int slot, RawUnit (&ru)[2], uint32_t (&uidx)[2]) {
+        const int s = t & 1;
+        if (t < 2) {
+            const int g = 2 * c + h;
+            uidx[s] = (g < G && ubase[s] != kOobUnit) ? ubase[s] + (uint32_t)g * 16u : kOobUnit;
+        }
+        switch (t >> 1) {
+            case 0: ru[s].a = buf_load16(wbuf[s].a, uidx[s] * 16u); break;
+            case 1: ru[s].b = buf_load8(wbuf[s].b, uidx[s] * 8u); break;
+            case 2: ru[s].s = buf_load2(wbuf[s].s, uidx[s] * 2u); break;
+            default: ru[s].z = buf_load2(wbuf[s].z, uidx[s] * 2u); break;
         }
         asm volatile("" ::: "memory");
-    };
-    const int mb_used = (ti.rows + 31) / 32;
-    auto compute = [&](int slot, RawUnit (&ru)[2]) {
-        pin_unit(ru[0]);
-        pin_unit(ru[1]);
-        // B fragment of step t, row block mb: row 32mb + i32, segment 8h + t.
-        const unsigned char* xs = smem + slot * STAGE + i32 * 256;
-        const int sx = i32 & 15;
-        if (MB == 4) {
-            // 128 accumulator registers leave no room for a prefetched fragment set if two waves
-            // are to share a SIMD; the second wave hides the read latency instead.
-            dequant_units2_steps(ru[0], ru[1], [&](int t, f16x8 a0, f16x8 a1) {
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    if (mb < mb_used) {     // row blocks past the tile's rows are skipped (uniform)
-                        const f16x8 b = __builtin_bit_cast(
-                            f16x8,
-                            *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h + t) ^ sx) << 4)));
+        for (int i = t; i < NCP; i += 8) {
+            unsigned char* stage = smem + slot * STAGE;
+            const bool past = c >= nchunks;
+            const bool last_half = ktail && c == nchunks - 1;
+            uint32_t off = xoff[i] + (uint32_t)c * 256u;
+            if (past || (last_half && xhi[i])) off = kOobHalf;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (LdsPtr)(stage + (wave_s * NCP + i) * 1024), 16, off, 0, 0,
+                                                     0);
+            asm volatile("" ::: "memory");
+        }
+    };
+    // Row blocks of 32 actually present in this tile.  The K loop is instantiated per count, so
+    // that blocks past the tile's rows cost nothing and the loop body has no branches (the
+    // instruction scheduler interleaves conversion, LDS reads and MFMAs only within a basic block).
+    const int mb_used = (ti.rows + 31) / 32;
+    auto k_loop = [&](auto mbu_c) {
+        constexpr int MBU = decltype(mbu_c)::value;
+        auto compute = [&](int slot, RawUnit (&ru)[2], auto&& between) {
+            pin_unit(ru[0]);
+            pin_unit(ru[1]);
+            // B fragment of step t, row block mb: row 32mb + i32, segment 8h + t.
+            const unsigned char* xs = smem + slot * STAGE + i32 * 256;
+            const int sx = i32 & 15;
+            auto bfrag = [&](int mb, int t) {
+                return __builtin_bit_cast(
+                    f16x8, *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h + t) ^ sx) << 4)));
+            };
+            if constexpr (MBU == 4) {
+                // 128 accumulator registers leave no room for a second fragment set when two
+                // waves share a SIMD: the fragments are read where they are used and the
+                // scheduler moves the reads up as far as registers allow.
+                dequant_units2_steps(ru[0], ru[1], [&](int t, f16x8 a0, f16x8 a1) {
+                    between(t);
+#pragma unroll
+                    for (int mb = 0; mb < MBU; ++mb) {
+                        const f16x8 b = bfrag(mb, t);
                         acc[0][mb] = mfma32(a0, b, acc[0][mb]);
                         acc[1][mb] = mfma32(a1, b, acc[1][mb]);
                     }
-                }
-            });
-        } else {
-            f16x8 bc[MB], bn[MB];
+                });
+            } else {
+                f16x8 bc[MBU], bn[MBU];
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-                bc[mb] = __builtin_bit_cast(
-                    f16x8, *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h) ^ sx) << 4)));
-            dequant_units2_steps(ru[0], ru[1], [&](int t, f16x8 a0, f16x8 a1) {
-                if (t < 7) {
+                for (int mb = 0; mb < MBU; ++mb) bc[mb] = bfrag(mb, 0);
+                dequant_units2_steps(ru[0], ru[1], [&](int t, f16x8 a0, f16x8 a1) {
+                    between(t);
+                    if (t < 7) {
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-                        bn[mb] = __builtin_bit_cast(
-                            f16x8,
-                            *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h + t + 1) ^ sx) << 4)));
-                }
+                        for (int mb = 0; mb < MBU; ++mb) bn[mb] = bfrag(mb, t + 1);
+                    }
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    acc[0][mb] = mfma32(a0, bc[mb], acc[0][mb]);
-                    acc[1][mb] = mfma32(a1, bc[mb], acc[1][mb]);
-                }
-                if (t < 7) {
+                    for (int mb = 0; mb < MBU; ++mb) {
+                        acc[0][mb] = mfma32(a0, bc[mb], acc[0][mb]);
+                        acc[1][mb] = mfma32(a1, bc[mb], acc[1][mb]);
+                    }
+                    if (t < 7) {
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) bc[mb] = bn[mb];
-                }
-            });
+                        for (int mb = 0; mb < MBU; ++mb) bc[mb] = bn[mb];
+                    }
+                });
+            }
+        };
+
+        // PD-deep pipeline: chunk c lives in ring slot c % PD (registers for the weights, LDS stage
+        // for the activations).  Vector memory operations complete in order, so once at most the
+        // (PD - 2) * PER instructions of the younger chunks are outstanding, chunk c has arrived.
+        // (The count relies on the compiler adding no memory operation of its own, i.e. on the
+        // kernel not using scratch memory; the build script checks that.)
+        RawUnit ring[PD][2];
+        uint32_t uidx[2];
+#pragma unroll
+        for (int i = 0; i < PD - 1; ++i)
+#pragma unroll
+            for (int t = 0; t < 8; ++t) issue_part(t, i, i, ring[i], uidx);
+        for (int c0 = 0; c0 < nchunks; c0 += PD) {
+#pragma unroll
+            for (int slot = 0; slot < PD; ++slot) {
+                const int c = c0 + slot;
+                if (c >= nchunks) break;
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PD - 2) * PER) : "memory");
+                __syncthreads();        // everyone's copies of chunk c landed; everyone left chunk c-1
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    issue_part(t, c + PD - 1, (slot + PD - 1) % PD, ring[(slot + PD - 1) % PD], uidx);
+                compute(slot, ring[slot], [](int) {});
+            }
         }
     };
-
-    // PD-deep pipeline: chunk c lives in ring slot c % PD (registers for the weights, LDS stage
-    // for the activations).  Vector memory operations complete in order, so once at most the
-    // (PD - 2) * PER instructions of the younger chunks are outstanding, chunk c has arrived.
-    // (The count relies on the compiler adding no memory operation of its own, i.e. on the
-    // kernel not using scratch memory; the build script checks that.)
-    RawUnit ring[PD][2];
-#pragma unroll
-    for (int i = 0; i < PD - 1; ++i) issue(i, i, ring[i]);
-    for (int c0 = 0; c0 < nchunks; c0 += PD) {
-#pragma unroll
-        for (int slot = 0; slot < PD; ++slot) {
-            const int c = c0 + slot;
-            if (c >= nchunks) break;
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PD - 2) * PER) : "memory");
-            __syncthreads();        // everyone's copies of chunk c landed; everyone left chunk c-1
-            issue(c + PD - 1, (slot + PD - 1) % PD, ring[(slot + PD - 1) % PD]);
-            compute(slot, ring[slot]);
-        }
-    }
+    if (MB >= 4 && mb_used >= 4) k_loop(std::integral_constant<int, MB >= 4 ? 4 : 1>{});
+    else if (MB >= 4 && mb_used == 3) k_loop(std::integral_constant<int, MB >= 4 ? 3 : 1>{});
+    else if (MB >= 2 && mb_used >= 2) k_loop(std::integral_constant<int, MB >= 2 ? 2 : 1>{});
+    else k_loop(std::integral_constant<int, 1>{});
 
     bool nvalid[2];
     nvalid[0] = nrow[0] < N;
