@@ -43,6 +43,34 @@ extern "C" int milo_workspace_init(void* workspace, size_t workspace_bytes, void
 
 static int64_t rank_pad(int r) { return ((int64_t)r + 15) / 16 * 16; }
 
+// Tile height (in blocks of 32 rows) and K splits of the tiled kernel for an [M x N x K] problem.
+static int gemm_mb(int64_t M) {
+    int mb = M <= 32 ? 1 : (M <= 64 ? 2 : 4);
+    if (const char* e = getenv("MILO_GEMM_MB")) mb = atoi(e);           // tuning override
+    return mb;
+}
+static int gemm_splits(int64_t M, int64_t N, int64_t K) {
+    const int bm = 32 * gemm_mb(M);
+    return tiled_k_splits(((M + bm - 1) / bm) * ((N + 255) / 256), K);
+}
+
+// Adds the fp32 partial sums of the K splits in split order and rounds once.
+__global__ __launch_bounds__(256) void splitk_sum_kernel(const float* __restrict__ part, int splits,
+                                                         int64_t n4, int64_t stride, f16* __restrict__ Y) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n4) return;
+    f32x4 sum = *reinterpret_cast<const f32x4*>(part + 4 * i);
+    for (int s = 1; s < splits; ++s) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(part + (int64_t)s * stride + 4 * i);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum[e] += v[e];
+    }
+    f16x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (f16)sum[e];
+    *reinterpret_cast<f16x4*>(Y + 4 * i) = o;
+}
+
 static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
     return M >= 1 && M <= (int64_t)0x3fffffff && weight_shape_ok(N, K);
 }
@@ -50,9 +78,14 @@ static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
 extern "C" size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int r) {
     if (!gemm_shape_ok(M, N, K) || r < 0) return 0;
     if (M <= 16) return decode_workspace_bytes(r, K);
-    // control words | two flag words per 32-row tile | T = X V^T as fp16 [M x pad16(r)]
-    return 256 + align_up((size_t)((M + 31) / 32) * 8, 256) +
-           align_up((size_t)M * (size_t)rank_pad(r) * 2 + 256, 256);
+    // control words | four flag words per 32-row tile | T = X V^T, fp16 [M x pad16(r)] | its fp32
+    // partials per part of K | with K splits, their fp32 partial sums [M x N] each
+    const size_t parts = r > 0 ? (size_t)tiled_t_parts(K) : 0;
+    const int splits = gemm_splits(M, N, K);
+    return 256 + align_up((size_t)((M + 31) / 32) * 16, 256) +
+           align_up((size_t)M * (size_t)rank_pad(r) * 2 + 256, 256) +
+           align_up(parts * (size_t)M * (size_t)rank_pad(r) * 4 + 256, 256) +
+           (splits > 1 ? align_up((size_t)splits * (size_t)M * (size_t)N * 4, 256) : 0);
 }
 
 extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t K, const void* q3,
@@ -92,17 +125,21 @@ extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t 
     char* ws = reinterpret_cast<char*>(workspace);
     uint32_t* ctrl = reinterpret_cast<uint32_t*>(ws);
     uint32_t* flags = reinterpret_cast<uint32_t*>(ws + 256);
-    f16* T = reinterpret_cast<f16*>(ws + 256 + align_up((size_t)((M + 31) / 32) * 8, 256));
+    f16* T = reinterpret_cast<f16*>(ws + 256 + align_up((size_t)((M + 31) / 32) * 16, 256));
     const int64_t ldt = rank_pad(r);
 
-    int mb = M <= 32 ? 1 : (M <= 64 ? 2 : 4);
-    if (const char* e = getenv("MILO_GEMM_MB")) mb = atoi(e);           // tuning override
+    const int mb = gemm_mb(M);
     const int bm = 32 * mb;
     const int64_t m_tiles = (M + bm - 1) / bm;
     if (m_tiles > 65535) return MILO_ERR_SHAPE;
+    const int parts = r > 0 ? tiled_t_parts(K) : 0;
+    const int splits = gemm_splits(M, N, K);
     if ((uint64_t)M * K * 2 >= 0x80000000ull || ((uint64_t)r + 256) * K * 2 >= 0xFFFFFFF0ull ||
-        (uint64_t)M * ldt * 2 >= 0xFFFFFFF0ull)
+        (uint64_t)(parts > 0 ? parts : 1) * M * ldt * 4 >= 0xFFFFFFF0ull || (N & 3) != 0)
         return MILO_ERR_SHAPE;                                          // 32-bit offsets in the kernel
+    float* Tp = reinterpret_cast<float*>(reinterpret_cast<char*>(T) + align_up((size_t)M * (size_t)ldt * 2 + 256, 256));
+    float* partial = reinterpret_cast<float*>(
+        reinterpret_cast<char*>(Tp) + align_up((size_t)parts * (size_t)M * (size_t)ldt * 4 + 256, 256));
 
     RowSpace rs;
     rs.tiles = nullptr; rs.n_tiles = nullptr; rs.experts = nullptr;
@@ -114,7 +151,17 @@ extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t 
     ga.rs = rs; ga.X = reinterpret_cast<const f16*>(X); ga.ldx = K; ga.x_bytes = (uint64_t)M * K * 2;
     ga.N = N; ga.K = K;
     ga.T[0] = ga.T[1] = T; ga.ldt = ldt; ga.t_bytes = (uint64_t)M * ldt * 2;
-    ga.v_tiles = r > 0 ? 1 : 0; ga.flags = flags; ga.flags_status = ctrl + 3;
-    ga.out = Y; ga.ldo = N; ga.out_rows = nullptr; ga.out_scale = nullptr;
-    return launch_tiled(ga, 1, mb, EPI_STORE, (int)m_tiles, stream);
+    ga.Tp[0] = ga.Tp[1] = Tp; ga.tp_bytes = (uint64_t)parts * M * ldt * 4;
+    ga.t_part_stride = M * ldt; ga.t_parts = parts; ga.v_tiles = parts; ga.ksplit = splits;
+    ga.flags = flags; ga.flags_status = ctrl + 3;
+    ga.out = splits > 1 ? static_cast<void*>(partial) : static_cast<void*>(Y);
+    ga.ldo = N; ga.out_split_stride = M * N; ga.out_rows = nullptr; ga.out_scale = nullptr;
+    int st = launch_tiled(ga, 1, mb, EPI_STORE, (int)m_tiles, stream);
+    if (st != MILO_OK || splits == 1) return st;
+    const int64_t n4 = M * N / 4;
+    const int64_t blocks = (n4 + 255) / 256;
+    if (blocks > 0x7fffffff) return MILO_ERR_SHAPE;
+    splitk_sum_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(partial, splits, n4, M * N,
+                                                                        reinterpret_cast<f16*>(Y));
+    return launch_status();
 }

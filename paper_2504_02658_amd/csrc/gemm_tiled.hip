@@ -69,10 +69,10 @@ typedef __attribute__((address_space(3))) void* LdsPtr;
 // when a column offset is added to it.
 constexpr uint32_t kOobHalf = 0x80000000u;
 
-// Spin until *flag becomes non-zero.  The producer never waits and was dispatched earlier, so the
+// Spin until *flag reaches `target`.  The producers never wait and were dispatched earlier, so the
 // wait ends; the bound only turns a broken assumption into an error code instead of a hang.
-__device__ __forceinline__ void wait_flag(const uint32_t* flag, uint32_t* status) {
-    for (uint32_t spins = 0; __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u; ++spins) {
+__device__ __forceinline__ void wait_flag(const uint32_t* flag, uint32_t target, uint32_t* status) {
+    for (uint32_t spins = 0; __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target; ++spins) {
         __builtin_amdgcn_s_sleep(2);
         if (spins > (1u << 24)) {
             if (status) atomicOr(status, 1u);
@@ -87,7 +87,7 @@ __device__ __forceinline__ void wait_flag(const uint32_t* flag, uint32_t* status
 // ranks 32w ..; larger ranks take further passes.  T is written with device-coherent stores and
 // published through the tile's flag.
 template <int NW, int MB>
-__device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& ti, unsigned char* smem) {
+__device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& ti, unsigned char* smem, int part) {
     constexpr int BM = 32 * MB;
     constexpr int STAGE = BM * 256;
     constexpr int NCP = BM / 16;
@@ -98,6 +98,10 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
     const int64_t K = a.K;
     const int G = (int)(K / kGroup);
     const int nchunks = (G + 1) / 2;
+    // this part's share of the chunks
+    const int cpp = (nchunks + a.t_parts - 1) / a.t_parts;
+    const int c_lo = part * cpp;
+    const int c_hi = (c_lo + cpp < nchunks) ? c_lo + cpp : nchunks;
 
     const BufRsrc xb = make_rsrc(a.X, a.x_bytes);
     uint32_t xoff[NCP];
@@ -156,18 +160,18 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
 
         // V fragment of step t of chunk c; out of range (inactive stream, ragged K tail) reads zero
         auto load_v = [&](int c, int s, int t) -> u32x4 {
-            const bool out = !active[s] || c >= nchunks || (ktail && c == nchunks - 1 && h == 1);
+            const bool out = !active[s] || c >= c_hi || (ktail && c == nchunks - 1 && h == 1);
             return buf_load16(vb[s], out ? kOobOffset : voff[s] + (uint32_t)c * 256u + 16u * t);
         };
 
         u32x4 va[2][8];
         __syncthreads();            // a previous pass is done with the stages
-        issue_x(0);
+        if (c_lo < c_hi) issue_x(c_lo);
 #pragma unroll
         for (int s = 0; s < 2; ++s)
 #pragma unroll
-            for (int t = 0; t < 8; ++t) va[s][t] = load_v(0, s, t);
-        for (int c = 0; c < nchunks; ++c) {
+            for (int t = 0; t < 8; ++t) va[s][t] = load_v(c_lo, s, t);
+        for (int c = c_lo; c < c_hi; ++c) {
             wait_vmem();
 #pragma unroll
             for (int s = 0; s < 2; ++s)
@@ -175,7 +179,7 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
                 for (int t = 0; t < 8; ++t)
                     asm volatile("" : "+v"(va[s][t].x), "+v"(va[s][t].y), "+v"(va[s][t].z), "+v"(va[s][t].w));
             __syncthreads();
-            if (c + 1 < nchunks) issue_x(c + 1);
+            if (c + 1 < c_hi) issue_x(c + 1);
             const unsigned char* xs = smem + (c & 1) * STAGE + i32 * 256;
             const int sx = i32 & 15;
 #pragma unroll
@@ -196,31 +200,69 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
         // multiple of 16 are written (they are exact zeros) because the consumers read that far.
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            if (NW == 1 && s == 1 && false) continue;
             const WeightDev& w = ti.w[NW == 1 ? 0 : s];
             const int rpad = (w.r + 15) & ~15;
-            const BufRsrc tb = make_rsrc(a.T[NW == 1 ? 0 : s], a.t_bytes);
+            const BufRsrc pb = make_rsrc(a.Tp[NW == 1 ? 0 : s], a.tp_bytes);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 const int m = 32 * mb + i32;
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq) {
                     const int rank = rank0[s] + 8 * vq + 4 * h;
-                    f16x4 o;
+                    f32x4 o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (f16)acc[s][mb][4 * vq + e];
+                    for (int e = 0; e < 4; ++e) o[e] = acc[s][mb][4 * vq + e];
                     const bool ok = m < ti.rows && rank < rpad;
-                    __builtin_amdgcn_raw_buffer_store_b64(
-                        __builtin_bit_cast(u32x2, o), tb,
-                        ok ? (uint32_t)(((ti.row0 + m) * a.ldt + rank) * 2) : kOobOffset, 0, 17);
+                    __builtin_amdgcn_raw_buffer_store_b128(
+                        __builtin_bit_cast(u32x4, o), pb,
+                        ok ? (uint32_t)((part * a.t_part_stride + (ti.row0 + m) * a.ldt + rank) * 4) : kOobOffset, 0,
+                        17);
                 }
             }
+        }
+    }
+    // This part is complete once its stores are; the last part of the tile to get here adds all
+    // parts in part order (so the sum does not depend on which one that was), writes T as fp16
+    // and raises the tile's flag.
+    wait_vmem();
+    __syncthreads();
+    int last = 0;
+    if (tid == 0) last = atomicAdd(a.flags + 4 * blockIdx.y, 1u) == (uint32_t)a.t_parts - 1u;
+    if (!__syncthreads_or(last)) return;
+#pragma unroll
+    for (int s = 0; s < NW; ++s) {
+        const WeightDev& w = ti.w[s];
+        const int rquads = ((w.r + 15) & ~15) / 4;              // groups of four ranks
+        if (rquads == 0) continue;
+        const BufRsrc pb = make_rsrc(a.Tp[s], a.tp_bytes);
+        const BufRsrc tb = make_rsrc(a.T[s], a.t_bytes);
+        for (int item = tid; item < ti.rows * rquads; item += kTiledThreads) {
+            const int m = item / rquads, rank = 4 * (item - m * rquads);
+            const uint32_t at = (uint32_t)((ti.row0 + m) * a.ldt + rank);
+            f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int p0 = 0; p0 < a.t_parts; p0 += 4) {
+                u32x4 v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    v[i] = buf_load16_coherent(
+                        pb, p0 + i < a.t_parts ? (uint32_t)(((p0 + i) * a.t_part_stride + at) * 4) : kOobOffset);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const f32x4 f = __builtin_bit_cast(f32x4, v[i]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) sum[e] += f[e];
+                }
+            }
+            f16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (f16)sum[e];
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), tb, at * 2u, 0, 17);
         }
     }
     wait_vmem();
     __syncthreads();
     if (tid == 0)
-        __hip_atomic_store(a.flags + 2 * blockIdx.y, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.flags + 4 * blockIdx.y + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int NW, int MB, int EPI>
@@ -237,8 +279,10 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     if (!ti.valid) return;
     const bool any_rank = ti.w[0].r > 0 || ti.w[1].r > 0;
     if ((int)blockIdx.x < a.v_tiles) {
-        // leading workgroup column: forms T = X V^T for this M-tile (see v_tile_body)
-        if (any_rank) v_tile_body<NW, MB>(a, ti, smem);
+        // leading workgroup columns of the first K split: each forms one part of T = X V^T for this
+        // M-tile (see v_tile_body).  They sit in the same grid row and split as the workgroups
+        // that wait for them, hence are dispatched before those.
+        if (any_rank && blockIdx.z == 0) v_tile_body<NW, MB>(a, ti, smem, (int)blockIdx.x);
         return;
     }
 
@@ -250,6 +294,10 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     const int64_t N = a.N, K = a.K;
     const int G = (int)(K / kGroup);
     const int nchunks = (G + 1) / 2;
+    // K split: this workgroup multiplies chunks [c_begin, c_end)
+    const int cps = (nchunks + a.ksplit - 1) / a.ksplit;
+    const int c_begin = (int)blockIdx.z * cps;
+    const int c_end = (c_begin + cps < nchunks) ? c_begin + cps : nchunks;
     const int64_t n0 = (int64_t)((int)blockIdx.x - a.v_tiles) * BN;
 
     // Weight streams of this wave: lane (i32, h) feeds row nrow of the stream, group 2c + h.
@@ -311,7 +359,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
         const int s = t & 1;
         if (t < 2) {
             const int g = 2 * c + h;
-            uidx[s] = (g < G && ubase[s] != kOobUnit) ? ubase[s] + (uint32_t)g * 16u : kOobUnit;
+            uidx[s] = (g < G && c < c_end && ubase[s] != kOobUnit) ? ubase[s] + (uint32_t)g * 16u : kOobUnit;
         }
         switch (t >> 1) {
             case 0: ru[s].a = buf_load16(wbuf[s].a, uidx[s] * 16u); break;
@@ -323,7 +371,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
 #pragma unroll
         for (int i = t; i < NCP; i += 8) {
             unsigned char* stage = smem + slot * STAGE;
-            const bool past = c >= nchunks;
+            const bool past = c >= c_end;
             const bool last_half = ktail && c == nchunks - 1;
             uint32_t off = xoff[i] + (uint32_t)c * 256u;
             if (past || (last_half && xhi[i])) off = kOobHalf;
@@ -394,12 +442,12 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
 #pragma unroll
         for (int i = 0; i < PD - 1; ++i)
 #pragma unroll
-            for (int t = 0; t < 8; ++t) issue_part(t, i, i, ring[i], uidx);
-        for (int c0 = 0; c0 < nchunks; c0 += PD) {
+            for (int t = 0; t < 8; ++t) issue_part(t, c_begin + i, i, ring[i], uidx);
+        for (int c0 = c_begin; c0 < c_end; c0 += PD) {
 #pragma unroll
             for (int slot = 0; slot < PD; ++slot) {
                 const int c = c0 + slot;
-                if (c >= nchunks) break;
+                if (c >= c_end) break;
                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PD - 2) * PER) : "memory");
                 __syncthreads();        // everyone's copies of chunk c landed; everyone left chunk c-1
 #pragma unroll
@@ -421,8 +469,8 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     // Low-rank term: r extra k-steps with A = U rows and B = T rows.  T of this M-tile is formed
     // by the leading workgroup of the same grid row during this launch: wait for its flag (it was
     // dispatched before this workgroup and never waits itself), then read T coherently.
-    if (any_rank) {
-        if (tid == 0) wait_flag(a.flags + 2 * blockIdx.y, a.flags_status);
+    if (any_rank && blockIdx.z == 0) {
+        if (tid == 0) wait_flag(a.flags + 4 * blockIdx.y + 1, 1u, a.flags_status);
         __syncthreads();
         const BufRsrc tb0 = make_rsrc(a.T[0], a.t_bytes);
         const BufRsrc tb1 = make_rsrc(a.T[1], a.t_bytes);
@@ -448,13 +496,14 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                 }
             }
         }
-        // the last reader of this M-tile's T clears its two control words for the next launch
+        // the last reader of this M-tile's T clears its control words for the next launch
         __syncthreads();
         if (tid == 0) {
             const uint32_t readers = gridDim.x - (uint32_t)a.v_tiles;
-            if (atomicAdd(a.flags + 2 * blockIdx.y + 1, 1u) == readers - 1u) {
-                __hip_atomic_store(a.flags + 2 * blockIdx.y, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(a.flags + 2 * blockIdx.y + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (atomicAdd(a.flags + 4 * blockIdx.y + 2, 1u) == readers - 1u) {
+                __hip_atomic_store(a.flags + 4 * blockIdx.y, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.flags + 4 * blockIdx.y + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.flags + 4 * blockIdx.y + 2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
@@ -482,7 +531,19 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 const int64_t nb = n0 + 64 * wave + 32 * s;
-                if (EPI == EPI_STORE) {
+                if (EPI == EPI_STORE && a.ksplit > 1) {
+                    // partial sum of this K split, fp32; a small kernel adds the splits in order
+                    float* orow = reinterpret_cast<float*>(a.out) + (int64_t)blockIdx.z * a.out_split_stride + R * a.ldo;
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        const int64_t n = nb + 8 * vq + 4 * h;
+                        if (n >= N) continue;
+                        f32x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = acc[s][mb][4 * vq + e];
+                        *reinterpret_cast<f32x4*>(orow + n) = o;
+                    }
+                } else if (EPI == EPI_STORE) {
                     f16* orow = reinterpret_cast<f16*>(a.out) + R * a.ldo;
 #pragma unroll
                     for (int vq = 0; vq < 4; ++vq) {
@@ -496,15 +557,15 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                 } else {
                     const int64_t orow_i = a.out_rows ? (int64_t)a.out_rows[R] : R;
                     const float sc = a.out_scale ? a.out_scale[orow_i] : 1.0f;
-                    float* orow = reinterpret_cast<float*>(a.out) + orow_i * a.ldo;
+                    f16* orow = reinterpret_cast<f16*>(a.out) + (int64_t)blockIdx.z * a.out_split_stride + orow_i * a.ldo;
 #pragma unroll
                     for (int vq = 0; vq < 4; ++vq) {
                         const int64_t n = nb + 8 * vq + 4 * h;
                         if (n >= N) continue;
-                        f32x4 o;
+                        f16x4 o;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = sc * acc[s][mb][4 * vq + e];
-                        *reinterpret_cast<f32x4*>(orow + n) = o;
+                        for (int e = 0; e < 4; ++e) o[e] = (f16)(sc * acc[s][mb][4 * vq + e]);
+                        *reinterpret_cast<f16x4*>(orow + n) = o;
                     }
                 }
             }
@@ -545,12 +606,24 @@ int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipSt
     const int bn = (nw == 1) ? 256 : 128;
     const int64_t n_tiles = (a.N + bn - 1) / bn + a.v_tiles;
     if (n_tiles > 0x7fffffff || m_tiles > 65535) return MILO_ERR_SHAPE;
-    dim3 grid((unsigned)n_tiles, (unsigned)m_tiles, 1);
+    if (a.ksplit < 1 || a.ksplit > 64 || a.v_tiles != a.t_parts || (epi == EPI_SWIGLU && a.ksplit != 1))
+        return MILO_ERR_SHAPE;
+    dim3 grid((unsigned)n_tiles, (unsigned)m_tiles, (unsigned)a.ksplit);
     if (nw == 2 && epi == EPI_SWIGLU) return launch_tiled_mb<2, EPI_SWIGLU>(a, mb, grid, stream);
     if (nw == 1 && epi == EPI_STORE) return launch_tiled_mb<1, EPI_STORE>(a, mb, grid, stream);
     if (nw == 1 && epi == EPI_SCALE_SCATTER)
         return launch_tiled_mb<1, EPI_SCALE_SCATTER>(a, mb, grid, stream);
     return MILO_ERR_SHAPE;
+}
+
+// Parts of T = X V^T per M-tile: about eight 128-column chunks each, so that forming a part takes
+// a fraction of the time a streaming workgroup needs for its tile.
+int tiled_t_parts(int64_t K) {
+    const int64_t nchunks = (K / kGroup + 1) / 2;
+    int64_t p = (nchunks + 7) / 8;
+    if (p < 1) p = 1;
+    if (p > 16) p = 16;
+    return (int)p;
 }
 
 }  // namespace milo

@@ -10,6 +10,31 @@ namespace milo {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Compute units of the current device (256 if the query fails); cached per device.
+inline int device_cus() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        cached[dev] = cus;
+    }
+    return cached[dev];
+}
+
+// K splits for a tiled GEMM whose grid would have `tiles` workgroups: enough to give every CU
+// about two workgroups, as long as a split keeps at least eight 128-column chunks.
+inline int tiled_k_splits(int64_t tiles, int64_t K) {
+    const int64_t nchunks = (K / 64 + 1) / 2;
+    int64_t s = tiles > 0 ? (2 * (int64_t)device_cus()) / tiles : 1;
+    if (s > nchunks / 8) s = nchunks / 8;
+    if (s > 16) s = 16;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+
 // K % 64 == 0, N % 16 == 0, both positive, and N*K small enough for 64-bit byte arithmetic
 // and 32-bit group counts per row.
 inline bool weight_shape_ok(int64_t N, int64_t K) {

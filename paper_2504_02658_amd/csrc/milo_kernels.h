@@ -47,14 +47,26 @@ struct TiledArgs {
     int64_t ldx;
     uint64_t x_bytes;   // size of the X buffer in bytes (< 2 GiB: it is addressed with 32-bit offsets)
     int64_t N, K;       // weight shape (out x in)
-    f16* T[2];          // X V^T per weight stream, [rows x ldt] fp16, zero beyond the rank; written
-    int64_t ldt;        // by the launch's leading workgroup column, read by the others
+    // T = X V^T per weight stream, [rows x ldt] fp16, zero beyond the rank.  It is formed during the
+    // launch by the leading workgroup columns: column p multiplies its share of K into the fp32
+    // partial Tp[.] + p * t_part_stride, and whichever column finishes last adds the partials in
+    // column order, writes T and raises the tile's flag; the other workgroups read T after that.
+    f16* T[2];
+    int64_t ldt;
     uint64_t t_bytes;   // size of each T buffer in bytes
-    int v_tiles;        // 1 when a leading workgroup column forms T (some rank > 0), else 0
-    uint32_t* flags;    // per M-tile: [2t] T ready, [2t+1] readers done; zero between launches
+    float* Tp[2];       // partials, [t_parts][rows x ldt] fp32
+    uint64_t tp_bytes;  // size of each partial buffer in bytes (all parts)
+    int64_t t_part_stride;   // elements between consecutive parts
+    int t_parts;        // 0 when no weight has a compensator
+    int v_tiles;        // leading workgroup columns of the grid: t_parts (they work in split 0 only)
+    int ksplit;         // K splits (grid z); split z multiplies its share of the chunks
+    uint32_t* flags;    // per M-tile t: [4t] parts done, [4t+1] T ready, [4t+2] readers done; zero between launches
     uint32_t* flags_status;  // set non-zero if a wait ever gave up
-    void* out;          // EPI 0/1: fp16 [rows x ldo];  EPI 2: fp32 [.. x ldo]
+    // EPI 0: fp16 [rows x ldo], or with ksplit > 1 fp32 partial sums, split z at out + z * out_split_stride
+    // EPI 1: fp16 [rows x ldo];  EPI 2: fp16 [.. x ldo], split z at out + z * out_split_stride
+    void* out;
     int64_t ldo;
+    int64_t out_split_stride;   // elements
     const int32_t* out_rows;   // EPI 2: output row of tile row R (nullptr: R)
     const float* out_scale;    // EPI 2: factor per output row (nullptr: 1)
 };
@@ -63,6 +75,8 @@ enum { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_SCALE_SCATTER = 2 };
 
 // Launchers.  mb = tile rows / 32 (1, 2 or 4); m_tiles = grid extent over tiles.
 int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipStream_t stream);
+// Parts of T and K splits the launchers use for a K of nchunks 128-column chunks.
+int tiled_t_parts(int64_t K);
 
 constexpr int kDecDoneBytes = 8192;  // sign-off words: up to 2048 resident workgroups
 constexpr int kDecMaxWorkers = 32;  // workgroups forming T = X V^T in the decode kernel

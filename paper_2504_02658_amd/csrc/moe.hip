@@ -106,7 +106,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const RouteArgs a)
 }
 
 // y[t, h..h+3] = fp16( sum_j O[t*topk + j, h..h+3] ), slots in order, invalid ids skipped.
-__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ O,
+__global__ __launch_bounds__(256) void combine_kernel(const f16* __restrict__ O, int splits,
+                                                      int64_t split_stride,
                                                       const int32_t* __restrict__ ids, int E,
                                                       int topk, int64_t T, int64_t H,
                                                       f16* __restrict__ Y) {
@@ -117,9 +118,11 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
     for (int j = 0; j < topk; ++j) {
         const int id = ids[t * topk + j];
         if (id < 0 || id >= E) continue;
-        const f32x4 v = *reinterpret_cast<const f32x4*>(O + (t * topk + j) * H + h);
+        for (int s = 0; s < splits; ++s) {
+            const f16x4 v = *reinterpret_cast<const f16x4*>(O + s * split_stride + (t * topk + j) * H + h);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) sum[e] += v[e];
+            for (int e = 0; e < 4; ++e) sum[e] += (float)v[e];
+        }
     }
     f16x4 o;
 #pragma unroll
@@ -131,7 +134,9 @@ struct MoeLayout {
     int bm;
     int max_tiles;
     int64_t ldt;
-    size_t off_header, off_flags, off_sorted, off_token, off_tiles, off_t1, off_t3, off_h, off_o, total;
+    int parts_up, parts_down;   // parts of T = X V^T for the gate/up and the down projection
+    int splits_down;            // K splits of the down projection
+    size_t off_header, off_flags, off_sorted, off_token, off_tiles, off_t1, off_t3, off_tp1, off_tp3, off_h, off_o, total;
     int64_t max_tiles32;
 };
 
@@ -152,18 +157,25 @@ static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_m
     if (max_tiles > 65535) return false;
     L->max_tiles = (int)max_tiles;
     L->ldt = ((int64_t)r_max + 15) / 16 * 16;
-    if ((uint64_t)P * (uint64_t)L->ldt * 2 >= 0xFFFFFFF0ull) return false;
+    L->parts_up = r_max > 0 ? tiled_t_parts(H) : 0;
+    L->parts_down = r_max > 0 ? tiled_t_parts(F) : 0;
+    const int parts = L->parts_up > L->parts_down ? L->parts_up : L->parts_down;
+    if ((uint64_t)(parts > 0 ? parts : 1) * (uint64_t)P * (uint64_t)L->ldt * 4 >= 0xFFFFFFF0ull) return false;
+    // the down projection has few column tiles (hidden / 256): split K when they do not fill the chip
+    L->splits_down = tiled_k_splits(((P + L->bm - 1) / L->bm + E / 2) * ((H + 255) / 256), F);
     size_t off = 0;
     L->off_header = off; off = align_up(off + 64, 256);
     L->max_tiles32 = max_tiles32;
-    L->off_flags = off;  off = align_up(off + (size_t)max_tiles32 * 8, 256);
+    L->off_flags = off;  off = align_up(off + (size_t)max_tiles32 * 16, 256);
     L->off_sorted = off; off = align_up(off + (size_t)P * 4, 256);
     L->off_token = off;  off = align_up(off + (size_t)P * 4, 256);
     L->off_tiles = off;  off = align_up(off + (size_t)max_tiles32 * sizeof(TileDesc), 256);
     L->off_t1 = off;     off = align_up(off + (size_t)P * L->ldt * 2, 256);
     L->off_t3 = off;     off = align_up(off + (size_t)P * L->ldt * 2, 256);
+    L->off_tp1 = off;    off = align_up(off + (size_t)parts * P * L->ldt * 4, 256);
+    L->off_tp3 = off;    off = align_up(off + (size_t)L->parts_up * P * L->ldt * 4, 256);
     L->off_h = off;      off = align_up(off + (size_t)P * F * 2, 256);
-    L->off_o = off;      off = align_up(off + (size_t)P * H * 4, 256);
+    L->off_o = off;      off = align_up(off + (size_t)L->splits_down * P * H * 2, 256);
     L->total = off;
     return true;
 }
@@ -228,15 +240,17 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
     TileDesc* tiles = reinterpret_cast<TileDesc*>(ws + L.off_tiles);
     f16* T1 = reinterpret_cast<f16*>(ws + L.off_t1);
     f16* T3 = reinterpret_cast<f16*>(ws + L.off_t3);
+    float* Tp1 = reinterpret_cast<float*>(ws + L.off_tp1);
+    float* Tp3 = reinterpret_cast<float*>(ws + L.off_tp3);
     f16* Hbuf = reinterpret_cast<f16*>(ws + L.off_h);
-    float* O = reinterpret_cast<float*>(ws + L.off_o);
+    f16* O = reinterpret_cast<f16*>(ws + L.off_o);
     const int P = (int)(T * topk);
 
     RouteArgs ra;
     ra.ids = topk_ids; ra.P = P; ra.E = E; ra.bm = L.bm;
     ra.topk = topk; ra.sorted = sorted; ra.sorted_token = sorted_token; ra.tiles = tiles; ra.header = header;
     uint32_t* flags = reinterpret_cast<uint32_t*>(ws + L.off_flags);
-    ra.flags = flags; ra.n_flags = (int32_t)(2 * L.max_tiles32);
+    ra.flags = flags; ra.n_flags = (int32_t)(4 * L.max_tiles32);
     route_kernel<<<dim3((unsigned)E), dim3(kRouteThreads), (size_t)E * sizeof(int32_t), stream>>>(ra);
     int st = launch_status();
     if (st != MILO_OK) return st;
@@ -254,7 +268,9 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         ga.rs = rs; ga.X = reinterpret_cast<const f16*>(X); ga.ldx = H; ga.x_bytes = (uint64_t)T * H * 2;
         ga.N = F; ga.K = H;
         ga.T[0] = T1; ga.T[1] = T3; ga.ldt = L.ldt; ga.t_bytes = (uint64_t)P * L.ldt * 2;
-        ga.v_tiles = r_max > 0 ? 1 : 0; ga.flags = flags;
+        ga.Tp[0] = Tp1; ga.Tp[1] = Tp3; ga.tp_bytes = (uint64_t)L.parts_up * P * L.ldt * 4;
+        ga.t_part_stride = (int64_t)P * L.ldt; ga.t_parts = L.parts_up; ga.v_tiles = L.parts_up; ga.ksplit = 1;
+        ga.out_split_stride = 0; ga.flags = flags;
         ga.flags_status = reinterpret_cast<uint32_t*>(header + 2);
         ga.out = Hbuf; ga.ldo = F; ga.out_rows = nullptr; ga.out_scale = nullptr;
         st = launch_tiled(ga, 2, mb, EPI_SWIGLU, L.max_tiles, stream);
@@ -268,7 +284,9 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         da.rs = rs; da.X = Hbuf; da.ldx = F; da.x_bytes = (uint64_t)P * F * 2;
         da.N = H; da.K = F;
         da.T[0] = T1; da.T[1] = T1; da.ldt = L.ldt; da.t_bytes = (uint64_t)P * L.ldt * 2;
-        da.v_tiles = r_max > 0 ? 1 : 0; da.flags = flags;
+        da.Tp[0] = Tp1; da.Tp[1] = Tp1; da.tp_bytes = (uint64_t)L.parts_down * P * L.ldt * 4;
+        da.t_part_stride = (int64_t)P * L.ldt; da.t_parts = L.parts_down; da.v_tiles = L.parts_down;
+        da.ksplit = L.splits_down; da.out_split_stride = (int64_t)P * H; da.flags = flags;
         da.flags_status = reinterpret_cast<uint32_t*>(header + 2);
         da.out = O; da.ldo = H; da.out_rows = sorted; da.out_scale = topk_weights;
         st = launch_tiled(da, 1, mb, EPI_SCALE_SCATTER, L.max_tiles, stream);
@@ -281,12 +299,12 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
             for (int64_t t0 = 0; t0 < T; t0 += 65535) {
                 const int64_t nt = (T - t0) < 65535 ? (T - t0) : 65535;
                 combine_kernel<<<dim3(gx, (unsigned)nt), dim3(256), 0, stream>>>(
-                    O + t0 * topk * H, topk_ids + t0 * topk, E, topk, nt, H,
+                    O + t0 * topk * H, L.splits_down, (int64_t)P * H, topk_ids + t0 * topk, E, topk, nt, H,
                     reinterpret_cast<f16*>(Y) + t0 * H);
             }
         } else {
             combine_kernel<<<dim3(gx, (unsigned)T), dim3(256), 0, stream>>>(
-                O, topk_ids, E, topk, T, H, reinterpret_cast<f16*>(Y));
+                O, L.splits_down, (int64_t)P * H, topk_ids, E, topk, T, H, reinterpret_cast<f16*>(Y));
         }
         st = launch_status();
     }
