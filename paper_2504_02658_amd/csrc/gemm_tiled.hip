@@ -44,6 +44,7 @@ __device__ __forceinline__ TileInfo resolve_tile(const RowSpace& rs, int tile, i
         const TileDesc td = rs.tiles[tile];
         ti.row0 = td.row0;
         ti.rows = td.rows;
+        if (td.rows <= 0) ti.valid = false;          // an empty slot of the tile list
         const WeightDev* ew = reinterpret_cast<const WeightDev*>(rs.experts + td.expert);
         ti.w[0] = ew[rs.which[0]];
         ti.w[1] = ew[rs.which[NW - 1]];

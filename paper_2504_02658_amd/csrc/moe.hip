@@ -28,78 +28,113 @@ struct RouteArgs {
     int32_t* header;        // [0] routing status, [1] number of tiles, [2] wait status
     uint32_t* flags;        // per-tile control words of the GEMM kernels, cleared here
     int32_t n_flags;
+    int32_t max_tiles;      // slots of the tile list: ceil(P / bm) + E
 };
 
-// One workgroup per expert.  Every workgroup histograms all ids itself (integer LDS atomics),
-// so no workgroup depends on another one and a single launch suffices.
+// One workgroup per expert; no workgroup depends on another one, so a single launch suffices.
+// A thread owns a contiguous range of the pairs and counts the ids equal to its expert and the
+// ids below it: the stable position of a pair inside its expert's group is the number of matches
+// in the threads before it (one scan over the workgroup) plus the matches before it in its own
+// range, and the group starts at the number of ids below the expert.  No histogram over all
+// experts is needed (LDS atomics of a whole workgroup on the few popular experts serialize
+// badly): expert e places its tiles from slot floor(start_e / bm) + e of the tile list, which
+// never overlaps the next expert's first slot, and marks the slots up to there as empty.
 __global__ __launch_bounds__(kRouteThreads) void route_kernel(const RouteArgs a) {
-    extern __shared__ int32_t hist[];               // [E]
-    __shared__ int32_t s_off, s_tile0, s_tiles_total, s_bad, s_running;
-    __shared__ int32_t wcount[kRouteThreads / 64];
+    __shared__ int32_t s_bad;
+    __shared__ int32_t wsum_eq[kRouteThreads / 64], wsum_less[kRouteThreads / 64];
 
     const int e = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < a.E; i += kRouteThreads) hist[i] = 0;
-    if (tid == 0) { s_off = 0; s_tile0 = 0; s_tiles_total = 0; s_bad = 0; s_running = 0; }
+    if (tid == 0) s_bad = 0;
     __syncthreads();
-    int bad = 0;
-    for (int i = tid; i < a.P; i += kRouteThreads) {
-        const int id = a.ids[i];
-        if (id >= 0 && id < a.E) atomicAdd(&hist[id], 1); else bad = 1;
-    }
-    if (bad) atomicOr(&s_bad, 1);
-    __syncthreads();
-    {
-        int off = 0, t0 = 0, tt = 0;
-        for (int i = tid; i < a.E; i += kRouteThreads) {
-            const int c = hist[i];
-            const int nt = (c + a.bm - 1) / a.bm;
-            tt += nt;
-            if (i < e) { off += c; t0 += nt; }
-        }
-        if (off) atomicAdd(&s_off, off);
-        if (t0) atomicAdd(&s_tile0, t0);
-        if (tt) atomicAdd(&s_tiles_total, tt);
-    }
-    __syncthreads();
-    const int off_e = s_off, tile0 = s_tile0, count = hist[e];
 
+    // a thread's range: a multiple of 16 pairs, read 16 at a time with four 16-byte loads in flight
+    // (one id per load would pay the memory latency once per pair)
+    const int per = ((a.P + kRouteThreads - 1) / kRouteThreads + 15) & ~15;
+    const int lo = tid * per < a.P ? tid * per : a.P;
+    const int hi = lo + per < a.P ? lo + per : a.P;
+    int n_eq = 0, n_less = 0, bad = 0;
+    auto load16 = [&](int i0, int32_t (&v)[16]) {
+        if (i0 + 16 <= a.P) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int4 q = *reinterpret_cast<const int4*>(a.ids + i0 + 4 * j);
+                v[4 * j] = q.x; v[4 * j + 1] = q.y; v[4 * j + 2] = q.z; v[4 * j + 3] = q.w;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) v[j] = i0 + j < a.P ? a.ids[i0 + j] : e + 1;   // padding: no match
+        }
+    };
+    for (int i0 = lo; i0 < hi; i0 += 16) {
+        int32_t v[16];
+        load16(i0, v);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            if (i0 + j >= hi) break;
+            const int id = v[j];
+            if (id >= 0 && id < a.E) {
+                n_eq += id == e;
+                n_less += id < e;
+            } else {
+                bad = 1;
+            }
+        }
+    }
+    // inclusive scan of n_eq within the wave, wave totals to LDS
+    int scan = n_eq;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int v = __shfl_up(scan, d, 64);
+        if (lane >= d) scan += v;
+    }
+    int less = n_less;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) less += __shfl_xor(less, d, 64);
+    if (lane == 63) wsum_eq[wave] = scan;
+    if (lane == 0) wsum_less[wave] = less;
+    __syncthreads();
+    int before = 0, off_e = 0, count = 0;
+    for (int w = 0; w < kRouteThreads / 64; ++w) {
+        if (w < wave) before += wsum_eq[w];
+        count += wsum_eq[w];
+        off_e += wsum_less[w];
+    }
     // stable scatter of the pairs routed to expert e
-    for (int base = 0; base < a.P; base += kRouteThreads) {
-        const int i = base + tid;
-        const bool mine = (i < a.P) && (a.ids[i] == e);
-        const unsigned long long bal = __ballot(mine);
-        if (lane == 0) wcount[wave] = __popcll(bal);
-        __syncthreads();
-        int before = s_running;
-        for (int w = 0; w < wave; ++w) before += wcount[w];
-        if (mine) {
-            const int pos = off_e + before + __popcll(bal & ((1ull << lane) - 1ull));
-            a.sorted[pos] = i;
-            a.sorted_token[pos] = i / a.topk;
+    int pos = off_e + before + scan - n_eq;
+    if (n_eq) {
+        for (int i0 = lo; i0 < hi; i0 += 16) {
+            int32_t v[16];
+            load16(i0, v);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                if (i0 + j < hi && v[j] == e) {
+                    a.sorted[pos] = i0 + j;
+                    a.sorted_token[pos] = (i0 + j) / a.topk;
+                    ++pos;
+                }
+            }
         }
-        __syncthreads();
-        if (tid == 0) {
-            int tot = 0;
-            for (int w = 0; w < kRouteThreads / 64; ++w) tot += wcount[w];
-            s_running += tot;
-        }
-        __syncthreads();
     }
-
+    // this expert's slots of the tile list: its tiles, then empty slots up to the next expert's first
+    const int tile0 = off_e / a.bm + e;
+    const int tile1 = (e + 1 < a.E) ? (off_e + count) / a.bm + e + 1 : a.max_tiles;
     const int nt = (count + a.bm - 1) / a.bm;
-    for (int i = tid; i < nt; i += kRouteThreads) {
+    for (int i = tid; i < tile1 - tile0; i += kRouteThreads) {
         TileDesc td;
         td.expert = e;
-        td.row0 = off_e + i * a.bm;
-        td.rows = (count - i * a.bm) < a.bm ? (count - i * a.bm) : a.bm;
+        td.row0 = off_e + (i < nt ? i * a.bm : 0);
+        td.rows = i < nt ? ((count - i * a.bm) < a.bm ? (count - i * a.bm) : a.bm) : 0;
         td.pad = 0;
         a.tiles[tile0 + i] = td;
     }
     if (e == 0) {
+        // every workgroup has looked at all ids; this one reports the ones out of range
+        if (bad) atomicOr(&s_bad, 1);
         for (int i = tid; i < a.n_flags; i += kRouteThreads) a.flags[i] = 0u;
+        __syncthreads();
         if (tid == 0) {
             a.header[0] = s_bad ? MILO_ERR_ROUTING : MILO_OK;
-            a.header[1] = s_tiles_total;
+            a.header[1] = a.max_tiles;
             a.header[2] = 0;
         }
     }
@@ -251,7 +286,8 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
     ra.topk = topk; ra.sorted = sorted; ra.sorted_token = sorted_token; ra.tiles = tiles; ra.header = header;
     uint32_t* flags = reinterpret_cast<uint32_t*>(ws + L.off_flags);
     ra.flags = flags; ra.n_flags = (int32_t)(4 * L.max_tiles32);
-    route_kernel<<<dim3((unsigned)E), dim3(kRouteThreads), (size_t)E * sizeof(int32_t), stream>>>(ra);
+    ra.max_tiles = L.max_tiles;
+    route_kernel<<<dim3((unsigned)E), dim3(kRouteThreads), 0, stream>>>(ra);
     int st = launch_status();
     if (st != MILO_OK) return st;
 
