@@ -76,4 +76,11 @@ if bad or n == 0 or waits == 0:
 print("tiled kernel: no scratch access around %d hand-counted waits in %d variants" % (waits, n))
 PY
 hipcc --offload-arch=gfx950 -shared -fPIC -o "$OUT/libmilo.so" _build/pack.o _build/gemm_tiled.o _build/gemm_decode.o _build/moe.o _build/api.o
+# Every kernel the host code launches must have its launch stub in the library (a stub that the
+# compiler failed to emit only shows up as an undefined symbol when the library is loaded).
+if nm -u "$OUT/libmilo.so" | grep -q "__device_stub__"; then
+    echo "libmilo.so has undefined kernel launch stubs:" >&2
+    nm -u "$OUT/libmilo.so" | grep "__device_stub__" >&2
+    exit 1
+fi
 echo "built $OUT/libmilo.so"

@@ -348,38 +348,52 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[s][mb][v] = 0.0f;
 
-    // One chunk's loads of this wave are always PER instructions (chunks past the end read out of
-    // range, which costs no memory traffic), in eight parts: part t = piece t of the two weight
-    // units (16-byte words, 8-byte words, scale, zero-point of stream t % 2) and, while there are
-    // any left, activation copy t into stage `slot`.  All parts are issued when a chunk starts:
-    // a wave needs some eighty cycles to get one vector memory instruction out while its three
-    // neighbours do the same, and that time is best spent while the other workgroup on the CU
-    // multiplies (spreading the parts over the steps of the chunk was slower).
+    // One chunk's loads of this wave are always PER instructions: the two weight units (four loads
+    // each), then the NCP activation copies into stage `slot`.  All are issued when a chunk starts:
+    // the time a wave needs to get them out is best spent while the other workgroup on the CU
+    // multiplies (spreading them over the steps of the chunk was slower).  The common case costs
+    // an add per instruction: unit indices advance by 32 per chunk (a row without data starts at
+    // 2^27, far past every weight, and stays there), copy offsets by 256 bytes.  Chunks past the
+    // end of this workgroup's share are requested like any other: nobody looks at them, and a
+    // request past the end of a buffer returns zeros.  Only the last chunk of a K that is an odd
+    // number of groups takes the careful path, where the upper 64 columns must read as zero
+    // instead of running into the next row.
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);        // known to be uniform
-    auto issue_part = [&](int t, int c, int slot, RawUnit (&ru)[2], uint32_t (&uidx)[2]) {
-        const int s = t & 1;
-        if (t < 2) {
-            const int g = 2 * c + h;
-            uidx[s] = (g < G && c < c_end && ubase[s] != kOobUnit) ? ubase[s] + (uint32_t)g * 16u : kOobUnit;
-        }
-        switch (t >> 1) {
-            case 0: ru[s].a = buf_load16(wbuf[s].a, uidx[s] * 16u); break;
-            case 1: ru[s].b = buf_load8(wbuf[s].b, uidx[s] * 8u); break;
-            case 2: ru[s].s = buf_load2(wbuf[s].s, uidx[s] * 2u); break;
-            default: ru[s].z = buf_load2(wbuf[s].z, uidx[s] * 2u); break;
+    uint32_t ucur[2];               // unit of this lane in the chunk to be requested next
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+        ucur[s] = ubase[s] != kOobUnit ? ubase[s] + (uint32_t)(2 * c_begin + h) * 16u : (1u << 27);
+    auto issue = [&](int c, int slot, RawUnit (&ru)[2]) {
+        const bool ragged = ktail && c == nchunks - 1;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const uint32_t u = (ragged && h == 1) ? (1u << 27) : ucur[s];
+            ru[s].a = buf_load16(wbuf[NW == 1 ? 0 : s].a, u * 16u);
+            ru[s].b = buf_load8(wbuf[NW == 1 ? 0 : s].b, u * 8u);
+            ru[s].s = buf_load2(wbuf[NW == 1 ? 0 : s].s, u * 2u);
+            ru[s].z = buf_load2(wbuf[NW == 1 ? 0 : s].z, u * 2u);
+            ucur[s] += 32u;
         }
         asm volatile("" ::: "memory");
+        unsigned char* const stage = smem + slot * STAGE + wave_s * NCP * 1024;
+        const uint32_t cbytes = (uint32_t)c * 256u;
+        // (the offset goes through a named variable: with an expression as the builtin's argument
+        // the host pass of the compiler silently drops the kernel's launch stub)
+        if (!ragged) {
 #pragma unroll
-        for (int i = t; i < NCP; i += 8) {
-            unsigned char* stage = smem + slot * STAGE;
-            const bool past = c >= c_end;
-            const bool last_half = ktail && c == nchunks - 1;
-            uint32_t off = xoff[i] + (uint32_t)c * 256u;
-            if (past || (last_half && xhi[i])) off = kOobHalf;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (LdsPtr)(stage + (wave_s * NCP + i) * 1024), 16, off, 0, 0,
-                                                     0);
-            asm volatile("" ::: "memory");
+            for (int i = 0; i < NCP; ++i) {
+                const uint32_t off = xoff[i] + cbytes;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (LdsPtr)(stage + i * 1024), 16, off, 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NCP; ++i) {
+                uint32_t off = xoff[i] + cbytes;
+                if (xhi[i]) off = kOobHalf;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (LdsPtr)(stage + i * 1024), 16, off, 0, 0, 0);
+            }
         }
+        asm volatile("" ::: "memory");
     };
     // Row blocks of 32 actually present in this tile.  The K loop is instantiated per count, so
     // that blocks past the tile's rows cost nothing and the loop body has no branches (the
@@ -439,11 +453,8 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
         // (The count relies on the compiler adding no memory operation of its own, i.e. on the
         // kernel not using scratch memory; the build script checks that.)
         RawUnit ring[PD][2];
-        uint32_t uidx[2];
 #pragma unroll
-        for (int i = 0; i < PD - 1; ++i)
-#pragma unroll
-            for (int t = 0; t < 8; ++t) issue_part(t, c_begin + i, i, ring[i], uidx);
+        for (int i = 0; i < PD - 1; ++i) issue(c_begin + i, i, ring[i]);
         for (int c0 = c_begin; c0 < c_end; c0 += PD) {
 #pragma unroll
             for (int slot = 0; slot < PD; ++slot) {
@@ -451,9 +462,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                 if (c >= c_end) break;
                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PD - 2) * PER) : "memory");
                 __syncthreads();        // everyone's copies of chunk c landed; everyone left chunk c-1
-#pragma unroll
-                for (int t = 0; t < 8; ++t)
-                    issue_part(t, c + PD - 1, (slot + PD - 1) % PD, ring[(slot + PD - 1) % PD], uidx);
+                issue(c + PD - 1, (slot + PD - 1) % PD, ring[(slot + PD - 1) % PD]);
                 compute(slot, ring[slot], [](int) {});
             }
         }

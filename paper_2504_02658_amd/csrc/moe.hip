@@ -197,7 +197,8 @@ static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_m
     const int parts = L->parts_up > L->parts_down ? L->parts_up : L->parts_down;
     if ((uint64_t)(parts > 0 ? parts : 1) * (uint64_t)P * (uint64_t)L->ldt * 4 >= 0xFFFFFFF0ull) return false;
     // the down projection has few column tiles (hidden / 256): split K when they do not fill the chip
-    L->splits_down = tiled_k_splits(((P + L->bm - 1) / L->bm + E / 2) * ((H + 255) / 256), F);
+    // (counted in full tiles: the partly filled last tile of an expert is cheap)
+    L->splits_down = tiled_k_splits(((P + L->bm - 1) / L->bm) * ((H + 255) / 256), F);
     size_t off = 0;
     L->off_header = off; off = align_up(off + 64, 256);
     L->max_tiles32 = max_tiles32;
