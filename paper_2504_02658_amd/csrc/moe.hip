@@ -140,6 +140,48 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const RouteArgs a)
     }
 }
 
+// Work list of the grouped GEMMs: the slots the experts filled, compacted and put longest first
+// (full tiles in expert order, then the partly filled ones, empty slots dropped), so that the
+// dispatcher, which hands out workgroups in grid order, ends with the short items.  One
+// workgroup; a thread owns a contiguous range of slots and two scans give every tile its place.
+__global__ __launch_bounds__(kRouteThreads) void order_tiles_kernel(const TileDesc* __restrict__ slots,
+                                                                    int n_slots, int bm,
+                                                                    TileDesc* __restrict__ tiles,
+                                                                    int32_t* __restrict__ header) {
+    __shared__ int32_t wfull[kRouteThreads / 64], wpart[kRouteThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = (n_slots + kRouteThreads - 1) / kRouteThreads;
+    const int lo = tid * per < n_slots ? tid * per : n_slots;
+    const int hi = lo + per < n_slots ? lo + per : n_slots;
+    int nfull = 0, npart = 0;
+    for (int i = lo; i < hi; ++i) {
+        const int rows = slots[i].rows;
+        nfull += rows >= bm;
+        npart += rows > 0 && rows < bm;
+    }
+    int sfull = nfull, spart = npart;          // inclusive scans within the wave
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int a = __shfl_up(sfull, d, 64), b = __shfl_up(spart, d, 64);
+        if (lane >= d) { sfull += a; spart += b; }
+    }
+    if (lane == 63) { wfull[wave] = sfull; wpart[wave] = spart; }
+    __syncthreads();
+    int bfull = 0, bpart = 0, tfull = 0, tpart = 0;
+    for (int w = 0; w < kRouteThreads / 64; ++w) {
+        if (w < wave) { bfull += wfull[w]; bpart += wpart[w]; }
+        tfull += wfull[w];
+        tpart += wpart[w];
+    }
+    int pf = bfull + sfull - nfull, pp = tfull + bpart + spart - npart;
+    for (int i = lo; i < hi; ++i) {
+        const TileDesc td = slots[i];
+        if (td.rows >= bm) tiles[pf++] = td;
+        else if (td.rows > 0) tiles[pp++] = td;
+    }
+    if (tid == 0) header[1] = tfull + tpart;
+}
+
 // y[t, h..h+3] = fp16( sum_j O[t*topk + j, h..h+3] ), slots in order, invalid ids skipped.
 __global__ __launch_bounds__(256) void combine_kernel(const f16* __restrict__ O, int splits,
                                                       int64_t split_stride,
@@ -171,7 +213,7 @@ struct MoeLayout {
     int64_t ldt;
     int parts_up, parts_down;   // parts of T = X V^T for the gate/up and the down projection
     int splits_down;            // K splits of the down projection
-    size_t off_header, off_flags, off_sorted, off_token, off_tiles, off_t1, off_t3, off_tp1, off_tp3, off_h, off_o, total;
+    size_t off_header, off_flags, off_sorted, off_token, off_slots, off_tiles, off_t1, off_t3, off_tp1, off_tp3, off_h, off_o, total;
     int64_t max_tiles32;
 };
 
@@ -205,6 +247,7 @@ static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_m
     L->off_flags = off;  off = align_up(off + (size_t)max_tiles32 * 16, 256);
     L->off_sorted = off; off = align_up(off + (size_t)P * 4, 256);
     L->off_token = off;  off = align_up(off + (size_t)P * 4, 256);
+    L->off_slots = off;  off = align_up(off + (size_t)max_tiles32 * sizeof(TileDesc), 256);
     L->off_tiles = off;  off = align_up(off + (size_t)max_tiles32 * sizeof(TileDesc), 256);
     L->off_t1 = off;     off = align_up(off + (size_t)P * L->ldt * 2, 256);
     L->off_t3 = off;     off = align_up(off + (size_t)P * L->ldt * 2, 256);
@@ -273,6 +316,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
     int32_t* header = reinterpret_cast<int32_t*>(ws + L.off_header);
     int32_t* sorted = reinterpret_cast<int32_t*>(ws + L.off_sorted);
     int32_t* sorted_token = reinterpret_cast<int32_t*>(ws + L.off_token);
+    TileDesc* slots = reinterpret_cast<TileDesc*>(ws + L.off_slots);
     TileDesc* tiles = reinterpret_cast<TileDesc*>(ws + L.off_tiles);
     f16* T1 = reinterpret_cast<f16*>(ws + L.off_t1);
     f16* T3 = reinterpret_cast<f16*>(ws + L.off_t3);
@@ -284,12 +328,15 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
 
     RouteArgs ra;
     ra.ids = topk_ids; ra.P = P; ra.E = E; ra.bm = L.bm;
-    ra.topk = topk; ra.sorted = sorted; ra.sorted_token = sorted_token; ra.tiles = tiles; ra.header = header;
+    ra.topk = topk; ra.sorted = sorted; ra.sorted_token = sorted_token; ra.tiles = slots; ra.header = header;
     uint32_t* flags = reinterpret_cast<uint32_t*>(ws + L.off_flags);
     ra.flags = flags; ra.n_flags = (int32_t)(4 * L.max_tiles32);
     ra.max_tiles = L.max_tiles;
     route_kernel<<<dim3((unsigned)E), dim3(kRouteThreads), 0, stream>>>(ra);
     int st = launch_status();
+    if (st != MILO_OK) return st;
+    order_tiles_kernel<<<dim3(1), dim3(kRouteThreads), 0, stream>>>(slots, L.max_tiles, L.bm, tiles, header);
+    st = launch_status();
     if (st != MILO_OK) return st;
 
     RowSpace rs;
