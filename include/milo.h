@@ -56,7 +56,8 @@ typedef uint16_t milo_half;
 enum milo_status {
     MILO_OK = 0,
     MILO_ERR_NULL = 1,       /* a required pointer is NULL                                  */
-    MILO_ERR_SHAPE = 2,      /* K % 64, N % 16, M < 1, a size overflows, bad top-k / E      */
+    MILO_ERR_SHAPE = 2,      /* K % 64, N % 16, M < 1, a size overflows (N*K/64 > 2^26, K > 2^26, an
+                                array the kernels address with 32-bit offsets), bad top-k / E */
     MILO_ERR_GROUP = 3,      /* group_size != 64                                            */
     MILO_ERR_RANK = 4,       /* r < 0, r > min(N, K), or r > 0 with U or V NULL             */
     MILO_ERR_WORKSPACE = 5,  /* workspace NULL or smaller than the *_workspace() size       */
@@ -117,7 +118,11 @@ int milo_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
  *   once with milo_workspace_init; beyond the control block its contents are scratch.  Calls that
  *   share a workspace must be ordered on one stream (concurrent calls would race on it).
  * M <= 16 takes the weight-streaming decode kernel (a single launch that also forms X V^T),
- * larger M the tiled MFMA kernel.
+ * larger M the tiled MFMA kernel (which also forms X V^T inside the launch; when the problem has
+ * too few tiles to fill the device it splits K over workgroups and a second small kernel adds the
+ * fp32 partial sums in a fixed order, so the result is rounded once and two runs agree bit for bit).
+ * The workspace size depends on the device the call is made on (the K split follows its number of
+ * compute units): query it with that device current.
  * Errors: NULL, SHAPE, RANK, WORKSPACE, ALIGN, HIP.
  */
 size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int r);
@@ -165,8 +170,9 @@ int milo_moe_w3lr_check_experts(const milo_w3lr_expert* experts, int E, int64_t 
  *   workspace    at least milo_moe_w3lr_workspace(T, H, F, E, topk, r_max) bytes
  * An id outside 0..E-1 contributes nothing and raises a flag that
  * milo_moe_w3lr_routing_status() reports; an expert with no tokens is legal.
- * The combine over the top-k slots is done in a fixed order in fp32 with one rounding, so two
- * runs give bit-identical results.
+ * Each routed pair's weighted expert output is kept as fp16 (per K split of the down projection,
+ * when that is split); the combine adds a token's slots (and splits) in a fixed order in fp32 and
+ * rounds once, so two runs give bit-identical results.
  * Errors: NULL, SHAPE, RANK, WORKSPACE, ALIGN, HIP.
  */
 size_t milo_moe_w3lr_workspace(int64_t T, int64_t H, int64_t F, int E, int topk, int r_max);

@@ -1,12 +1,14 @@
 // milo_moe_w3lr_forward: top-k routed SwiGLU experts over compensated W3A16 linears.
 //
 // Launch sequence on the caller's stream (no host synchronisation in between):
-//   route     group the (token, slot) pairs per expert: stable counting sort + M-tile list
-//   T13       T1 = X V1^T, T3 = X V3^T per expert (low-rank inputs of gate and up projection)
-//   gate/up   H = SiLU(lin_w1(x)) * lin_w3(x), both projections in one grouped launch
-//   T2        T2 = H V2^T
-//   down      O[pair] = gate_weight * lin_w2(H)       (fp32, one row per routed pair)
-//   combine   y_t = fp16( sum over the token's slots, in slot order, of O )
+//   route     group the (token, slot) pairs per expert: stable placement by counting and scans,
+//             and each expert's M-tiles in its own slots of a tile list
+//   order     work list = the filled slots, full tiles first, then the partly filled ones
+//   gate/up   H = SiLU(lin_w1(x)) * lin_w3(x), both projections in one grouped launch, which
+//             also forms T1 = X V1^T and T3 = X V3^T (low-rank inputs) in its leading columns
+//   down      O[split][pair] = gate_weight * lin_w2(H) over the split's share of K (fp16, one row
+//             per routed pair); T2 = H V2^T is formed inside this launch as well
+//   combine   y_t = fp16( sum over the token's slots and the K splits, in a fixed order, of O )
 #include <stdlib.h>
 
 #include "milo_host.h"

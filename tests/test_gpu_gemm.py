@@ -162,3 +162,50 @@ def test_c2_mixtral_down_projection_prefill():
     ow = oracle_weight(W, c.r, seed=c.seed)
     pw = gpu_weight(W, ow)
     assert_close(_run(X, pw), oracle.w3lr_linear(X, **ow), c.name)
+
+
+def test_k_splits_and_t_parts_many_chunks():
+    # few tiles and a long K: the tiled kernel splits K over workgroups (partial sums added in
+    # order by a second kernel) and forms X V^T in several parts; odd number of groups as well
+    _check_case(48, 512, 4096, 24, seed=301)
+    _check_case(200, 256, 8256, 72, seed=302)           # 129 groups
+
+
+def test_graph_replay_matches_eager_and_needs_no_reset():
+    # the kernels leave their control words clean: a captured graph of calls that share one
+    # workspace per shape can be replayed with eager work in between, bit for bit
+    import torch
+    from paper_2504_02658_amd import api
+    cases = []
+    for M, N, K, r, seed in ((16, 1024, 4096, 32, 71), (7, 272, 1408, 8, 72), (96, 512, 4096, 24, 73)):
+        case = wl.LinearCase("t", M=M, N=N, K=K, r=r, seed=seed)
+        X, W = wl.linear_inputs(case)
+        pw = gpu_weight(W, oracle_weight(W, r, seed=seed), check_pack=False)
+        Xd = torch.from_numpy(X).cuda()
+        ws = api.new_workspace(api.gemm_workspace_bytes(M, N, K, r), Xd.device)
+        out = torch.empty((M, N), dtype=torch.float16, device=Xd.device)
+        cases.append((Xd, pw, ws, out))
+    eager = [api.w3lr_gemm(Xd, pw, workspace=ws).clone() for Xd, pw, ws, _ in cases]
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for Xd, pw, ws, out in cases:
+            api.w3lr_gemm(Xd, pw, out=out, workspace=ws)
+    torch.cuda.current_stream().wait_stream(stream)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(2):                     # back-to-back calls on the same workspaces
+            for Xd, pw, ws, out in cases:
+                api.w3lr_gemm(Xd, pw, out=out, workspace=ws)
+    for rep in range(3):
+        for _, _, _, out in cases:
+            out.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        for (_, _, _, out), ref in zip(cases, eager):
+            assert torch.equal(out, ref), f"replay {rep} differs from the eager result"
+        # eager work and a synchronisation between the replays
+        again = api.w3lr_gemm(cases[0][0], cases[0][1], workspace=cases[0][2])
+        torch.cuda.synchronize()
+        assert torch.equal(again, eager[0])
