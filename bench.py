@@ -6,7 +6,7 @@ X fp16 [16 x 4096], W [14336 x 4096] 3-bit group-64 with a rank-32 compensator. 
 one milo_w3lr_gemm call.  The weight is rotated through >= 24 distinct copies (> 2x the 256 MB
 Infinity Cache) so that every step streams its weight from HBM ("cold" protocol); the steps are
 captured in a HIP graph so that Python call overhead does not throttle a microsecond-scale kernel.
-value = (packed codes + scales + zeros + U + V bytes) / time per step.
+value = (packed blob: codes, scales, zero-points; + U + V bytes) / time per step.
 
 Prints ONE JSON line.  --extra adds M = 1 / 4, cache-resident ("hot") numbers, the prefill GEMM
 (c2) and the two MoE layers (c3, c4) to an "extra" object.
@@ -125,7 +125,7 @@ def main():
     W, pw = build_linear(case)
     copies = [pw] + [compress.clone_weight(pw) for _ in range(args.copies - 1)]
     wbytes = pw.weight_bytes()
-    code_bytes = pw.q3.numel() + 2 * pw.scales.numel() + 2 * pw.zeros.numel()
+    code_bytes = pw.q3.numel()           # codes, scales and zero-points
 
     def decode_bench(M, weights, steps, warmup):
         X = torch.from_numpy(wl.gen_activations(M, case.K, case.seed)).to(dev)

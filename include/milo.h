@@ -8,7 +8,7 @@
  *      Y = X * dequant(Q3)^T + (X * V^T) * U^T
  *
  *   X  [M x K]  fp16 activations, row-major
- *   W  [N x K]  weight (out x in); Q3 holds its 3-bit codes q in 0..7,
+ *   W  [N x K]  weight (out x in); the Q3 blob holds its 3-bit codes q in 0..7 and
  *               one fp16 scale s and one fp16 zero-point z per group of 64
  *               consecutive k of a row:  W_dq[n,k] = s[n,g] * (q[n,k] - z[n,g])
  *   U  [N x r], V [r x K]  fp16 low-rank compensator of rank r (r may be 0)
@@ -27,19 +27,20 @@
  *     (the only group size of the paper's kernel, appendix "Correctness Test").
  *   - Pointers must be 16-byte aligned; inputs and outputs must not alias.
  *
- * Packed format ("Q3 blob", exactly 3 bits per weight, Section 3.3
- * "Zero bit waste 3-bit weights packing"; the concrete layout is this
- * library's own):
- *   - unit(n, g) = the 64 codes of row n, group g; units are ordered
+ * Packed format ("Q3 blob": exactly 3 bits per weight for the codes, Section 3.3 "Zero bit
+ * waste 3-bit weights packing", plus the two fp16 parameters of every group of 64, i.e. 28 bytes
+ * per group = 3.5 bits per weight in total; the concrete layout is this library's own):
+ *   - unit(n, g) = the 64 codes of row n, group g, with its scale and zero-point; units are ordered
  *         u = ((n / 16) * (K / 64) + g) * 16 + n % 16
- *   - a unit is six little-endian 32-bit words d0..d5; plane A (first N*K/4
- *     bytes of the blob) stores d0..d3 of unit u at byte 16u, plane B (the next
- *     N*K/8 bytes) stores d4, d5 at byte 8u
+ *   - the codes of a unit are six little-endian 32-bit words d0..d5; plane A (first N*K/4 bytes of
+ *     the blob) stores d0..d3 of unit u at byte 16u, plane B (the next 3*N*K/16 bytes) stores at
+ *     byte 12u the three words d4, d5, p, where p = scale bits | zero-point bits << 16 (both
+ *     IEEE binary16)
  *   - the unit's codes form pairs P = (q[2P], q[2P+1]) = (lo, hi); for P < 30,
  *     word j = P / 5, slot c = P % 5: lo in bits 3c..3c+2, hi in bits
  *     16+3c..16+3c+2; bits 15 and 31 of words 0,1,2 carry bits 0,1,2 of pair 30
- *     (lo in bit 15, hi in bit 31), those of words 3,4,5 carry pair 31
- *   - scales and zeros are fp16 arrays of N*K/64 entries in the same unit order.
+ *     (lo in bit 15, hi in bit 31), those of words 3,4,5 carry pair 31.
+ *   A kernel lane fetches a whole unit with one 16-byte and one 12-byte load.
  */
 #ifndef MILO_H
 #define MILO_H
@@ -72,7 +73,7 @@ const char* milo_status_string(int status);
 /* Library version, major*10000 + minor*100 + patch. */
 int milo_version(void);
 
-/* Bytes of the Q3 blob of an [N x K] weight: exactly N*K*3/8 (0 if the shape is invalid). */
+/* Bytes of the Q3 blob of an [N x K] weight: exactly N*K*7/16 (0 if the shape is invalid). */
 size_t milo_w3_packed_bytes(int64_t N, int64_t K);
 
 /*
@@ -81,23 +82,24 @@ size_t milo_w3_packed_bytes(int64_t N, int64_t K);
  * all in binary32 with round-half-even and no fused multiply-add; a group whose fp16 scale is
  * zero or not finite stores s = 1, z = fp16(-min), q = 0.
  *   W       [N x K] fp32 row-major (device, read only)
- *   q3      out, milo_w3_packed_bytes(N, K) bytes
- *   scales  out, N*K/64 fp16 in unit order;  zeros likewise
+ *   q3      out, milo_w3_packed_bytes(N, K) bytes (codes, scales and zero-points)
  * Errors: NULL, SHAPE, GROUP, ALIGN, HIP.
  */
-int milo_pack_w3(const float* W, int64_t N, int64_t K, int group_size,
-                 void* q3, milo_half* scales, milo_half* zeros, void* stream);
+int milo_pack_w3(const float* W, int64_t N, int64_t K, int group_size, void* q3, void* stream);
 
-/* Test aid: codes[n*K + k] = q[n,k] as bytes, from a Q3 blob. */
-int milo_unpack_w3(const void* q3, int64_t N, int64_t K, uint8_t* codes, void* stream);
+/*
+ * Test aid: the parts of a Q3 blob.  codes[n*K + k] = q[n,k] as bytes; scales and zeros
+ * [N x K/64] fp16 row-major.  Each output may be NULL (not all three).
+ */
+int milo_unpack_w3(const void* q3, int64_t N, int64_t K, uint8_t* codes, milo_half* scales,
+                   milo_half* zeros, void* stream);
 
 /*
  * Dequantize a packed weight to dense fp16 (Eq. wdq), W_dq [N x K] row-major, with the same
  * in-register conversion the GEMM kernels use.  Used to build the residual W - W_dq that the
  * compensator is fitted to, and by the tests.
  */
-int milo_dequant_w3(const void* q3, const milo_half* scales, const milo_half* zeros,
-                    int64_t N, int64_t K, milo_half* W_dq, void* stream);
+int milo_dequant_w3(const void* q3, int64_t N, int64_t K, milo_half* W_dq, void* stream);
 
 /*
  * Prepare a freshly allocated workspace (for milo_w3lr_gemm or milo_moe_w3lr_forward): zero-fills
@@ -112,7 +114,7 @@ int milo_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * One compensated W3A16 linear:  Y = X dequant(Q3)^T + (X V^T) U^T.
- *   X [M x K] fp16;  q3/scales/zeros as written by milo_pack_w3 (zeros may be any finite fp16,
+ *   X [M x K] fp16;  q3 as written by milo_pack_w3 (its zero-points may be any finite fp16,
  *   integer or not);  U [N x r], V [r x K] fp16 row-major, ignored when r == 0;  Y [M x N] fp16.
  *   workspace: at least milo_w3lr_gemm_workspace(M, N, K, r) bytes of device memory, prepared
  *   once with milo_workspace_init; beyond the control block its contents are scratch.  Calls that
@@ -127,15 +129,12 @@ int milo_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
  */
 size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int r);
 int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t K,
-                   const void* q3, const milo_half* scales, const milo_half* zeros,
-                   const milo_half* U, const milo_half* V, int r,
+                   const void* q3, const milo_half* U, const milo_half* V, int r,
                    milo_half* Y, void* workspace, size_t workspace_bytes, void* stream);
 
 /* One packed weight with its compensator (all device pointers). */
 typedef struct milo_w3lr_weight {
     const void* q3;
-    const milo_half* scales;
-    const milo_half* zeros;
     const milo_half* U;      /* [N x r] or NULL when r == 0 */
     const milo_half* V;      /* [r x K] or NULL when r == 0 */
     int32_t r;

@@ -12,16 +12,17 @@ description, independently of the GPU packer:
     row n, group g  ->  codes q[n, 64 g .. 64 g + 63].
   * Units are ordered by (row block of 16 rows, group, row within block):
         u(n, g) = ((n // 16) * (K // 64) + g) * 16 + n % 16
-  * A unit is six little-endian 32-bit words d0..d5.  Plane A holds d0..d3 of
-    unit u at byte offset 16 u; plane B follows plane A (it starts at byte
-    N K / 4) and holds d4, d5 of unit u at byte offset 8 u.
+  * The codes of a unit are six little-endian 32-bit words d0..d5.  Plane A holds
+    d0..d3 of unit u at byte offset 16 u; plane B follows plane A (it starts at
+    byte N K / 4) and holds, at byte offset 12 u, the three words d4, d5 and
+    p = (scale bits) | (zero-point bits) << 16, both parameters being IEEE
+    binary16 bit patterns.  28 bytes per unit = 3.5 bits per weight.
   * The 64 codes form 32 pairs, pair P = (q[2P], q[2P+1]) = (lo, hi).
     Pairs 0..29: word j = P // 5, slot c = P % 5; lo sits in bits 3c..3c+2 and
     hi in bits 16+3c..16+3c+2 of word j.  That leaves bits 15 and 31 of every
     word free.  Pair 30 uses those of words 0, 1, 2: bit i of lo is bit 15 of
     word i and bit i of hi is bit 31 of word i.  Pair 31 does the same with
     words 3, 4, 5.
-  * Scales and zero-points are fp16 arrays of N K / 64 entries in unit order.
 """
 import numpy as np
 
@@ -29,6 +30,12 @@ GROUP = 64
 
 
 def packed_bytes(N, K):
+    """Bytes of the blob: 24 bytes of codes and 4 bytes of parameters per group of 64."""
+    return N * K // GROUP * 28
+
+
+def code_bytes(N, K):
+    """Bytes the codes alone occupy: exactly 3 bits per weight."""
     return N * K * 3 // 8
 
 
@@ -54,11 +61,17 @@ def from_unit_order(flat, N, K):
         np.asarray(flat).reshape(N // 16, G, 16).transpose(0, 2, 1)).reshape(N, G)
 
 
-def pack_w3(codes):
-    """codes uint8 [N, K] in 0..7 -> uint8 blob of exactly N*K*3/8 bytes."""
+def pack_w3(codes, scales, zeros):
+    """codes uint8 [N, K] in 0..7, scales and zeros fp16 [N, K/64] -> uint8 blob."""
     codes = np.asarray(codes)
     N, K = codes.shape
     _check(N, K)
+    scales = np.asarray(scales)
+    zeros = np.asarray(zeros)
+    if scales.dtype != np.float16 or zeros.dtype != np.float16:
+        raise ValueError("scales and zeros must be float16")
+    if scales.shape != (N, K // GROUP) or zeros.shape != (N, K // GROUP):
+        raise ValueError("scales and zeros must be [N, K/64]")
     if codes.max(initial=0) > 7:
         raise ValueError("codes must lie in 0..7")
     G = K // GROUP
@@ -76,15 +89,18 @@ def pack_w3(codes):
         for i in range(3):
             d[:, base + i] |= ((lo >> np.uint32(i)) & np.uint32(1)) << np.uint32(15)
             d[:, base + i] |= ((hi >> np.uint32(i)) & np.uint32(1)) << np.uint32(31)
+    params = to_unit_order(scales).view(np.uint16).astype(np.uint32) | \
+        (to_unit_order(zeros).view(np.uint16).astype(np.uint32) << np.uint32(16))
     plane_a = np.ascontiguousarray(d[:, :4]).astype("<u4").view(np.uint8).reshape(-1)
-    plane_b = np.ascontiguousarray(d[:, 4:]).astype("<u4").view(np.uint8).reshape(-1)
+    plane_b = np.ascontiguousarray(np.concatenate([d[:, 4:], params[:, None]], axis=1)).astype("<u4") \
+        .view(np.uint8).reshape(-1)
     blob = np.concatenate([plane_a, plane_b])
     assert blob.size == packed_bytes(N, K)
     return blob
 
 
 def unpack_w3(blob, N, K):
-    """Inverse of pack_w3."""
+    """Inverse of pack_w3: (codes uint8 [N, K], scales fp16 [N, K/64], zeros fp16 [N, K/64])."""
     _check(N, K)
     blob = np.asarray(blob, dtype=np.uint8).reshape(-1)
     if blob.size != packed_bytes(N, K):
@@ -92,8 +108,10 @@ def unpack_w3(blob, N, K):
     G = K // GROUP
     nu = N * G
     a = blob[: nu * 16].view("<u4").reshape(nu, 4).astype(np.uint32)
-    b = blob[nu * 16:].view("<u4").reshape(nu, 2).astype(np.uint32)
-    d = np.concatenate([a, b], axis=1)
+    b3 = blob[nu * 16:].view("<u4").reshape(nu, 3).astype(np.uint32)
+    d = np.concatenate([a, b3[:, :2]], axis=1)
+    scales = from_unit_order((b3[:, 2] & np.uint32(0xFFFF)).astype(np.uint16).view(np.float16), N, K)
+    zeros = from_unit_order((b3[:, 2] >> np.uint32(16)).astype(np.uint16).view(np.float16), N, K)
     cu = np.zeros((nu, GROUP), dtype=np.uint32)
     seven = np.uint32(7)
     for P in range(30):
@@ -105,4 +123,4 @@ def unpack_w3(blob, N, K):
             cu[:, 2 * P] |= ((d[:, base + i] >> np.uint32(15)) & np.uint32(1)) << np.uint32(i)
             cu[:, 2 * P + 1] |= ((d[:, base + i] >> np.uint32(31)) & np.uint32(1)) << np.uint32(i)
     codes = cu.astype(np.uint8).reshape(N // 16, G, 16, GROUP).transpose(0, 2, 1, 3)
-    return np.ascontiguousarray(codes).reshape(N, K)
+    return np.ascontiguousarray(codes).reshape(N, K), scales, zeros

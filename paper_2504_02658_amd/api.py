@@ -33,8 +33,7 @@ class MiloError(RuntimeError):
 
 
 class Weight(ctypes.Structure):
-    _fields_ = [("q3", ctypes.c_void_p), ("scales", ctypes.c_void_p), ("zeros", ctypes.c_void_p),
-                ("U", ctypes.c_void_p), ("V", ctypes.c_void_p), ("r", ctypes.c_int32),
+    _fields_ = [("q3", ctypes.c_void_p), ("U", ctypes.c_void_p), ("V", ctypes.c_void_p), ("r", ctypes.c_int32),
                 ("reserved", ctypes.c_int32)]
 
 
@@ -59,17 +58,17 @@ def lib():
         L.milo_w3_packed_bytes.restype = sz
         L.milo_w3_packed_bytes.argtypes = [i64, i64]
         L.milo_pack_w3.restype = ci
-        L.milo_pack_w3.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
+        L.milo_pack_w3.argtypes = [vp, i64, i64, ci, vp, vp]
         L.milo_unpack_w3.restype = ci
-        L.milo_unpack_w3.argtypes = [vp, i64, i64, vp, vp]
+        L.milo_unpack_w3.argtypes = [vp, i64, i64, vp, vp, vp, vp]
         L.milo_dequant_w3.restype = ci
-        L.milo_dequant_w3.argtypes = [vp, vp, vp, i64, i64, vp, vp]
+        L.milo_dequant_w3.argtypes = [vp, i64, i64, vp, vp]
         L.milo_workspace_init.restype = ci
         L.milo_workspace_init.argtypes = [vp, sz, vp]
         L.milo_w3lr_gemm_workspace.restype = sz
         L.milo_w3lr_gemm_workspace.argtypes = [i64, i64, i64, ci]
         L.milo_w3lr_gemm.restype = ci
-        L.milo_w3lr_gemm.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp, ci, vp, vp, sz, vp]
+        L.milo_w3lr_gemm.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, vp, vp, sz, vp]
         L.milo_moe_w3lr_check_experts.restype = ci
         L.milo_moe_w3lr_check_experts.argtypes = [ctypes.POINTER(Expert), ci, i64, i64,
                                                   ctypes.POINTER(ci)]
@@ -105,9 +104,9 @@ def _dev(t, dtype, name):
 class PackedWeight:
     """Device buffers of one packed [N x K] weight and its optional compensator."""
 
-    def __init__(self, N, K, q3, scales, zeros, U=None, V=None):
+    def __init__(self, N, K, q3, U=None, V=None):
         self.N, self.K = int(N), int(K)
-        self.q3, self.scales, self.zeros = q3, scales, zeros
+        self.q3 = q3                    # uint8 blob: codes, scales and zero-points
         self.U, self.V = U, V
 
     @property
@@ -120,17 +119,16 @@ class PackedWeight:
         assert U.shape[0] == self.N and V.shape[1] == self.K and U.shape[1] == V.shape[0]
         if U.shape[1] == 0:
             U = V = None
-        return PackedWeight(self.N, self.K, self.q3, self.scales, self.zeros, U, V)
+        return PackedWeight(self.N, self.K, self.q3, U, V)
 
     def weight_bytes(self):
-        n = self.q3.numel() + 2 * self.scales.numel() + 2 * self.zeros.numel()
+        n = self.q3.numel()
         if self.U is not None:
             n += 2 * self.U.numel() + 2 * self.V.numel()
         return n
 
     def c_struct(self):
-        return Weight(self.q3.data_ptr(), self.scales.data_ptr(), self.zeros.data_ptr(),
-                      0 if self.U is None else self.U.data_ptr(),
+        return Weight(self.q3.data_ptr(), 0 if self.U is None else self.U.data_ptr(),
                       0 if self.V is None else self.V.data_ptr(), self.r, 0)
 
 
@@ -144,24 +142,24 @@ def pack_w3(W, group_size=64):
     N, K = W.shape
     nbytes = packed_bytes(N, K)
     q3 = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=W.device)
-    groups = max(N * K // 64, 8)
-    scales = torch.empty(groups, dtype=torch.float16, device=W.device)
-    zeros = torch.empty(groups, dtype=torch.float16, device=W.device)
-    _check(lib().milo_pack_w3(_ptr(W), N, K, group_size, _ptr(q3), _ptr(scales), _ptr(zeros),
-                              _stream()), "milo_pack_w3")
-    return PackedWeight(N, K, q3[:nbytes], scales[: N * K // 64], zeros[: N * K // 64])
+    _check(lib().milo_pack_w3(_ptr(W), N, K, group_size, _ptr(q3), _stream()), "milo_pack_w3")
+    return PackedWeight(N, K, q3[:nbytes])
 
 
 def unpack_w3(pw):
-    codes = torch.empty((pw.N, pw.K), dtype=torch.uint8, device=pw.q3.device)
-    _check(lib().milo_unpack_w3(_ptr(pw.q3), pw.N, pw.K, _ptr(codes), _stream()), "milo_unpack_w3")
-    return codes
+    """milo_unpack_w3: (codes uint8 [N, K], scales fp16 [N, K/64], zeros fp16 [N, K/64])."""
+    dev = pw.q3.device
+    codes = torch.empty((pw.N, pw.K), dtype=torch.uint8, device=dev)
+    scales = torch.empty((pw.N, pw.K // 64), dtype=torch.float16, device=dev)
+    zeros = torch.empty((pw.N, pw.K // 64), dtype=torch.float16, device=dev)
+    _check(lib().milo_unpack_w3(_ptr(pw.q3), pw.N, pw.K, _ptr(codes), _ptr(scales), _ptr(zeros),
+                                _stream()), "milo_unpack_w3")
+    return codes, scales, zeros
 
 
 def dequant_w3(pw):
     out = torch.empty((pw.N, pw.K), dtype=torch.float16, device=pw.q3.device)
-    _check(lib().milo_dequant_w3(_ptr(pw.q3), _ptr(pw.scales), _ptr(pw.zeros), pw.N, pw.K,
-                                 _ptr(out), _stream()), "milo_dequant_w3")
+    _check(lib().milo_dequant_w3(_ptr(pw.q3), pw.N, pw.K, _ptr(out), _stream()), "milo_dequant_w3")
     return out
 
 
@@ -187,8 +185,7 @@ def w3lr_gemm(X, pw, out=None, workspace=None):
     need = gemm_workspace_bytes(M, pw.N, K, pw.r)
     if workspace is None:
         workspace = new_workspace(need, X.device)
-    _check(lib().milo_w3lr_gemm(_ptr(X), M, pw.N, K, _ptr(pw.q3), _ptr(pw.scales), _ptr(pw.zeros),
-                                _ptr(pw.U), _ptr(pw.V), pw.r, _ptr(out), _ptr(workspace),
+    _check(lib().milo_w3lr_gemm(_ptr(X), M, pw.N, K, _ptr(pw.q3), _ptr(pw.U), _ptr(pw.V), pw.r, _ptr(out), _ptr(workspace),
                                 workspace.numel(), _stream()), "milo_w3lr_gemm")
     return out
 

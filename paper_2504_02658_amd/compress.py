@@ -29,6 +29,6 @@ def fit_compensator(W, pw, r, niter=2, oversample=10, seed=0):
 
 def clone_weight(pw):
     """A byte-identical copy at new addresses (used to rotate weights through HBM in benchmarks)."""
-    return api.PackedWeight(pw.N, pw.K, pw.q3.clone(), pw.scales.clone(), pw.zeros.clone(),
+    return api.PackedWeight(pw.N, pw.K, pw.q3.clone(),
                             None if pw.U is None else pw.U.clone(),
                             None if pw.V is None else pw.V.clone())

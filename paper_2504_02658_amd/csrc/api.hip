@@ -89,24 +89,22 @@ extern "C" size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int 
 }
 
 extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t K, const void* q3,
-                              const milo_half* scales, const milo_half* zeros, const milo_half* U,
+                              const milo_half* U,
                               const milo_half* V, int r, milo_half* Y, void* workspace,
                               size_t workspace_bytes, void* stream_) {
-    if (!X || !q3 || !scales || !zeros || !Y) return MILO_ERR_NULL;
+    if (!X || !q3 || !Y) return MILO_ERR_NULL;
     if (!gemm_shape_ok(M, N, K)) return MILO_ERR_SHAPE;
     if (r < 0 || r > N || r > K) return MILO_ERR_RANK;
     if (r > 0 && (!U || !V)) return MILO_ERR_RANK;
     if (!workspace || workspace_bytes < milo_w3lr_gemm_workspace(M, N, K, r))
         return MILO_ERR_WORKSPACE;
-    if (!aligned16(X) || !aligned16(q3) || !aligned16(scales) || !aligned16(zeros) ||
+    if (!aligned16(X) || !aligned16(q3) ||
         !aligned16(Y) || !aligned16(workspace) || (r > 0 && (!aligned16(U) || !aligned16(V))))
         return MILO_ERR_ALIGN;
     hipStream_t stream = (hipStream_t)stream_;
 
     WeightDev w;
     w.q3 = q3;
-    w.scales = reinterpret_cast<const f16*>(scales);
-    w.zeros = reinterpret_cast<const f16*>(zeros);
     w.U = reinterpret_cast<const f16*>(U);
     w.V = reinterpret_cast<const f16*>(V);
     w.r = r;

@@ -14,7 +14,7 @@ hipcc $FLAGS -c api.hip -o _build/api.o & pids+=($!)
 for p in "${pids[@]}"; do wait $p; done
 # The decode kernel counts outstanding memory operations by hand (see gemm_decode.hip): all loads
 # of a piece are issued in a fixed order (per chunk eight buffer-to-LDS copies, then per row block
-# a 16-byte, an 8-byte and two 2-byte loads) before the first hand-written "s_waitcnt vmcnt(N)",
+# a 16-byte and a 12-byte load) before the first hand-written "s_waitcnt vmcnt(N)",
 # and the compiler must neither reorder them nor add memory operations of its own (spills).
 hipcc $FLAGS -S --cuda-device-only gemm_decode.hip -o _build/gemm_decode.s
 python3 - <<'PY'
@@ -28,8 +28,8 @@ for m in re.finditer(r"^(_ZN4milo18w3lr_decode_kernelILi(\d+)ELi(\d+)\S*):[^\n]*
     meta = re.search(r"\.name:\s+%s\b(.*?)\.wavefront_size" % re.escape(name), txt, re.S)
     if int(re.search(r"\.private_segment_fixed_size:\s+(\d+)", meta.group(1)).group(1)):
         sys.exit("%s uses scratch memory" % name)
-    total = CPW * (8 + 4 * R)
-    first = total - (8 + 4)
+    total = CPW * (8 + 2 * R)
+    first = total - (8 + 2)
     hits = [i for i, line in enumerate(body)
             if i > 0 and "ASMSTART" in body[i - 1] and re.search(r"s_waitcnt vmcnt\(%d\)" % first, line)]
     if not hits:
@@ -42,7 +42,7 @@ for m in re.finditer(r"^(_ZN4milo18w3lr_decode_kernelILi(\d+)ELi(\d+)\S*):[^\n]*
                 seen.append(v.group(1) + v.group(2) + (" lds" if " lds" in body[j] else ""))
             j -= 1
         seen.reverse()
-        unit = ["buffer_load_dwordx4", "buffer_load_dwordx2", "buffer_load_ushort", "buffer_load_ushort"]
+        unit = ["buffer_load_dwordx4", "buffer_load_dwordx3"]
         want = (["buffer_load_dwordx4 lds"] * 8 + unit * R) * CPW
         if seen != want:
             sys.exit("%s: the loads before s_waitcnt vmcnt(%d) are not in the counted order:\n%r" % (name, first, seen))

@@ -5,8 +5,8 @@
 // walked in pieces of 16 chunks of 256; wave w takes chunks w and w+8 of the piece for all R
 // 16-row blocks, so for K = 4096 every load of the launch is issued in the first few hundred
 // cycles.  For a chunk a
-// lane loads one unit per 16-row block (24 bytes of codes, one scale, one zero-point) with fully
-// coalesced 16- and 8-byte buffer loads and no branches (lanes without data read out of range
+// lane loads one unit per 16-row block (24 bytes of codes, fp16 scale and zero-point) with fully
+// coalesced 16- and 12-byte buffer loads and no branches (lanes without data read out of range
 // and get zeros), converts it in registers and feeds it as the A operand of
 // v_mfma_f32_16x16x32_f16 (lane quad q = group 4c+q, eight steps of eight codes).
 // The activations of a chunk, X[0..15][256c .. 256c+255], are the B operand of every block.  The
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
         const uint32_t nchunks = (G + 3) / 4;
         const uint32_t npieces = (nchunks + kDecPiece - 1) / kDecPiece;
         const int r = a.w.r;
-        const W3Buf wb = make_w3buf(a.w.q3, a.w.scales, a.w.zeros, a.N, a.K);
+        const W3Buf wb = make_w3buf(a.w.q3, a.N, a.K);
         const BufRsrc xb = make_rsrc(a.X, (uint64_t)M * K * 2u);
         // Staging: copy i of a chunk moves rows 2i, 2i+1: lane l -> row 2i + l/32, slot position
         // p = l%32, which receives segment p ^ row of the row's 32 segments of 8 columns.
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
                     }
                 }
                 // Vector memory operations complete in order, so unit (ci, b) and the activations of
-                // its chunk have arrived once at most the operations issued after that unit's four
+                // its chunk have arrived once at most the operations issued after that unit's two
                 // loads are outstanding.  The slots are private to the wave, so no barrier is
                 // involved, and the first unit is converted while most of the rest is still on its
                 // way.  (The counts rely on the compiler adding no memory operation of its own in
@@ -281,9 +281,9 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
                 static_for<0, CPW * R>([&](auto su_c) {
                     constexpr int su = decltype(su_c)::value;
                     constexpr int ci = su / R, b = su % R;
-                    constexpr int kIssued = CPW * (8 + 4 * R);
+                    constexpr int kIssued = CPW * (8 + 2 * R);
                     __builtin_amdgcn_sched_barrier(0);      // nothing of this unit moves above its wait
-                    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kIssued - (ci * (8 + 4 * R) + 8 + 4 * (b + 1))) : "memory");
+                    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kIssued - (ci * (8 + 2 * R) + 8 + 2 * (b + 1))) : "memory");
                     __builtin_amdgcn_sched_barrier(0);
                     if (b == 0) {
                         const unsigned char* slot = myslot + kDecWaves * ci * kDecSlotBytes;

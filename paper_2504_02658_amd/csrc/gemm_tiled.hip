@@ -273,7 +273,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     constexpr int STAGE = BM * 256;              // bytes of one X stage: BM rows x 128 columns
     constexpr int NCP = BM / 16;                 // 1-KB copies per wave and stage (4 rows each)
     constexpr int PD = MB == 4 ? 2 : kTiledStages;   // chunks in flight, the one being computed included
-    constexpr int PER = NCP + 8;                 // vector memory instructions a wave issues per chunk
+    constexpr int PER = NCP + 4;                 // vector memory instructions a wave issues per chunk
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];      // PD stages
 
     const TileInfo ti = resolve_tile<NW>(a.rs, blockIdx.y, BM);
@@ -308,7 +308,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
         const WeightDev& w = ti.w[NW == 1 ? 0 : s];
-        wbuf[s] = make_w3buf(w.q3, w.scales, w.zeros, N, K);
+        wbuf[s] = make_w3buf(w.q3, N, K);
         const int64_t nb = (NW == 1) ? n0 + 64 * wave + 32 * s : n0 + 32 * wave;
         nrow[s] = nb + i32;
         ubase[s] = (nrow[s] < N) ? (uint32_t)unit_index(nrow[s], 0, G) : kOobUnit;
@@ -348,7 +348,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[s][mb][v] = 0.0f;
 
-    // One chunk's loads of this wave are always PER instructions: the two weight units (four loads
+    // One chunk's loads of this wave are always PER instructions: the two weight units (two loads
     // each), then the NCP activation copies into stage `slot`.  All are issued when a chunk starts:
     // the time a wave needs to get them out is best spent while the other workgroup on the CU
     // multiplies (spreading them over the steps of the chunk was slower).  The common case costs
@@ -368,10 +368,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const uint32_t u = (ragged && h == 1) ? (1u << 27) : ucur[s];
-            ru[s].a = buf_load16(wbuf[NW == 1 ? 0 : s].a, u * 16u);
-            ru[s].b = buf_load8(wbuf[NW == 1 ? 0 : s].b, u * 8u);
-            ru[s].s = buf_load2(wbuf[NW == 1 ? 0 : s].s, u * 2u);
-            ru[s].z = buf_load2(wbuf[NW == 1 ? 0 : s].z, u * 2u);
+            ru[s] = load_unit_buf(wbuf[NW == 1 ? 0 : s], u);
             ucur[s] += 32u;
         }
         asm volatile("" ::: "memory");

@@ -23,22 +23,18 @@ constexpr int kWave = 64;
 
 // ---------------------------------------------------------------------------------------------
 // Packed weight view.  Unit u = ((n/16) * G + g) * 16 + n%16 with G = K/64 groups per row;
-// plane A holds 16 bytes per unit, plane B (right behind it) 8 bytes per unit.
+// plane A holds 16 bytes per unit (code words 0..3), plane B (right behind it) 12 bytes per unit:
+// code words 4, 5 and one word with the fp16 scale (low half) and zero-point (high half).
 struct W3View {
     const u32x4* planeA;
-    const u32x2* planeB;
-    const f16* scales;
-    const f16* zeros;
+    const uint32_t* planeB;         // three words per unit
     int G;                          // groups per row
 };
 
-__host__ __device__ inline W3View make_view(const void* q3, const void* scales, const void* zeros,
-                                            int64_t N, int64_t K) {
+__host__ __device__ inline W3View make_view(const void* q3, int64_t N, int64_t K) {
     W3View v;
     v.planeA = reinterpret_cast<const u32x4*>(q3);
-    v.planeB = reinterpret_cast<const u32x2*>(reinterpret_cast<const char*>(q3) + (N * K) / 4);
-    v.scales = reinterpret_cast<const f16*>(scales);
-    v.zeros = reinterpret_cast<const f16*>(zeros);
+    v.planeB = reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(q3) + (N * K) / 4);
     v.G = static_cast<int>(K / kGroup);
     return v;
 }
@@ -51,7 +47,7 @@ __host__ __device__ inline int64_t unit_index(int64_t n, int64_t g, int64_t G) {
 struct RawUnit {
     u32x4 a;        // words 0..3
     u32x2 b;        // words 4, 5
-    uint32_t s, z;  // fp16 bit patterns of scale and zero-point, as the 16-bit loads left them
+    uint32_t sz;    // fp16 scale (low half) and zero-point (high half)
 };
 __device__ __forceinline__ f16 f16_bits(uint32_t v) { return __builtin_bit_cast(f16, (unsigned short)v); }
 
@@ -59,27 +55,15 @@ __device__ __forceinline__ RawUnit zero_unit() {
     RawUnit r;
     r.a = u32x4{0u, 0u, 0u, 0u};
     r.b = u32x2{0u, 0u};
-    r.s = 0u;
-    r.z = 0u;
+    r.sz = 0u;
     return r;
 }
 
-// STREAM = true marks the loads non-temporal: the decode kernel reads every weight byte exactly
-// once, so keeping it out of the caches' replacement order protects the activations.
-template <bool STREAM>
 __device__ __forceinline__ RawUnit load_unit(const W3View& w, int64_t u) {
     RawUnit r;
-    if (STREAM) {
-        r.a = __builtin_nontemporal_load(w.planeA + u);
-        r.b = __builtin_nontemporal_load(w.planeB + u);
-        r.s = __builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(w.scales) + u);
-        r.z = __builtin_nontemporal_load(reinterpret_cast<const unsigned short*>(w.zeros) + u);
-    } else {
-        r.a = w.planeA[u];
-        r.b = w.planeB[u];
-        r.s = reinterpret_cast<const unsigned short*>(w.scales)[u];
-        r.z = reinterpret_cast<const unsigned short*>(w.zeros)[u];
-    }
+    r.a = w.planeA[u];
+    r.b = u32x2{w.planeB[3 * u], w.planeB[3 * u + 1]};
+    r.sz = w.planeB[3 * u + 2];
     return r;
 }
 
@@ -105,36 +89,35 @@ __device__ __forceinline__ u32x4 buf_load16_coherent(BufRsrc r, uint32_t off) {
 __device__ __forceinline__ u32x2 buf_load8(BufRsrc r, uint32_t off) {
     return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
 }
-__device__ __forceinline__ uint32_t buf_load2(BufRsrc r, uint32_t off) {
-    return (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
+typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+__device__ __forceinline__ u32x3 buf_load12(BufRsrc r, uint32_t off) {
+    return __builtin_amdgcn_raw_buffer_load_b96(r, off, 0, 0);
 }
 
 // All vector memory operations issued so far by this wave (loads, stores and buffer-to-LDS copies)
 // have completed; nothing may be moved across.
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// The four arrays of a packed weight as buffers.
+// The two planes of a packed weight as buffers.
 struct W3Buf {
-    BufRsrc a, b, s, z;
+    BufRsrc a, b;
 };
-__device__ __forceinline__ W3Buf make_w3buf(const void* q3, const void* scales, const void* zeros,
-                                            int64_t N, int64_t K) {
+__device__ __forceinline__ W3Buf make_w3buf(const void* q3, int64_t N, int64_t K) {
     const uint64_t units = (uint64_t)N * (uint64_t)(K / kGroup);
     W3Buf w;
     w.a = make_rsrc(q3, units * 16);
-    w.b = make_rsrc(reinterpret_cast<const char*>(q3) + units * 16, units * 8);
-    w.s = make_rsrc(scales, units * 2);
-    w.z = make_rsrc(zeros, units * 2);
+    w.b = make_rsrc(reinterpret_cast<const char*>(q3) + units * 16, units * 12);
     return w;
 }
-// Unit u, or an all-zero unit (which dequantizes to zeros) when u is kOobUnit.
+// Unit u with two loads (16 and 12 bytes), or an all-zero unit (which dequantizes to zeros) when
+// u lies past the end of the weight, e.g. kOobUnit.
 constexpr uint32_t kOobUnit = 0x0FFFFFFFu;
 __device__ __forceinline__ RawUnit load_unit_buf(const W3Buf& w, uint32_t u) {
     RawUnit r;
     r.a = buf_load16(w.a, u * 16u);
-    r.b = buf_load8(w.b, u * 8u);
-    r.s = buf_load2(w.s, u * 2u);
-    r.z = buf_load2(w.z, u * 2u);
+    const u32x3 t = buf_load12(w.b, u * 12u);
+    r.b = u32x2{t.x, t.y};
+    r.sz = t.z;
     return r;
 }
 
@@ -142,13 +125,13 @@ __device__ __forceinline__ RawUnit load_unit_buf(const W3Buf& w, uint32_t u) {
 // earlier.  Without it the compiler converts the scale and zero-point of the NEXT chunk right
 // after issuing their loads and puts the wait for them in the middle of the current chunk.
 __device__ __forceinline__ void pin_unit(RawUnit& u) {
-    asm volatile("" : "+v"(u.a.x), "+v"(u.a.y), "+v"(u.a.z), "+v"(u.a.w), "+v"(u.b.x), "+v"(u.b.y), "+v"(u.s), "+v"(u.z));
+    asm volatile("" : "+v"(u.a.x), "+v"(u.a.y), "+v"(u.a.z), "+v"(u.a.w), "+v"(u.b.x), "+v"(u.b.y), "+v"(u.sz));
 }
 // The same for the scale and the zero-point alone (the values whose conversion the compiler likes
 // to start early); the code words stay untouched, which keeps them in the registers they were
 // loaded into.
 __device__ __forceinline__ void pin_unit_params(RawUnit& u) {
-    asm volatile("" : "+v"(u.s), "+v"(u.z));
+    asm volatile("" : "+v"(u.sz));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -195,14 +178,14 @@ struct UnitConsts {
     uint32_t A0, A3, A6, S2, C2;
 };
 __device__ __forceinline__ UnitConsts unit_consts(const RawUnit& ru) {
-    const float s = (float)f16_bits(ru.s);
-    const float z = (float)f16_bits(ru.z);
+    const float s = (float)f16_bits(ru.sz);
+    const float z = (float)f16_bits(ru.sz >> 16);
     const float zr = __builtin_fminf(__builtin_fmaxf(__builtin_rintf(z), -8.0f), 15.0f);
     UnitConsts c;
     c.A0 = pack2((f16)(1024.0f + zr));
     c.A3 = pack2((f16)(128.0f + zr));
     c.A6 = pack2((f16)(16.0f + zr));
-    c.S2 = pack2(f16_bits(ru.s));
+    c.S2 = pack2(f16_bits(ru.sz));
     c.C2 = pack2((f16)((zr - z) * s));
     return c;
 }

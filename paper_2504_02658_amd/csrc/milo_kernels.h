@@ -8,8 +8,6 @@ namespace milo {
 // Same bytes as the public milo_w3lr_weight.
 struct WeightDev {
     const void* q3;
-    const f16* scales;
-    const f16* zeros;
     const f16* U;
     const f16* V;
     int32_t r;

@@ -262,11 +262,10 @@ static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_m
 }
 
 static int check_weight(const milo_w3lr_weight& w, int64_t N, int64_t K) {
-    if (!w.q3 || !w.scales || !w.zeros) return MILO_ERR_NULL;
+    if (!w.q3) return MILO_ERR_NULL;
     if (w.r < 0 || w.r > N || w.r > K) return MILO_ERR_RANK;
     if (w.r > 0 && (!w.U || !w.V)) return MILO_ERR_RANK;
-    if (!aligned16(w.q3) || !aligned16(w.scales) || !aligned16(w.zeros) || !aligned16(w.U) ||
-        !aligned16(w.V))
+    if (!aligned16(w.q3) || !aligned16(w.U) || !aligned16(w.V))
         return MILO_ERR_ALIGN;
     return MILO_OK;
 }

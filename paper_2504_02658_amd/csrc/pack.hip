@@ -21,7 +21,7 @@ __device__ __forceinline__ uint32_t shfl_xor16(uint32_t v, int m) {
 
 __global__ __launch_bounds__(kPackThreads) void pack_w3_kernel(
     const float* __restrict__ W, int64_t N, int64_t K, uint32_t* __restrict__ planeA,
-    uint32_t* __restrict__ planeB, f16* __restrict__ scales, f16* __restrict__ zeros) {
+    uint32_t* __restrict__ planeB) {
     const int64_t G = K / kGroup;
     const int64_t total = N * G;
     const int64_t gu = (int64_t)blockIdx.x * kUnitsPerBlock + (threadIdx.x >> 4);
@@ -98,23 +98,28 @@ __global__ __launch_bounds__(kPackThreads) void pack_w3_kernel(
     if (l16 == 0) {
         const int64_t u = unit_index(n, g, G);
         *reinterpret_cast<u32x4*>(planeA + 4 * u) = u32x4{d[0], d[1], d[2], d[3]};
-        *reinterpret_cast<u32x2*>(planeB + 2 * u) = u32x2{d[4], d[5]};
-        scales[u] = s16;
-        zeros[u] = z16;
+        planeB[3 * u] = d[4];
+        planeB[3 * u + 1] = d[5];
+        planeB[3 * u + 2] = (uint32_t)__builtin_bit_cast(unsigned short, s16) |
+                            ((uint32_t)__builtin_bit_cast(unsigned short, z16) << 16);
     }
 }
 
 // One thread per unit: unpack to bytes / dequantize to fp16.  Test aids, not tuned.
 __global__ __launch_bounds__(256) void unpack_w3_kernel(W3View w, int64_t N, int64_t K,
-                                                        uint8_t* __restrict__ codes) {
+                                                        uint8_t* __restrict__ codes,
+                                                        unsigned short* __restrict__ scales,
+                                                        unsigned short* __restrict__ zeros) {
     const int64_t G = w.G;
     const int64_t gu = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gu >= N * G) return;
     const int64_t n = gu / G, g = gu - n * G;
     const int64_t u = unit_index(n, g, G);
-    const u32x4 a = w.planeA[u];
-    const u32x2 b = w.planeB[u];
-    const uint32_t d[6] = {a.x, a.y, a.z, a.w, b.x, b.y};
+    const RawUnit ru = load_unit(w, u);
+    const uint32_t d[6] = {ru.a.x, ru.a.y, ru.a.z, ru.a.w, ru.b.x, ru.b.y};
+    if (scales) scales[gu] = (unsigned short)(ru.sz & 0xffffu);
+    if (zeros) zeros[gu] = (unsigned short)(ru.sz >> 16);
+    if (!codes) return;
     uint8_t* out = codes + n * K + g * kGroup;
     for (int P = 0; P < 32; ++P) {
         uint32_t lo, hi;
@@ -141,7 +146,7 @@ __global__ __launch_bounds__(256) void dequant_w3_kernel(W3View w, int64_t N, in
     const int64_t gu = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gu >= N * G) return;
     const int64_t n = gu / G, g = gu - n * G;
-    const RawUnit ru = load_unit<false>(w, unit_index(n, g, G));
+    const RawUnit ru = load_unit(w, unit_index(n, g, G));
     uint32_t wv[32];
     dequant_unit(ru, wv);
     u32x4* out = reinterpret_cast<u32x4*>(Wdq + n * K + g * kGroup);
@@ -155,48 +160,44 @@ using namespace milo;
 
 extern "C" size_t milo_w3_packed_bytes(int64_t N, int64_t K) {
     if (!weight_shape_ok(N, K)) return 0;
-    return (size_t)(N * K / 8 * 3);
+    return (size_t)(N * K / 64 * 28);
 }
 
-extern "C" int milo_pack_w3(const float* W, int64_t N, int64_t K, int group_size, void* q3,
-                            milo_half* scales, milo_half* zeros, void* stream) {
-    if (!W || !q3 || !scales || !zeros) return MILO_ERR_NULL;
+extern "C" int milo_pack_w3(const float* W, int64_t N, int64_t K, int group_size, void* q3, void* stream) {
+    if (!W || !q3) return MILO_ERR_NULL;
     if (group_size != kGroup) return MILO_ERR_GROUP;
     if (!weight_shape_ok(N, K)) return MILO_ERR_SHAPE;
-    if (!aligned16(W) || !aligned16(q3) || !aligned16(scales) || !aligned16(zeros))
-        return MILO_ERR_ALIGN;
+    if (!aligned16(W) || !aligned16(q3)) return MILO_ERR_ALIGN;
     const int64_t units = N * (K / kGroup);
     const int64_t blocks = (units + kUnitsPerBlock - 1) / kUnitsPerBlock;
     if (blocks > 0x7fffffff) return MILO_ERR_SHAPE;
     uint32_t* planeA = reinterpret_cast<uint32_t*>(q3);
     uint32_t* planeB = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(q3) + (N * K) / 4);
-    pack_w3_kernel<<<dim3((unsigned)blocks), dim3(kPackThreads), 0, (hipStream_t)stream>>>(
-        W, N, K, planeA, planeB, reinterpret_cast<f16*>(scales), reinterpret_cast<f16*>(zeros));
+    pack_w3_kernel<<<dim3((unsigned)blocks), dim3(kPackThreads), 0, (hipStream_t)stream>>>(W, N, K, planeA, planeB);
     return launch_status();
 }
 
-extern "C" int milo_unpack_w3(const void* q3, int64_t N, int64_t K, uint8_t* codes, void* stream) {
-    if (!q3 || !codes) return MILO_ERR_NULL;
+extern "C" int milo_unpack_w3(const void* q3, int64_t N, int64_t K, uint8_t* codes, milo_half* scales,
+                              milo_half* zeros, void* stream) {
+    if (!q3 || (!codes && !scales && !zeros)) return MILO_ERR_NULL;
     if (!weight_shape_ok(N, K)) return MILO_ERR_SHAPE;
     if (!aligned16(q3)) return MILO_ERR_ALIGN;
     const int64_t units = N * (K / kGroup);
     const int64_t blocks = (units + 255) / 256;
     if (blocks > 0x7fffffff) return MILO_ERR_SHAPE;
-    W3View w = make_view(q3, nullptr, nullptr, N, K);
-    unpack_w3_kernel<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>(w, N, K, codes);
+    W3View w = make_view(q3, N, K);
+    unpack_w3_kernel<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>(w, N, K, codes, scales, zeros);
     return launch_status();
 }
 
-extern "C" int milo_dequant_w3(const void* q3, const milo_half* scales, const milo_half* zeros,
-                               int64_t N, int64_t K, milo_half* W_dq, void* stream) {
-    if (!q3 || !scales || !zeros || !W_dq) return MILO_ERR_NULL;
+extern "C" int milo_dequant_w3(const void* q3, int64_t N, int64_t K, milo_half* W_dq, void* stream) {
+    if (!q3 || !W_dq) return MILO_ERR_NULL;
     if (!weight_shape_ok(N, K)) return MILO_ERR_SHAPE;
-    if (!aligned16(q3) || !aligned16(scales) || !aligned16(zeros) || !aligned16(W_dq))
-        return MILO_ERR_ALIGN;
+    if (!aligned16(q3) || !aligned16(W_dq)) return MILO_ERR_ALIGN;
     const int64_t units = N * (K / kGroup);
     const int64_t blocks = (units + 255) / 256;
     if (blocks > 0x7fffffff) return MILO_ERR_SHAPE;
-    W3View w = make_view(q3, scales, zeros, N, K);
+    W3View w = make_view(q3, N, K);
     dequant_w3_kernel<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>(
         w, N, K, reinterpret_cast<f16*>(W_dq));
     return launch_status();

@@ -33,9 +33,9 @@ def test_status_strings(L):
 
 
 def test_sizes(L):
-    assert L.milo_w3_packed_bytes(1024, 1024) == 1024 * 1024 * 3 // 8
-    assert L.milo_w3_packed_bytes(14336, 4096) == 22020096
-    assert L.milo_w3_packed_bytes(16, 64) == 384
+    assert L.milo_w3_packed_bytes(1024, 1024) == 1024 * 1024 * 7 // 16
+    assert L.milo_w3_packed_bytes(14336, 4096) == 25690112      # 22,020,096 of codes + 3,670,016 of parameters
+    assert L.milo_w3_packed_bytes(16, 64) == 448
     assert L.milo_w3_packed_bytes(8, 64) == 0 and L.milo_w3_packed_bytes(16, 100) == 0
     assert L.milo_w3lr_gemm_workspace(16, 1024, 1024, 16) >= 16 * 16 * 2
     assert L.milo_w3lr_gemm_workspace(0, 1024, 1024, 16) == 0
@@ -48,16 +48,17 @@ def test_host_side_argument_errors(L):
     null = ctypes.c_void_p(0)
     odd = ctypes.c_void_p(0x10008)
     st = ctypes.c_void_p(0)
-    assert L.milo_pack_w3(null, 16, 64, 64, p, p, p, st) == 1
-    assert L.milo_pack_w3(p, 16, 64, 128, p, p, p, st) == 3          # group size must be 64
-    assert L.milo_pack_w3(p, 16, 100, 64, p, p, p, st) == 2
-    assert L.milo_pack_w3(p, 8, 64, 64, p, p, p, st) == 2
-    assert L.milo_pack_w3(odd, 16, 64, 64, p, p, p, st) == 7
-    assert L.milo_unpack_w3(null, 16, 64, p, st) == 1
-    assert L.milo_dequant_w3(p, p, p, 16, 65, p, st) == 2
+    assert L.milo_pack_w3(null, 16, 64, 64, p, st) == 1
+    assert L.milo_pack_w3(p, 16, 64, 128, p, st) == 3          # group size must be 64
+    assert L.milo_pack_w3(p, 16, 100, 64, p, st) == 2
+    assert L.milo_pack_w3(p, 8, 64, 64, p, st) == 2
+    assert L.milo_pack_w3(odd, 16, 64, 64, p, st) == 7
+    assert L.milo_unpack_w3(null, 16, 64, p, p, p, st) == 1
+    assert L.milo_unpack_w3(p, 16, 64, null, null, null, st) == 1
+    assert L.milo_dequant_w3(p, 16, 65, p, st) == 2
     big = 1 << 20
     g = lambda **kw: L.milo_w3lr_gemm(kw.get("X", p), kw.get("M", 16), kw.get("N", 1024),
-                                      kw.get("K", 1024), p, p, p, kw.get("U", p), kw.get("V", p),
+                                      kw.get("K", 1024), p, kw.get("U", p), kw.get("V", p),
                                       kw.get("r", 16), p, kw.get("ws", p), kw.get("wsb", big), st)
     assert g(X=null) == 1
     assert g(M=0) == 2 and g(K=1000) == 2 and g(N=1000) == 2
@@ -67,7 +68,7 @@ def test_host_side_argument_errors(L):
     # MoE
     experts = (api.Expert * 2)()
     assert L.milo_moe_w3lr_check_experts(experts, 2, 256, 512, None) == 1      # NULL weight pointers
-    w = api.Weight(0x10000, 0x10000, 0x10000, 0, 0, 0, 0)
+    w = api.Weight(0x10000, 0, 0, 0, 0)
     for e in range(2):
         experts[e] = api.Expert(w, w, w)
     rmax = ctypes.c_int(-1)

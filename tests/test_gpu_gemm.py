@@ -60,7 +60,7 @@ def test_rank_zero_equals_no_compensator_and_is_deterministic():
     X, W = wl.linear_inputs(case)
     ow = oracle_weight(W, 16)
     pw = gpu_weight(W, ow)
-    pw0 = api.PackedWeight(pw.N, pw.K, pw.q3, pw.scales, pw.zeros)
+    pw0 = api.PackedWeight(pw.N, pw.K, pw.q3)
     for Xm in (X, X[:9]):
         Y0 = _run(Xm, pw0)
         assert_close(Y0, oracle.w3lr_linear(Xm, ow["codes"], ow["scales"], ow["zeros"]), "rank 0")
@@ -79,9 +79,7 @@ def test_integer_case_is_exact(M):
     s = np.ones((N, K // 64), np.float16)
     z = np.zeros((N, K // 64), np.float16)
     X = rng.integers(-1, 2, size=(M, K)).astype(np.float16)
-    pw = api.PackedWeight(N, K, torch.from_numpy(oracle.pack_w3(q)).cuda(),
-                          torch.from_numpy(oracle.to_unit_order(s)).cuda(),
-                          torch.from_numpy(oracle.to_unit_order(z)).cuda())
+    pw = api.PackedWeight(N, K, torch.from_numpy(oracle.pack_w3(q, s, z)).cuda())
     Y = _run(X, pw).astype(np.float64)
     assert np.array_equal(Y, oracle.w3lr_linear(X, q, s, z))
 
@@ -113,9 +111,7 @@ def test_real_valued_zero_points():
     q = rng.integers(0, 8, size=(N, K), dtype=np.uint8)
     s = rng.uniform(0.005, 0.03, size=(N, K // 64)).astype(np.float16)
     z = rng.uniform(1.5, 5.5, size=(N, K // 64)).astype(np.float16)
-    pw = api.PackedWeight(N, K, torch.from_numpy(oracle.pack_w3(q)).cuda(),
-                          torch.from_numpy(oracle.to_unit_order(s)).cuda(),
-                          torch.from_numpy(oracle.to_unit_order(z)).cuda())
+    pw = api.PackedWeight(N, K, torch.from_numpy(oracle.pack_w3(q, s, z)).cuda())
     for M in (4, 40):
         X = rng.standard_normal((M, K)).astype(np.float16)
         assert_close(_run(X, pw), oracle.w3lr_linear(X, q, s, z), f"real z, M={M}")

@@ -20,13 +20,11 @@ def _assert_pack_equal(W, what):
     (q, s, z), pw = _pack_both(W)
     N, K = W.shape
     got = pw.q3.cpu().numpy()
-    assert got.size == N * K * 3 // 8, what
-    gs = pw.scales.cpu().numpy().view(np.uint16)
-    gz = pw.zeros.cpu().numpy().view(np.uint16)
-    assert np.array_equal(gs, oracle.to_unit_order(s).view(np.uint16)), f"{what}: scales"
-    assert np.array_equal(gz, oracle.to_unit_order(z).view(np.uint16)), f"{what}: zeros"
-    if not np.array_equal(got, oracle.pack_w3(q)):
-        gq = oracle.unpack_w3(got, N, K)
+    assert got.size == N * K * 7 // 16, what
+    if not np.array_equal(got, oracle.pack_w3(q, s, z)):
+        gq, gs, gz = oracle.unpack_w3(got, N, K)
+        assert np.array_equal(gs.view(np.uint16), s.view(np.uint16)), f"{what}: scales"
+        assert np.array_equal(gz.view(np.uint16), z.view(np.uint16)), f"{what}: zeros"
         bad = np.argwhere(gq != q)
         raise AssertionError(f"{what}: {len(bad)} codes differ, first at {bad[:5].tolist()}")
     return (q, s, z), pw
@@ -66,7 +64,10 @@ def test_unpack_and_dequant():
     from paper_2504_02658_amd import api
     W = wl.gen_weight(112, 448, seed=5)
     (q, s, z), pw = _assert_pack_equal(W, "unpack case")
-    assert np.array_equal(api.unpack_w3(pw).cpu().numpy(), q)
+    uq, us, uz = api.unpack_w3(pw)
+    assert np.array_equal(uq.cpu().numpy(), q)
+    assert np.array_equal(us.cpu().numpy().view(np.uint16), s.view(np.uint16))
+    assert np.array_equal(uz.cpu().numpy().view(np.uint16), z.view(np.uint16))
     wdq = api.dequant_w3(pw).cpu().numpy()
     ref = oracle.dequantize(q, s, z)
     # the kernel rounds s*(q-z) once to fp16: compare with the correctly rounded oracle value
@@ -80,10 +81,8 @@ def test_unpack_and_dequant():
     codes = rng.integers(0, 8, size=(N, K), dtype=np.uint8)
     s2 = (rng.uniform(0.001, 0.05, size=(N, K // 64))).astype(np.float16)
     z2 = (rng.uniform(-3.0, 9.0, size=(N, K // 64))).astype(np.float16)
-    pw2 = api.PackedWeight(N, K, torch.from_numpy(oracle.pack_w3(codes)).cuda(),
-                           torch.from_numpy(oracle.to_unit_order(s2)).cuda(),
-                           torch.from_numpy(oracle.to_unit_order(z2)).cuda())
-    assert np.array_equal(api.unpack_w3(pw2).cpu().numpy(), codes)
+    pw2 = api.PackedWeight(N, K, torch.from_numpy(oracle.pack_w3(codes, s2, z2)).cuda())
+    assert np.array_equal(api.unpack_w3(pw2)[0].cpu().numpy(), codes)
     wdq2 = api.dequant_w3(pw2).cpu().numpy().astype(np.float64)
     ref2 = oracle.dequantize(codes, s2, z2)
     # one fp16 rounding of the result plus the fp32 cancellation of the 1024 bias (~2^-13 s)

@@ -2,7 +2,25 @@
 import numpy as np
 import pytest
 
-from oracle import pack_w3, unpack_w3, packed_bytes, unit_index, to_unit_order, from_unit_order
+from oracle import (pack_w3 as _pack, unpack_w3, packed_bytes, code_bytes, unit_index, to_unit_order,
+                    from_unit_order)
+
+
+def _params(N, K, seed=None):
+    """fp16 scales / zeros [N, K/64]: zero bit patterns, or random finite values."""
+    G = K // 64
+    if seed is None:
+        return np.zeros((N, G), np.float16), np.zeros((N, G), np.float16)
+    rng = np.random.default_rng(seed)
+    return (rng.uniform(1e-3, 0.2, (N, G)).astype(np.float16),
+            rng.uniform(-9.0, 9.0, (N, G)).astype(np.float16))
+
+
+def pack_w3(codes, scales=None, zeros=None):
+    """pack with all-zero parameter words unless given (most pins look at the code bits only)."""
+    if scales is None:
+        scales, zeros = _params(*codes.shape)
+    return _pack(codes, scales, zeros)
 
 
 def _bit_decode(blob, N, K):
@@ -12,7 +30,7 @@ def _bit_decode(blob, N, K):
     out = np.zeros((N, K), dtype=np.uint8)
 
     def word(u, j):
-        off = 16 * u + 4 * j if j < 4 else nu * 16 + 8 * u + 4 * (j - 4)
+        off = 16 * u + 4 * j if j < 4 else nu * 16 + 12 * u + 4 * (j - 4)
         return int.from_bytes(bytes(blob[off: off + 4].tolist()), "little")
 
     for n in range(N):
@@ -34,27 +52,42 @@ def _bit_decode(blob, N, K):
 
 
 def test_zero_waste_length():
+    # the codes take exactly 3 bits per weight; the two fp16 parameters per group of 64 add
+    # 4 bytes per 24: 3.5 bits per weight in all, nothing else
     for N, K in ((16, 64), (32, 128), (1024, 1024), (48, 1408)):
-        assert packed_bytes(N, K) * 8 == N * K * 3
+        assert code_bytes(N, K) * 8 == N * K * 3
+        assert packed_bytes(N, K) == code_bytes(N, K) + 4 * (N * K // 64)
+        assert packed_bytes(N, K) * 16 == N * K * 7
     codes = np.zeros((32, 128), np.uint8)
-    assert pack_w3(codes).size == 32 * 128 * 3 // 8
+    assert pack_w3(codes).size == 32 * 128 * 7 // 16
 
 
 def test_round_trip_random_and_bit_decoder():
     rng = np.random.default_rng(0)
     for N, K in ((16, 64), (32, 192), (48, 128)):
         codes = rng.integers(0, 8, size=(N, K), dtype=np.uint8)
-        blob = pack_w3(codes)
-        assert blob.dtype == np.uint8 and blob.size == N * K * 3 // 8
-        assert np.array_equal(unpack_w3(blob, N, K), codes)
+        sc, zp = _params(N, K, seed=N + K)
+        blob = pack_w3(codes, sc, zp)
+        assert blob.dtype == np.uint8 and blob.size == N * K * 7 // 16
+        c2, s2, z2 = unpack_w3(blob, N, K)
+        assert np.array_equal(c2, codes)
+        assert np.array_equal(s2.view(np.uint16), sc.view(np.uint16))
+        assert np.array_equal(z2.view(np.uint16), zp.view(np.uint16))
         assert np.array_equal(_bit_decode(blob, N, K), codes)
+        # the parameters do not disturb the code bits and sit where the layout says
+        nu = N * (K // 64)
+        for n, g in ((0, 0), (N - 1, K // 64 - 1), (17 % N, min(1, K // 64 - 1))):
+            u = unit_index(n, g, K)
+            p = int.from_bytes(bytes(blob[nu * 16 + 12 * u + 8: nu * 16 + 12 * u + 12].tolist()), "little")
+            assert p & 0xFFFF == int(sc[n, g].view(np.uint16))
+            assert p >> 16 == int(zp[n, g].view(np.uint16))
 
 
 def test_every_position_owns_three_private_bits():
     # one unit (row 0, the only group); code position p set to 7 must light exactly three
     # bits, disjoint between positions, and the 64 positions together cover all 192 bits.
     N, K = 16, 64
-    seen = np.zeros(N * K * 3, dtype=np.int32)
+    seen = np.zeros(packed_bytes(N, K) * 8, dtype=np.int32)
     unit_bits = None
     for p in range(64):
         codes = np.zeros((N, K), np.uint8)
@@ -74,7 +107,7 @@ def test_every_position_owns_three_private_bits():
         codes = np.full((N, K), v, np.uint8)
         bits = np.unpackbits(pack_w3(codes), bitorder="little")
         assert bits.sum() == N * K * bin(v).count("1")
-        assert np.array_equal(unpack_w3(pack_w3(codes), N, K), codes)
+        assert np.array_equal(unpack_w3(pack_w3(codes), N, K)[0], codes)
 
 
 def test_documented_bit_positions():
@@ -86,7 +119,7 @@ def test_documented_bit_positions():
     def words(codes):
         blob = pack_w3(codes)
         a = blob[: 16 * 16].view("<u4").reshape(16, 4)
-        b = blob[16 * 16:].view("<u4").reshape(16, 2)
+        b = blob[16 * 16:].view("<u4").reshape(16, 3)[:, :2]
         return np.concatenate([a, b], 1)
 
     def one(p, v, row=0):
@@ -133,3 +166,7 @@ def test_rejects_bad_input():
         pack_w3(np.full((16, 64), 8, np.uint8))
     with pytest.raises(ValueError):
         unpack_w3(np.zeros(10, np.uint8), 16, 64)
+    with pytest.raises(ValueError):
+        _pack(np.zeros((16, 64), np.uint8), np.zeros((16, 1), np.float32), np.zeros((16, 1), np.float16))
+    with pytest.raises(ValueError):
+        _pack(np.zeros((16, 64), np.uint8), np.zeros((16, 2), np.float16), np.zeros((16, 2), np.float16))
