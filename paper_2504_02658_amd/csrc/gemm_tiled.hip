@@ -408,40 +408,26 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                 return __builtin_bit_cast(
                     f16x8, *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h + t) ^ sx) << 4)));
             };
-            if constexpr (MBU == 4) {
-                // 128 accumulator registers leave no room for a second fragment set when two
-                // waves share a SIMD: the fragments are read where they are used and the
-                // scheduler moves the reads up as far as registers allow.
-                dequant_units2_steps(ru[0], ru[1], [&](int t, f16x8 a0, f16x8 a1) {
-                    between(t);
+            // the next step's B fragments are requested before this step's MFMAs are issued
+            f16x8 bc[MBU], bn[MBU];
 #pragma unroll
-                    for (int mb = 0; mb < MBU; ++mb) {
-                        const f16x8 b = bfrag(mb, t);
-                        acc[0][mb] = mfma32(a0, b, acc[0][mb]);
-                        acc[1][mb] = mfma32(a1, b, acc[1][mb]);
-                    }
-                });
-            } else {
-                f16x8 bc[MBU], bn[MBU];
+            for (int mb = 0; mb < MBU; ++mb) bc[mb] = bfrag(mb, 0);
+            dequant_units2_steps(ru[0], ru[1], [&](int t, f16x8 a0, f16x8 a1) {
+                between(t);
+                if (t < 7) {
 #pragma unroll
-                for (int mb = 0; mb < MBU; ++mb) bc[mb] = bfrag(mb, 0);
-                dequant_units2_steps(ru[0], ru[1], [&](int t, f16x8 a0, f16x8 a1) {
-                    between(t);
-                    if (t < 7) {
+                    for (int mb = 0; mb < MBU; ++mb) bn[mb] = bfrag(mb, t + 1);
+                }
 #pragma unroll
-                        for (int mb = 0; mb < MBU; ++mb) bn[mb] = bfrag(mb, t + 1);
-                    }
+                for (int mb = 0; mb < MBU; ++mb) {
+                    acc[0][mb] = mfma32(a0, bc[mb], acc[0][mb]);
+                    acc[1][mb] = mfma32(a1, bc[mb], acc[1][mb]);
+                }
+                if (t < 7) {
 #pragma unroll
-                    for (int mb = 0; mb < MBU; ++mb) {
-                        acc[0][mb] = mfma32(a0, bc[mb], acc[0][mb]);
-                        acc[1][mb] = mfma32(a1, bc[mb], acc[1][mb]);
-                    }
-                    if (t < 7) {
-#pragma unroll
-                        for (int mb = 0; mb < MBU; ++mb) bc[mb] = bn[mb];
-                    }
-                });
-            }
+                    for (int mb = 0; mb < MBU; ++mb) bc[mb] = bn[mb];
+                }
+            });
         };
 
         // PD-deep pipeline: chunk c lives in ring slot c % PD (registers for the weights, LDS stage
