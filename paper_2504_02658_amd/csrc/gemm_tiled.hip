@@ -463,10 +463,12 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     // by the leading workgroup of the same grid row during this launch: wait for its flag (it was
     // dispatched before this workgroup and never waits itself), then read T coherently.
     if (any_rank && blockIdx.z == 0) {
-        if (tid == 0) wait_flag(a.flags + 4 * blockIdx.y + 1, 1u, a.flags_status);
-        __syncthreads();
         const BufRsrc tb0 = make_rsrc(a.T[0], a.t_bytes);
         const BufRsrc tb1 = make_rsrc(a.T[1], a.t_bytes);
+        // Two k-steps of 16 ranks at a time: their U fragments (which do not depend on T) and then
+        // their T fragments are all requested before the first is used, so that a rank-128
+        // compensator costs four memory round trips instead of forty.
+        bool waited = false;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const WeightDev& w = ti.w[NW == 1 ? 0 : s];
@@ -475,19 +477,41 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
             const BufRsrc tb = (NW == 1 || s == 0) ? tb0 : tb1;
             const f16* urow = w.U + (nvalid[s] ? nrow[s] : 0) * (int64_t)r;
             const bool ualigned = (r & 7) == 0;
-            for (int ks = 0; ks < r; ks += 16) {
-                const int k0 = ks + 8 * h;
-                f16x8 av = zero_f16x8();
-                if (nvalid[s] && k0 < r) av = load_row8(urow, k0, r, ualigned);
+            const int rpad = (r + 15) & ~15;            // T is written (with zeros) up to here
+            for (int ks = 0; ks < r; ks += 32) {
+                f16x8 av[2];
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const int m = 32 * mb + i32;
-                    const f16x8 bv = __builtin_bit_cast(
-                        f16x8, buf_load16_coherent(tb, m < ti.rows ? (uint32_t)(((ti.row0 + m) * a.ldt + k0) * 2)
-                                                                   : kOobOffset));
-                    acc[s][mb] = mfma32(av, bv, acc[s][mb]);
+                for (int j = 0; j < 2; ++j) {
+                    const int k0 = ks + 16 * j + 8 * h;
+                    av[j] = zero_f16x8();
+                    if (nvalid[s] && k0 < r) av[j] = load_row8(urow, k0, r, ualigned);
                 }
+                if (!waited) {
+                    if (tid == 0) wait_flag(a.flags + 4 * blockIdx.y + 1, 1u, a.flags_status);
+                    __syncthreads();
+                    waited = true;
+                }
+                u32x4 bv[2][MB];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int k0 = ks + 16 * j + 8 * h;
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        const int m = 32 * mb + i32;
+                        bv[j][mb] = buf_load16_coherent(
+                            tb, (m < ti.rows && k0 < rpad) ? (uint32_t)(((ti.row0 + m) * a.ldt + k0) * 2) : kOobOffset);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+                        acc[s][mb] = mfma32(av[j], __builtin_bit_cast(f16x8, bv[j][mb]), acc[s][mb]);
             }
+        }
+        if (!waited) {          // (not reached: some rank is positive)
+            if (tid == 0) wait_flag(a.flags + 4 * blockIdx.y + 1, 1u, a.flags_status);
+            __syncthreads();
         }
         // the last reader of this M-tile's T clears its control words for the next launch
         __syncthreads();
