@@ -267,7 +267,7 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
 #pragma unroll
                     for (int b = 0; b < R; ++b) {
                         const uint32_t base = (rb0 + b < NB) ? ((rb0 + b) * G + 4u * chunk) * 16u : (1u << 27);
-                        u[ci][b] = load_unit_buf(wb, base + lane_u);
+                        u[ci][b] = load_unit_buf_once(wb, base + lane_u);
                         asm volatile("" ::: "memory");      // the loads keep this order (the waits count them)
                     }
                 }
