@@ -23,7 +23,7 @@ txt = open("_build/gemm_decode.s").read()
 checked = 0
 VMEM = re.compile(r"\s+(buffer_|global_|scratch_|flat_)(\S+)")
 CPW = 2
-for m in re.finditer(r"^(_ZN4milo18w3lr_decode_kernelILi(\d+)ELi(\d+)\S*):[^\n]*\n(.*?)s_endpgm", txt, re.S | re.M):
+for m in re.finditer(r"^(_ZN4milo18w3lr_decode_kernelILi(\d+)ELi(\d+)\S*):[^\n]*\n(.*?)^\.Lfunc_end", txt, re.S | re.M):
     name, R, body = m.group(1), int(m.group(2)), m.group(4).split("\n")
     meta = re.search(r"\.name:\s+%s\b(.*?)\.wavefront_size" % re.escape(name), txt, re.S)
     if int(re.search(r"\.private_segment_fixed_size:\s+(\d+)", meta.group(1)).group(1)):
@@ -59,7 +59,7 @@ python3 - <<'PY'
 import re, sys
 txt = open("_build/gemm_tiled.s").read()
 bad, n, waits = [], 0, 0
-for m in re.finditer(r"^(_ZN4milo17w3lr_tiled_kernel\S*):[^\n]*\n(.*?)s_endpgm", txt, re.S | re.M):
+for m in re.finditer(r"^(_ZN4milo17w3lr_tiled_kernel\S*):[^\n]*\n(.*?)^\.Lfunc_end", txt, re.S | re.M):
     n += 1
     body = m.group(2).split("\n")
     bars = [i for i, l in enumerate(body) if re.match(r"\s+s_barrier", l)]

@@ -88,7 +88,8 @@ __device__ __forceinline__ void wait_flag(const uint32_t* flag, uint32_t target,
 // ranks 32w ..; larger ranks take further passes.  T is written with device-coherent stores and
 // published through the tile's flag.
 template <int NW, int MB>
-__device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& ti, unsigned char* smem, int part) {
+__device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& ti, unsigned char* smem, int part,
+                                            uint32_t by) {
     constexpr int BM = 32 * MB;
     constexpr int STAGE = BM * 256;
     constexpr int NCP = BM / 16;
@@ -228,7 +229,7 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
     wait_vmem();
     __syncthreads();
     int last = 0;
-    if (tid == 0) last = atomicAdd(a.flags + 4 * blockIdx.y, 1u) == (uint32_t)a.t_parts - 1u;
+    if (tid == 0) last = atomicAdd(a.flags + 4 * by, 1u) == (uint32_t)a.t_parts - 1u;
     if (!__syncthreads_or(last)) return;
 #pragma unroll
     for (int s = 0; s < NW; ++s) {
@@ -263,7 +264,7 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
     wait_vmem();
     __syncthreads();
     if (tid == 0)
-        __hip_atomic_store(a.flags + 4 * blockIdx.y + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.flags + 4 * by + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int NW, int MB, int EPI>
@@ -276,14 +277,36 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     constexpr int PER = NCP + 4;                 // vector memory instructions a wave issues per chunk
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];      // PD stages
 
-    const TileInfo ti = resolve_tile<NW>(a.rs, blockIdx.y, BM);
+    // Placement.  The hardware hands workgroups to the eight XCDs (each with its own L2) round
+    // robin in grid order.  With many M-tiles the grid is therefore read as eight sequences,
+    // hardware index mod 8, and sequence k works through a contiguous range of the (K split,
+    // M-tile) rows, all column tiles of a row one after the other: the workgroups that share an
+    // activation tile meet in one L2.  (With few tiles a fixed share per XCD balances worse than
+    // the common queue, and the grid is taken as it is.)  Whatever the hardware really does with
+    // the index, every logical workgroup is taken by exactly one hardware workgroup.
+    const uint32_t gx = gridDim.x;
+    const uint32_t n_act = a.rs.tiles ? (uint32_t)*a.rs.n_tiles : (uint32_t)((a.rs.M + BM - 1) / BM);
+    uint32_t bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    if (n_act >= kXcdPlacementTiles) {
+        const uint32_t hw = blockIdx.x + gx * (blockIdx.y + gridDim.y * blockIdx.z);
+        const uint32_t xcd = hw & 7u, seq = hw >> 3;
+        const uint32_t n_rows = n_act * (uint32_t)a.ksplit, base = n_rows >> 3, rem = n_rows & 7u;
+        const uint32_t cnt = base + (xcd < rem ? 1u : 0u), first = xcd * base + (xcd < rem ? xcd : rem);
+        const uint32_t rl = seq / gx;
+        if (rl >= cnt) return;
+        bx = seq - rl * gx;
+        bz = (first + rl) / n_act;
+        by = (first + rl) - bz * n_act;
+    }
+
+    const TileInfo ti = resolve_tile<NW>(a.rs, (int)by, BM);
     if (!ti.valid) return;
     const bool any_rank = ti.w[0].r > 0 || ti.w[1].r > 0;
-    if ((int)blockIdx.x < a.v_tiles) {
+    if ((int)bx < a.v_tiles) {
         // leading workgroup columns of the first K split: each forms one part of T = X V^T for this
-        // M-tile (see v_tile_body).  They sit in the same grid row and split as the workgroups
-        // that wait for them, hence are dispatched before those.
-        if (any_rank && blockIdx.z == 0) v_tile_body<NW, MB>(a, ti, smem, (int)blockIdx.x);
+        // M-tile (see v_tile_body).  They come first in the row of the workgroups that wait for
+        // them, i.e. earlier in the same sequence, hence are dispatched before those.
+        if (any_rank && bz == 0) v_tile_body<NW, MB>(a, ti, smem, (int)bx, by);
         return;
     }
 
@@ -297,9 +320,9 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     const int nchunks = (G + 1) / 2;
     // K split: this workgroup multiplies chunks [c_begin, c_end)
     const int cps = (nchunks + a.ksplit - 1) / a.ksplit;
-    const int c_begin = (int)blockIdx.z * cps;
+    const int c_begin = (int)bz * cps;
     const int c_end = (c_begin + cps < nchunks) ? c_begin + cps : nchunks;
-    const int64_t n0 = (int64_t)((int)blockIdx.x - a.v_tiles) * BN;
+    const int64_t n0 = (int64_t)((int)bx - a.v_tiles) * BN;
 
     // Weight streams of this wave: lane (i32, h) feeds row nrow of the stream, group 2c + h.
     W3Buf wbuf[2];
@@ -462,7 +485,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     // Low-rank term: r extra k-steps with A = U rows and B = T rows.  T of this M-tile is formed
     // by the leading workgroup of the same grid row during this launch: wait for its flag (it was
     // dispatched before this workgroup and never waits itself), then read T coherently.
-    if (any_rank && blockIdx.z == 0) {
+    if (any_rank && bz == 0) {
         const BufRsrc tb0 = make_rsrc(a.T[0], a.t_bytes);
         const BufRsrc tb1 = make_rsrc(a.T[1], a.t_bytes);
         // Two k-steps of 16 ranks at a time: their U fragments (which do not depend on T) and then
@@ -487,7 +510,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                     if (nvalid[s] && k0 < r) av[j] = load_row8(urow, k0, r, ualigned);
                 }
                 if (!waited) {
-                    if (tid == 0) wait_flag(a.flags + 4 * blockIdx.y + 1, 1u, a.flags_status);
+                    if (tid == 0) wait_flag(a.flags + 4 * by + 1, 1u, a.flags_status);
                     __syncthreads();
                     waited = true;
                 }
@@ -510,17 +533,17 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
             }
         }
         if (!waited) {          // (not reached: some rank is positive)
-            if (tid == 0) wait_flag(a.flags + 4 * blockIdx.y + 1, 1u, a.flags_status);
+            if (tid == 0) wait_flag(a.flags + 4 * by + 1, 1u, a.flags_status);
             __syncthreads();
         }
         // the last reader of this M-tile's T clears its control words for the next launch
         __syncthreads();
         if (tid == 0) {
-            const uint32_t readers = gridDim.x - (uint32_t)a.v_tiles;
-            if (atomicAdd(a.flags + 4 * blockIdx.y + 2, 1u) == readers - 1u) {
-                __hip_atomic_store(a.flags + 4 * blockIdx.y, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(a.flags + 4 * blockIdx.y + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(a.flags + 4 * blockIdx.y + 2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t readers = gx - (uint32_t)a.v_tiles;
+            if (atomicAdd(a.flags + 4 * by + 2, 1u) == readers - 1u) {
+                __hip_atomic_store(a.flags + 4 * by, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.flags + 4 * by + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.flags + 4 * by + 2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
@@ -550,7 +573,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                 const int64_t nb = n0 + 64 * wave + 32 * s;
                 if (EPI == EPI_STORE && a.ksplit > 1) {
                     // partial sum of this K split, fp32; a small kernel adds the splits in order
-                    float* orow = reinterpret_cast<float*>(a.out) + (int64_t)blockIdx.z * a.out_split_stride + R * a.ldo;
+                    float* orow = reinterpret_cast<float*>(a.out) + (int64_t)bz * a.out_split_stride + R * a.ldo;
 #pragma unroll
                     for (int vq = 0; vq < 4; ++vq) {
                         const int64_t n = nb + 8 * vq + 4 * h;
@@ -574,7 +597,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                 } else {
                     const int64_t orow_i = a.out_rows ? (int64_t)a.out_rows[R] : R;
                     const float sc = a.out_scale ? a.out_scale[orow_i] : 1.0f;
-                    f16* orow = reinterpret_cast<f16*>(a.out) + (int64_t)blockIdx.z * a.out_split_stride + orow_i * a.ldo;
+                    f16* orow = reinterpret_cast<f16*>(a.out) + (int64_t)bz * a.out_split_stride + orow_i * a.ldo;
 #pragma unroll
                     for (int vq = 0; vq < 4; ++vq) {
                         const int64_t n = nb + 8 * vq + 4 * h;
@@ -625,7 +648,11 @@ int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipSt
     if (n_tiles > 0x7fffffff || m_tiles > 65535) return MILO_ERR_SHAPE;
     if (a.ksplit < 1 || a.ksplit > 64 || a.v_tiles != a.t_parts || (epi == EPI_SWIGLU && a.ksplit != 1))
         return MILO_ERR_SHAPE;
-    dim3 grid((unsigned)n_tiles, (unsigned)m_tiles, (unsigned)a.ksplit);
+    // every one of the eight sequences needs ceil(m_tiles * ksplit / 8) rows of the grid
+    const int64_t rows8 = (((int64_t)m_tiles * a.ksplit + 7) / 8) * 8;
+    const int64_t gy = (rows8 + a.ksplit - 1) / a.ksplit;
+    if (gy > 65535) return MILO_ERR_SHAPE;
+    dim3 grid((unsigned)n_tiles, (unsigned)gy, (unsigned)a.ksplit);
     if (nw == 2 && epi == EPI_SWIGLU) return launch_tiled_mb<2, EPI_SWIGLU>(a, mb, grid, stream);
     if (nw == 1 && epi == EPI_STORE) return launch_tiled_mb<1, EPI_STORE>(a, mb, grid, stream);
     if (nw == 1 && epi == EPI_SCALE_SCATTER)

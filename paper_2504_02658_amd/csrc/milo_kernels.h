@@ -69,6 +69,10 @@ struct TiledArgs {
     const float* out_scale;    // EPI 2: factor per output row (nullptr: 1)
 };
 
+// From this many M-tiles on, the tiled kernel gives each XCD a fixed contiguous share of the tile
+// list (and the MoE work list is dealt accordingly).
+constexpr uint32_t kXcdPlacementTiles = 128;
+
 enum { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_SCALE_SCATTER = 2 };
 
 // Launchers.  mb = tile rows / 32 (1, 2 or 4); m_tiles = grid extent over tiles.

@@ -143,8 +143,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const RouteArgs a)
 }
 
 // Work list of the grouped GEMMs: the slots the experts filled, compacted and put longest first
-// (full tiles in expert order, then the partly filled ones, empty slots dropped), so that the
-// dispatcher, which hands out workgroups in grid order, ends with the short items.  One
+// (full tiles in expert order, then the partly filled ones, empty slots dropped, dealt over the
+// eight ranges the tiled kernel works through in parallel), so that each range ends with its short items.  One
 // workgroup; a thread owns a contiguous range of slots and two scans give every tile its place.
 __global__ __launch_bounds__(kRouteThreads) void order_tiles_kernel(const TileDesc* __restrict__ slots,
                                                                     int n_slots, int bm,
@@ -175,13 +175,23 @@ __global__ __launch_bounds__(kRouteThreads) void order_tiles_kernel(const TileDe
         tfull += wfull[w];
         tpart += wpart[w];
     }
+    // From kXcdPlacementTiles tiles on, the tiled kernel reads the list as eight contiguous ranges,
+    // one per sequence of workgroups (range k starts at k * (n / 8) + min(k, n % 8)).  Position p of the order "full tiles, then
+    // partly filled ones" goes to range p % 8, place p / 8, so that every range gets the same mix
+    // and ends with its short items.
+    const int n = tfull + tpart, base = n >> 3, rem = n & 7;
+    auto place = [&](int p) {
+        if (n < (int)kXcdPlacementTiles) return p;          // the kernel takes the list in order
+        const int k = p & 7;
+        return k * base + (k < rem ? k : rem) + (p >> 3);
+    };
     int pf = bfull + sfull - nfull, pp = tfull + bpart + spart - npart;
     for (int i = lo; i < hi; ++i) {
         const TileDesc td = slots[i];
-        if (td.rows >= bm) tiles[pf++] = td;
-        else if (td.rows > 0) tiles[pp++] = td;
+        if (td.rows >= bm) tiles[place(pf++)] = td;
+        else if (td.rows > 0) tiles[place(pp++)] = td;
     }
-    if (tid == 0) header[1] = tfull + tpart;
+    if (tid == 0) header[1] = n;
 }
 
 // y[t, h..h+3] = fp16( sum_j O[t*topk + j, h..h+3] ), slots in order, invalid ids skipped.
