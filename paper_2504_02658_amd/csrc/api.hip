@@ -49,9 +49,10 @@ static int gemm_mb(int64_t M) {
     if (const char* e = getenv("MILO_GEMM_MB")) mb = atoi(e);           // tuning override
     return mb;
 }
-static int gemm_splits(int64_t M, int64_t N, int64_t K) {
+static int gemm_splits(int64_t M, int64_t N, int64_t K, int r) {
     const int bm = 32 * gemm_mb(M);
-    return tiled_k_splits(((M + bm - 1) / bm) * ((N + 255) / 256), K);
+    const int64_t m_tiles = (M + bm - 1) / bm;
+    return tiled_k_splits(m_tiles * ((N + 255) / 256), K, r > 0 ? m_tiles * tiled_t_parts(K) : 0);
 }
 
 // Adds the fp32 partial sums of the K splits in split order and rounds once.
@@ -81,7 +82,7 @@ extern "C" size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int 
     // control words | four flag words per 32-row tile | T = X V^T, fp16 [M x pad16(r)] | its fp32
     // partials per part of K | with K splits, their fp32 partial sums [M x N] each
     const size_t parts = r > 0 ? (size_t)tiled_t_parts(K) : 0;
-    const int splits = gemm_splits(M, N, K);
+    const int splits = gemm_splits(M, N, K, r);
     return 256 + align_up((size_t)((M + 31) / 32) * 16, 256) +
            align_up((size_t)M * (size_t)rank_pad(r) * 2 + 256, 256) +
            align_up(parts * (size_t)M * (size_t)rank_pad(r) * 4 + 256, 256) +
@@ -131,7 +132,7 @@ extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t 
     const int64_t m_tiles = (M + bm - 1) / bm;
     if (m_tiles > 65535) return MILO_ERR_SHAPE;
     const int parts = r > 0 ? tiled_t_parts(K) : 0;
-    const int splits = gemm_splits(M, N, K);
+    const int splits = gemm_splits(M, N, K, r);
     if ((uint64_t)M * K * 2 >= 0x80000000ull || ((uint64_t)r + 256) * K * 2 >= 0xFFFFFFF0ull ||
         (uint64_t)(parts > 0 ? parts : 1) * M * ldt * 4 >= 0xFFFFFFF0ull || (N & 3) != 0)
         return MILO_ERR_SHAPE;                                          // 32-bit offsets in the kernel

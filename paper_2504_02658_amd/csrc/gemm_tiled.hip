@@ -238,28 +238,52 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
         if (rquads == 0) continue;
         const BufRsrc pb = make_rsrc(a.Tp[s], a.tp_bytes);
         const BufRsrc tb = make_rsrc(a.T[s], a.t_bytes);
-        for (int item = tid; item < ti.rows * rquads; item += kTiledThreads) {
-            const int m = item / rquads, rank = 4 * (item - m * rquads);
-            const uint32_t at = (uint32_t)((ti.row0 + m) * a.ldt + rank);
-            f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
-            for (int p0 = 0; p0 < a.t_parts; p0 += 4) {
-                u32x4 v[4];
+        // all partials of two elements (up to NB parts at a time) are requested at once: the sum
+        // costs a few memory round trips, not one per part
+        const int items = ti.rows * rquads;
+        auto sum_parts = [&](auto nb_c) {
+            constexpr int NB = decltype(nb_c)::value;
+            for (int item0 = tid; item0 < items; item0 += 2 * kTiledThreads) {
+                uint32_t at[2];
+                f32x4 sum[2];
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    v[i] = buf_load16_coherent(
-                        pb, p0 + i < a.t_parts ? (uint32_t)(((p0 + i) * a.t_part_stride + at) * 4) : kOobOffset);
+                for (int u = 0; u < 2; ++u) {
+                    const int item = item0 + u * kTiledThreads;
+                    const int m = item / rquads, rank = 4 * (item - m * rquads);
+                    at[u] = item < items ? (uint32_t)((ti.row0 + m) * a.ldt + rank) : kOobOffset;
+                    sum[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                }
+                for (int p0 = 0; p0 < a.t_parts; p0 += NB) {
+                    u32x4 v[2][NB];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const f32x4 f = __builtin_bit_cast(f32x4, v[i]);
+                    for (int i = 0; i < NB; ++i)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) sum[e] += f[e];
+                        for (int u = 0; u < 2; ++u)
+                            v[u][i] = buf_load16_coherent(
+                                pb, (p0 + i < a.t_parts && at[u] != kOobOffset)
+                                        ? (uint32_t)(((p0 + i) * a.t_part_stride + at[u]) * 4)
+                                        : kOobOffset);
+#pragma unroll
+                    for (int i = 0; i < NB; ++i)
+#pragma unroll
+                        for (int u = 0; u < 2; ++u) {
+                            const f32x4 f = __builtin_bit_cast(f32x4, v[u][i]);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) sum[u][e] += f[e];
+                        }
+                }
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    f16x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = (f16)sum[u][e];
+                    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), tb,
+                                                          at[u] != kOobOffset ? at[u] * 2u : kOobOffset, 0, 17);
                 }
             }
-            f16x4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (f16)sum[e];
-            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), tb, at * 2u, 0, 17);
-        }
+        };
+        if (a.t_parts <= 4) sum_parts(std::integral_constant<int, 4>{});
+        else sum_parts(std::integral_constant<int, 16>{});
     }
     wait_vmem();
     __syncthreads();

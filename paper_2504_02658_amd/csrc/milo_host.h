@@ -24,11 +24,14 @@ inline int device_cus() {
     return cached[dev];
 }
 
-// K splits for a tiled GEMM whose grid would have `tiles` workgroups: enough to give every CU
-// about two workgroups, as long as a split keeps at least eight 128-column chunks.
-inline int tiled_k_splits(int64_t tiles, int64_t K) {
+// K splits for a tiled GEMM whose grid would have `tiles` workgroups, next to `others` workgroups
+// of the same launch that do not split (the ones forming X V^T): as many as fit on the chip at once
+// at two workgroups per CU, as long as a split keeps at least eight 128-column chunks.
+inline int tiled_k_splits(int64_t tiles, int64_t K, int64_t others) {
     const int64_t nchunks = (K / 64 + 1) / 2;
-    int64_t s = tiles > 0 ? (2 * (int64_t)device_cus()) / tiles : 1;
+    int64_t room = 2 * (int64_t)device_cus() - others;
+    if (room < (int64_t)device_cus()) room = device_cus();
+    int64_t s = tiles > 0 ? room / tiles : 1;
     if (s > nchunks / 8) s = nchunks / 8;
     if (s > 16) s = 16;
     if (s < 1) s = 1;

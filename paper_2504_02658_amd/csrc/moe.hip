@@ -252,7 +252,7 @@ static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_m
     if ((uint64_t)(parts > 0 ? parts : 1) * (uint64_t)P * (uint64_t)L->ldt * 4 >= 0xFFFFFFF0ull) return false;
     // the down projection has few column tiles (hidden / 256): split K when they do not fill the chip
     // (counted in full tiles: the partly filled last tile of an expert is cheap)
-    L->splits_down = tiled_k_splits(((P + L->bm - 1) / L->bm) * ((H + 255) / 256), F);
+    L->splits_down = tiled_k_splits(((P + L->bm - 1) / L->bm) * ((H + 255) / 256), F, 0);
     size_t off = 0;
     L->off_header = off; off = align_up(off + 64, 256);
     L->max_tiles32 = max_tiles32;

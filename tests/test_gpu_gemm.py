@@ -167,6 +167,13 @@ def test_k_splits_and_t_parts_many_chunks():
     _check_case(200, 256, 8256, 72, seed=302)           # 129 groups
 
 
+def test_many_m_tiles_take_the_xcd_placement_path():
+    # from 128 M-tiles on the tiled kernel renumbers its workgroups (a contiguous share of the
+    # tile rows per XCD); with one column tile K is split as well, ragged last tile included
+    _check_case(128 * 129 + 40, 256, 2048, 8, seed=303)
+    _check_case(128 * 128, 320, 192, 24, seed=304)
+
+
 def test_graph_replay_matches_eager_and_needs_no_reset():
     # the kernels leave their control words clean: a captured graph of calls that share one
     # workspace per shape can be replayed with eager work in between, bit for bit
