@@ -88,6 +88,17 @@ size_t milo_w3_packed_bytes(int64_t N, int64_t K);
 int milo_pack_w3(const float* W, int64_t N, int64_t K, int group_size, void* q3, void* stream);
 
 /*
+ * The same with the symmetric INT3 quantizer (Section 3.2.3, Eq. symm_int3: q = round(7 w / (2 s))
+ * + 4 with s the largest magnitude of the group).  The blob has the same layout and is used by the
+ * same GEMM entry points: its scale word holds the step d = fp16(2 s / 7) and its zero word 4, so
+ * that dequantization is d * (q - 4).  Codes are computed with the stored step, q = clamp(round(w /
+ * d) + 4, 0, 7), in binary32 with round-half-even; the clamp is needed because w = +s maps to 8.
+ * A group whose fp16 step is zero or not finite stores d = 1, q = 4 (dequantizes to 0).
+ * Arguments and errors as milo_pack_w3.
+ */
+int milo_pack_w3_sym(const float* W, int64_t N, int64_t K, int group_size, void* q3, void* stream);
+
+/*
  * Test aid: the parts of a Q3 blob.  codes[n*K + k] = q[n,k] as bytes; scales and zeros
  * [N x K/64] fp16 row-major.  Each output may be NULL (not all three).
  */

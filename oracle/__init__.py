@@ -14,7 +14,7 @@ Every function here is pinned by CPU tests against something other than itself
 The paper prints no worked numeric example for this path, so nothing is pinned
 against paper-printed values.
 """
-from .quantize import quantize_rtn, dequantize            # noqa: F401
+from .quantize import quantize_rtn, quantize_sym, dequantize   # noqa: F401
 from .packing import (pack_w3, unpack_w3, unit_index, to_unit_order,  # noqa: F401
                       from_unit_order, packed_bytes, code_bytes)
 from .linear import w3lr_linear, linear_from_dense        # noqa: F401

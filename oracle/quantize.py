@@ -60,6 +60,40 @@ def quantize_rtn(W, group=GROUP):
     return q.reshape(N, K), s16, z16
 
 
+def quantize_sym(W, group=GROUP):
+    """Symmetric INT3 quantizer (Section 3.2.3, Eq. symm_int3): q = round(7 w / (2 s)) + 4 with s the
+    largest magnitude of the group.  Returned in the same (codes, scales, zeros) form as
+    quantize_rtn: the scale is the step d = 2 s / 7 and every zero-point is 4, so dequantize()
+    gives d * (q - 4).
+
+    Readings: the step is rounded to fp16 before the codes are computed (q = round(w / d) + 4 with
+    the stored d, as for the asymmetric quantizer); round-half-to-even; the codes are clamped to
+    0..7, which the equation needs because w = +s maps to round(3.5) + 4 = 8; a group whose fp16
+    step is zero or not finite stores d = 1 and codes 4 (dequantizes to zero); binary32, one
+    rounding per operation.
+    """
+    if group != GROUP:
+        raise ValueError("group size must be 64")
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    N, K = W.shape
+    if K % GROUP:
+        raise ValueError("K must be a multiple of 64")
+    Wg = W.reshape(N, K // GROUP, GROUP)
+    amax = np.abs(Wg).max(axis=-1)
+    with np.errstate(over="ignore", invalid="ignore", divide="ignore"):
+        d32 = (amax + amax) / np.float32(QMAX)
+        d16 = d32.astype(np.float16)
+        degenerate = ~(np.isfinite(d16) & (d16 > 0))
+        df = np.where(degenerate, np.float32(1), d16.astype(np.float32))
+        t = np.rint(Wg / df[..., None])
+        t = t + np.float32(4)
+        q = np.clip(t, 0, QMAX)
+    q = np.where(degenerate[..., None], np.float32(4), q).astype(np.uint8)
+    d16 = np.where(degenerate, np.float16(1), d16)
+    z16 = np.full(d16.shape, 4, dtype=np.float16)
+    return q.reshape(N, K), d16, z16
+
+
 def dequantize(codes, scales, zeros):
     """Eq. wdq in fp64: W_dq[n, k] = s[n, g] * (q[n, k] - z[n, g]), g = k // 64."""
     N, K = codes.shape

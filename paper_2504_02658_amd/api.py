@@ -19,7 +19,7 @@ STATUS_NAMES = {0: "MILO_OK", 1: "MILO_ERR_NULL", 2: "MILO_ERR_SHAPE", 3: "MILO_
 
 # every symbol include/milo.h declares
 EXPORTS = ("milo_status_string", "milo_version", "milo_w3_packed_bytes", "milo_pack_w3",
-           "milo_workspace_init",
+           "milo_pack_w3_sym", "milo_workspace_init",
            "milo_unpack_w3", "milo_dequant_w3", "milo_w3lr_gemm_workspace", "milo_w3lr_gemm",
            "milo_moe_w3lr_check_experts", "milo_moe_w3lr_workspace", "milo_moe_w3lr_forward",
            "milo_moe_w3lr_routing_status")
@@ -59,6 +59,8 @@ def lib():
         L.milo_w3_packed_bytes.argtypes = [i64, i64]
         L.milo_pack_w3.restype = ci
         L.milo_pack_w3.argtypes = [vp, i64, i64, ci, vp, vp]
+        L.milo_pack_w3_sym.restype = ci
+        L.milo_pack_w3_sym.argtypes = [vp, i64, i64, ci, vp, vp]
         L.milo_unpack_w3.restype = ci
         L.milo_unpack_w3.argtypes = [vp, i64, i64, vp, vp, vp, vp]
         L.milo_dequant_w3.restype = ci
@@ -136,13 +138,14 @@ def packed_bytes(N, K):
     return int(lib().milo_w3_packed_bytes(N, K))
 
 
-def pack_w3(W, group_size=64):
-    """milo_pack_w3: fp32 CUDA weight [N, K] -> PackedWeight (no compensator)."""
+def pack_w3(W, group_size=64, symmetric=False):
+    """milo_pack_w3 (or milo_pack_w3_sym): fp32 CUDA weight [N, K] -> PackedWeight (no compensator)."""
     W = _dev(W, torch.float32, "W")
     N, K = W.shape
     nbytes = packed_bytes(N, K)
     q3 = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=W.device)
-    _check(lib().milo_pack_w3(_ptr(W), N, K, group_size, _ptr(q3), _stream()), "milo_pack_w3")
+    fn, name = (lib().milo_pack_w3_sym, "milo_pack_w3_sym") if symmetric else (lib().milo_pack_w3, "milo_pack_w3")
+    _check(fn(_ptr(W), N, K, group_size, _ptr(q3), _stream()), name)
     return PackedWeight(N, K, q3[:nbytes])
 
 

@@ -19,6 +19,9 @@ __device__ __forceinline__ uint32_t shfl_xor16(uint32_t v, int m) {
     return (uint32_t)__shfl_xor((int)v, m, 16);
 }
 
+// SYM = false: asymmetric quantizer (Eq. wq).  SYM = true: the symmetric INT3 quantizer (Eq.
+// symm_int3) in the same storage: the scale word holds the step 2 * max|w| / 7, the zero word 4.
+template <bool SYM>
 __global__ __launch_bounds__(kPackThreads) void pack_w3_kernel(
     const float* __restrict__ W, int64_t N, int64_t K, uint32_t* __restrict__ planeA,
     uint32_t* __restrict__ planeB) {
@@ -39,29 +42,50 @@ __global__ __launch_bounds__(kPackThreads) void pack_w3_kernel(
         mx = fmaxf(mx, shfl_xor16(mx, m));
     }
 
-    const float s32 = (mx - mn) / 7.0f;
-    f16 s16 = (f16)s32;
-    float sf = (float)s16;
-    const bool degenerate = !(sf > 0.0f && sf <= 65504.0f);   // zero, NaN or overflowed scale
-    f16 z16;
+    f16 s16, z16;
     uint32_t q[4];
-    if (degenerate) {
-        s16 = (f16)1.0f;
-        z16 = (f16)(-mn);
-        q[0] = q[1] = q[2] = q[3] = 0u;
-    } else {
-        float z = __builtin_rintf((-mn) / sf);
-        z = fminf(fmaxf(z, -65504.0f), 65504.0f);
-        z16 = (f16)z;
-        const float zf = (float)z16;
-        const float in[4] = {v.x, v.y, v.z, v.w};
+    const float in[4] = {v.x, v.y, v.z, v.w};
+    if (SYM) {
+        const float amax = fmaxf(mx, -mn);              // largest magnitude of the group
+        const float s32 = (amax + amax) / 7.0f;
+        s16 = (f16)s32;
+        const float sf = (float)s16;
+        z16 = (f16)4.0f;
+        if (!(sf > 0.0f && sf <= 65504.0f)) {           // zero, NaN or overflowed step: all codes 4
+            s16 = (f16)1.0f;
+            q[0] = q[1] = q[2] = q[3] = 4u;
+        } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float t = in[i] / sf;
-            t = t + zf;
-            t = __builtin_rintf(t);
-            t = fminf(fmaxf(t, 0.0f), 7.0f);
-            q[i] = (uint32_t)t;
+            for (int i = 0; i < 4; ++i) {
+                float t = in[i] / sf;
+                t = __builtin_rintf(t);
+                t = t + 4.0f;
+                t = fminf(fmaxf(t, 0.0f), 7.0f);
+                q[i] = (uint32_t)t;
+            }
+        }
+    } else {
+        const float s32 = (mx - mn) / 7.0f;
+        s16 = (f16)s32;
+        const float sf = (float)s16;
+        const bool degenerate = !(sf > 0.0f && sf <= 65504.0f);   // zero, NaN or overflowed scale
+        if (degenerate) {
+            s16 = (f16)1.0f;
+            z16 = (f16)(-mn);
+            q[0] = q[1] = q[2] = q[3] = 0u;
+        } else {
+            float z = __builtin_rintf((-mn) / sf);
+            z = fminf(fmaxf(z, -65504.0f), 65504.0f);
+            z16 = (f16)z;
+            const float zf = (float)z16;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float t = in[i] / sf;
+                t = t + zf;
+                t = __builtin_rintf(t);
+                t = fminf(fmaxf(t, 0.0f), 7.0f);
+                q[i] = (uint32_t)t;
+            }
         }
     }
 
@@ -163,7 +187,8 @@ extern "C" size_t milo_w3_packed_bytes(int64_t N, int64_t K) {
     return (size_t)(N * K / 64 * 28);
 }
 
-extern "C" int milo_pack_w3(const float* W, int64_t N, int64_t K, int group_size, void* q3, void* stream) {
+template <bool SYM>
+static int pack_launch(const float* W, int64_t N, int64_t K, int group_size, void* q3, void* stream) {
     if (!W || !q3) return MILO_ERR_NULL;
     if (group_size != kGroup) return MILO_ERR_GROUP;
     if (!weight_shape_ok(N, K)) return MILO_ERR_SHAPE;
@@ -173,8 +198,16 @@ extern "C" int milo_pack_w3(const float* W, int64_t N, int64_t K, int group_size
     if (blocks > 0x7fffffff) return MILO_ERR_SHAPE;
     uint32_t* planeA = reinterpret_cast<uint32_t*>(q3);
     uint32_t* planeB = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(q3) + (N * K) / 4);
-    pack_w3_kernel<<<dim3((unsigned)blocks), dim3(kPackThreads), 0, (hipStream_t)stream>>>(W, N, K, planeA, planeB);
+    pack_w3_kernel<SYM><<<dim3((unsigned)blocks), dim3(kPackThreads), 0, (hipStream_t)stream>>>(W, N, K, planeA, planeB);
     return launch_status();
+}
+
+extern "C" int milo_pack_w3(const float* W, int64_t N, int64_t K, int group_size, void* q3, void* stream) {
+    return pack_launch<false>(W, N, K, group_size, q3, stream);
+}
+
+extern "C" int milo_pack_w3_sym(const float* W, int64_t N, int64_t K, int group_size, void* q3, void* stream) {
+    return pack_launch<true>(W, N, K, group_size, q3, stream);
 }
 
 extern "C" int milo_unpack_w3(const void* q3, int64_t N, int64_t K, uint8_t* codes, milo_half* scales,

@@ -23,9 +23,9 @@ def assert_close(Y_gpu, Y_ref, what=""):
     return rel, mx
 
 
-def oracle_weight(W, r, seed=0, exact_svd_limit=1024 * 1024):
+def oracle_weight(W, r, seed=0, exact_svd_limit=1024 * 1024, symmetric=False):
     """Quantize W on the CPU and fit the rank-r compensator to the residual."""
-    q, s, z = oracle.quantize_rtn(W)
+    q, s, z = oracle.quantize_sym(W) if symmetric else oracle.quantize_rtn(W)
     if r > 0:
         E = W.astype(np.float64) - oracle.dequantize(q, s, z)
         if W.size <= exact_svd_limit:
@@ -39,11 +39,11 @@ def oracle_weight(W, r, seed=0, exact_svd_limit=1024 * 1024):
     return dict(codes=q, scales=s, zeros=z, U=U, V=V)
 
 
-def gpu_weight(W, ow, check_pack=True):
+def gpu_weight(W, ow, check_pack=True, symmetric=False):
     """Pack W with the library; the compensator comes from the oracle side as an input."""
     import torch
     from paper_2504_02658_amd import api
-    pw = api.pack_w3(torch.from_numpy(W).cuda())
+    pw = api.pack_w3(torch.from_numpy(W).cuda(), symmetric=symmetric)
     if check_pack:
         N, K = W.shape
         assert np.array_equal(pw.q3.cpu().numpy(), oracle.pack_w3(ow["codes"], ow["scales"], ow["zeros"])), \

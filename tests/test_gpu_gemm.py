@@ -167,6 +167,16 @@ def test_k_splits_and_t_parts_many_chunks():
     _check_case(200, 256, 8256, 72, seed=302)           # 129 groups
 
 
+@pytest.mark.parametrize("M,N,K,r", [(16, 528, 2112, 16), (5, 272, 1408, 0), (200, 512, 2048, 24)])
+def test_symmetric_weights(M, N, K, r):
+    # weights packed by milo_pack_w3_sym (Eq. symm_int3) go through the same kernels
+    case = wl.LinearCase("t", M=M, N=N, K=K, r=r, seed=400 + M)
+    X, W = wl.linear_inputs(case)
+    ow = oracle_weight(W, r, seed=400 + M, symmetric=True)
+    pw = gpu_weight(W, ow, symmetric=True)
+    assert_close(_run(X, pw), oracle.w3lr_linear(X, **ow), f"symmetric M{M} N{N} K{K} r{r}")
+
+
 def test_many_m_tiles_take_the_xcd_placement_path():
     # from 128 M-tiles on the tiled kernel renumbers its workgroups (a contiguous share of the
     # tile rows per XCD); with one column tile K is split as well, ragged last tile included

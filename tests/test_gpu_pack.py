@@ -8,16 +8,16 @@ from paper_2504_02658_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
-def _pack_both(W):
+def _pack_both(W, symmetric=False):
     import torch
     from paper_2504_02658_amd import api
-    q, s, z = oracle.quantize_rtn(W)
-    pw = api.pack_w3(torch.from_numpy(W).cuda())
+    q, s, z = oracle.quantize_sym(W) if symmetric else oracle.quantize_rtn(W)
+    pw = api.pack_w3(torch.from_numpy(W).cuda(), symmetric=symmetric)
     return (q, s, z), pw
 
 
-def _assert_pack_equal(W, what):
-    (q, s, z), pw = _pack_both(W)
+def _assert_pack_equal(W, what, symmetric=False):
+    (q, s, z), pw = _pack_both(W, symmetric)
     N, K = W.shape
     got = pw.q3.cpu().numpy()
     assert got.size == N * K * 7 // 16, what
@@ -89,3 +89,20 @@ def test_unpack_and_dequant():
     s_el = np.repeat(s2.astype(np.float64), 64, axis=1)
     tol = np.abs(ref2) * 2.0 ** -10 + s_el * 2.0 ** -12
     assert np.all(np.abs(wdq2 - ref2) <= tol)
+
+
+def test_pack_sym_bit_exact():
+    # milo_pack_w3_sym against the oracle's symmetric quantizer (Eq. symm_int3), same blob layout
+    for N, K, seed in ((16, 64, 1), (272, 1408, 2), (1024, 1024, 3)):
+        W = wl.gen_weight(N, K, seed=200 + seed, outlier_frac=0.01 if K >= 1024 else 0.0)
+        (q, s, z), _ = _assert_pack_equal(W, f"symmetric gaussian {N}x{K}", symmetric=True)
+        assert np.all(z == np.float16(4))
+    rng = np.random.default_rng(8)
+    W = (rng.standard_normal((64, 512)) * 0.02).astype(np.float32)
+    W[:, 0:64] = 0.0                                      # all zero -> degenerate rule
+    W[:, 64:128] *= 1e-7                                  # step below fp16 resolution
+    W[:, 128:192] *= 3000.0
+    W[0, 192:256] = (np.arange(64) % 8 - 3.5).astype(np.float32) * 0.25    # exact half-way cases, +max clamps
+    W[:, 256:320] = np.abs(W[:, 256:320])                 # one-sided group
+    (q, s, z), _ = _assert_pack_equal(W, "symmetric edge groups", symmetric=True)
+    assert np.all(q[:, 0:64] == 4) and np.all(s[:, 0] == np.float16(1))

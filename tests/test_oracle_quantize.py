@@ -4,7 +4,7 @@ from fractions import Fraction
 import numpy as np
 import pytest
 
-from oracle import quantize_rtn, dequantize
+from oracle import quantize_rtn, quantize_sym, dequantize
 
 
 def _half_even(fr: Fraction) -> int:
@@ -128,3 +128,79 @@ def test_rejects_bad_shapes():
         quantize_rtn(np.zeros((16, 100), np.float32))
     with pytest.raises(ValueError):
         quantize_rtn(np.zeros((16, 128), np.float32), group=128)
+
+
+# ---- symmetric INT3 quantizer (Section 3.2.3, Eq. symm_int3) -------------------------------------
+
+def test_sym_dyadic_worked_example_is_the_papers_equation():
+    # Values j/16 with largest magnitude 14/16: s = 0.875, so 7 w / (2 s) = 4 w = j/4 exactly and the
+    # step 2 s / 7 = 0.25 is exact in fp16.  Eq. symm_int3 evaluated with exact rationals must give
+    # the oracle's codes; +s maps to round(3.5) + 4 = 8 and is clamped, -s to round(-3.5) + 4 = 0.
+    js = list(range(-14, 15)) + [0] * 35
+    w = np.array([j / 16 for j in js], dtype=np.float32)[None, :].repeat(16, axis=0)
+    q, d, z = quantize_sym(w)
+    assert q.dtype == np.uint8 and d.dtype == np.float16 and z.dtype == np.float16
+    assert float(d[0, 0]) == 0.25 and np.all(z == np.float16(4))
+    s_max = Fraction(14, 16)
+    expect = [min(7, max(0, _half_even(7 * Fraction(j, 16) / (2 * s_max)) + 4)) for j in js]
+    assert q[0].tolist() == expect
+    assert expect[js.index(14)] == 7 and expect[js.index(-14)] == 0 and expect[js.index(0)] == 4
+    assert expect[js.index(2)] == 4 and expect[js.index(6)] == 6        # ties go to even
+    wdq = dequantize(q, d, z)
+    assert np.array_equal(wdq[0], 0.25 * (np.array(expect, dtype=np.float64) - 4.0))
+
+
+def test_sym_against_scalar_loop():
+    f = np.float32
+    rng = np.random.default_rng(15)
+    W = (rng.standard_normal((16, 256)) * 0.02).astype(np.float32)
+    W[2, 0:64] += 0.1
+    q, d, z = quantize_sym(W)
+    for n in (0, 2, 9):
+        for g in range(4):
+            grp = W[n, 64 * g: 64 * g + 64]
+            amax = f(max(abs(float(v)) for v in grp))
+            d16 = np.float16(f(f(amax + amax) / f(7)))
+            df = f(d16)
+            codes = [int(min(7, max(0, f(np.rint(f(f(v) / df)) + f(4))))) for v in grp]
+            assert q[n, 64 * g: 64 * g + 64].tolist() == codes
+            assert d[n, g] == d16
+
+
+def test_sym_properties():
+    rng = np.random.default_rng(16)
+    W = (rng.standard_normal((64, 512)) * 0.02).astype(np.float32)
+    q, d, z = quantize_sym(W)
+    assert q.min() >= 0 and q.max() <= 7 and np.all(z == np.float16(4))
+    Wg = W.reshape(64, 8, 64)
+    qg = q.reshape(64, 8, 64)
+    # the weight of largest magnitude sits 3.5 steps from zero, up to the fp16 rounding of the
+    # step: code 7 when it is positive (from 7 or from the clamped 8), 0 or 1 when negative
+    arg = np.abs(Wg).argmax(axis=-1)
+    ext_w = np.take_along_axis(Wg, arg[..., None], -1)[..., 0]
+    ext_q = np.take_along_axis(qg, arg[..., None], -1)[..., 0]
+    assert np.all(np.where(ext_w > 0, ext_q == 7, ext_q <= 1))
+    assert np.any((ext_w < 0) & (ext_q == 0))
+    # rounding error at most half a step everywhere (largest magnitude is 3.5 steps, within fp16
+    # rounding of the step), and about step^2 / 12 on average
+    err = (W.astype(np.float64) - dequantize(q, d, z)).reshape(64, 8, 64)
+    step = d.astype(np.float64)[..., None]
+    assert np.all(np.abs(err) <= step * (0.5 + 4e-3))
+    assert 0.07 < np.mean((err / step) ** 2) < 0.095
+    # odd symmetry wherever the clamp is not involved: q(-w) = 8 - q(w)
+    qn, dn, _ = quantize_sym(-W)
+    assert np.array_equal(dn, d)
+    inner = (q >= 1) & (q <= 7) & (qn >= 1)
+    assert inner.mean() > 0.95
+    assert np.array_equal(qn[inner].astype(int), 8 - q[inner].astype(int))
+    # zero weights get code 4 and dequantize to exactly 0
+    W0 = W.copy(); W0[:, ::7] = 0.0
+    q0, d0, z0 = quantize_sym(W0)
+    assert np.all(q0[:, ::7] == 4) and np.all(dequantize(q0, d0, z0)[:, ::7] == 0.0)
+
+
+def test_sym_degenerate_group():
+    W = np.zeros((16, 128), dtype=np.float32)
+    W[:, 64:] = 1e-9                      # step below fp16 resolution
+    q, d, z = quantize_sym(W)
+    assert np.all(q == 4) and np.all(d == np.float16(1)) and np.all(dequantize(q, d, z) == 0.0)
