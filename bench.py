@@ -219,6 +219,32 @@ def main():
                               "frac_mfma_peak": round(fl / ms / 1e9 / MFMA_FP16_PEAK_TFLOPS, 4)}
             del layer, experts, Xm, Ym, wsm
             torch.cuda.empty_cache()
+        # Context: what library kernels reach on this machine (not this repository's code): a plain
+        # device-to-device copy of 1 GiB (bytes read + written) and a dense fp16 GEMM of 8192^3.
+        def eager_ms(fn, n):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        ms = eager_ms(lambda: dst.copy_(src), 20)
+        copy_gbs = 2.0 * (1 << 30) / (ms * 1e-3) / 1e9
+        del src, dst
+        A = torch.randn((8192, 8192), device=dev, dtype=torch.float16)
+        B = torch.randn((8192, 8192), device=dev, dtype=torch.float16)
+        ms = eager_ms(lambda: torch.matmul(A, B), 10)
+        gemm_tf = 2.0 * 8192 ** 3 / (ms * 1e-3) / 1e12
+        del A, B
+        torch.cuda.empty_cache()
+        extra["achievable_context"] = {"torch_copy_1GiB_GBps": round(copy_gbs, 1),
+                                       "torch_fp16_gemm_8192_TFLOPs": round(gemm_tf, 1)}
         result["extra"] = extra
 
     if not args.no_cpu_baseline:
