@@ -53,7 +53,7 @@ print("decode kernel: load order before %d hand-counted wait sequences verified"
 PY
 # The tiled kernel counts outstanding memory operations by hand too (in its K loop); that is safe as
 # long as the compiler adds none of its own there: no scratch access may sit between the barriers
-# around a hand-written wait.  (Its cold path that forms T may spill; it only waits for zero.)
+# around a hand-written wait for a non-zero count (a wait for zero assumes nothing).  (Its cold path that forms T may spill; it only waits for zero.)
 hipcc $FLAGS -S --cuda-device-only gemm_tiled.hip -o _build/gemm_tiled.s
 python3 - <<'PY'
 import re, sys
@@ -64,8 +64,11 @@ for m in re.finditer(r"^(_ZN4milo17w3lr_tiled_kernel\S*):[^\n]*\n(.*?)^\.Lfunc_e
     body = m.group(2).split("\n")
     bars = [i for i, l in enumerate(body) if re.match(r"\s+s_barrier", l)]
     for i, l in enumerate(body):
-        if not (i > 0 and "ASMSTART" in body[i - 1] and re.search(r"s_waitcnt vmcnt\(\d+\)", l)):
+        w = re.search(r"s_waitcnt vmcnt\((\d+)\)", l)
+        if not (i > 0 and "ASMSTART" in body[i - 1] and w):
             continue
+        if int(w.group(1)) == 0:
+            continue        # waits for everything: valid whatever else is in flight
         waits += 1
         lo = max([b for b in bars if b < i] or [0])
         hi = min([b for b in bars if b > i] or [len(body)])

@@ -184,18 +184,22 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
             if (c + 1 < c_hi) issue_x(c + 1);
             const unsigned char* xs = smem + (c & 1) * STAGE + i32 * 256;
             const int sx = i32 & 15;
+            // A wave whose ranks lie past the compensator's (with a small rank, all but wave 0) only
+            // takes part in the copies and barriers.
+            if (active[0] || active[1]) {
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
+                for (int t = 0; t < 8; ++t) {
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const f16x8 b = __builtin_bit_cast(
-                        f16x8, *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h + t) ^ sx) << 4)));
-                    acc[0][mb] = mfma32(__builtin_bit_cast(f16x8, va[0][t]), b, acc[0][mb]);
-                    acc[1][mb] = mfma32(__builtin_bit_cast(f16x8, va[1][t]), b, acc[1][mb]);
+                    for (int mb = 0; mb < MB; ++mb) {
+                        const f16x8 b = __builtin_bit_cast(
+                            f16x8, *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h + t) ^ sx) << 4)));
+                        acc[0][mb] = mfma32(__builtin_bit_cast(f16x8, va[0][t]), b, acc[0][mb]);
+                        acc[1][mb] = mfma32(__builtin_bit_cast(f16x8, va[1][t]), b, acc[1][mb]);
+                    }
+                    // the registers of this step are free again: fetch the next chunk's fragment into them
+                    va[0][t] = load_v(c + 1, 0, t);
+                    va[1][t] = load_v(c + 1, 1, t);
                 }
-                // the registers of this step are free again: fetch the next chunk's fragment into them
-                va[0][t] = load_v(c + 1, 0, t);
-                va[1][t] = load_v(c + 1, 1, t);
             }
         }
         // D[v] of (s, mb): rank rank0 + 8*(v/4) + 4*h + v%4, row 32*mb + i32; ranks up to the next
