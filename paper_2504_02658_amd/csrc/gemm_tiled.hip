@@ -295,6 +295,21 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
         __hip_atomic_store(a.flags + 4 * by + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Lanes i and i + 32 hold, for the same row of a 32x32 accumulator block, interleaved groups of
+// four features (group v of lane half h is features 8v + 4h ..).  Swapping groups 2, 3 of the lower
+// half with groups 0, 1 of the upper half leaves every lane with 16 consecutive features, starting
+// at 16h, in the order o[0], o[2], o[1], o[3]: two 16-byte stores instead of four scattered 8-byte
+// ones.  Lane pairs are active together (they share the row).
+__device__ __forceinline__ void gather16(u32x2 (&o)[4]) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const u32x2 r0 = __builtin_amdgcn_permlane32_swap(o[j].x, o[j + 2].x, false, false);
+        const u32x2 r1 = __builtin_amdgcn_permlane32_swap(o[j].y, o[j + 2].y, false, false);
+        o[j].x = r0.x; o[j + 2].x = r0.y;
+        o[j].y = r1.x; o[j + 2].y = r1.y;
+    }
+}
+
 template <int NW, int MB, int EPI>
 __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const TiledArgs a) {
     constexpr int BM = 32 * MB;
@@ -577,24 +592,32 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     }
 
     // Epilogue.  D[v] of block (s, mb): feature nb + 8*(v/4) + 4*h + v%4, row 32*mb + i32.
+    // fp16 results go out as 16 consecutive features per lane (see gather16).
+    auto store16 = [&](f16* orow, int64_t nb, u32x2 (&o)[4]) {
+        gather16(o);
+        const int64_t n = nb + 16 * h;
+        if (n < N) {
+            *reinterpret_cast<u32x4*>(orow + n) = u32x4{o[0].x, o[0].y, o[2].x, o[2].y};
+            *reinterpret_cast<u32x4*>(orow + n + 8) = u32x4{o[1].x, o[1].y, o[3].x, o[3].y};
+        }
+    };
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int m = 32 * mb + i32;
         if (m >= ti.rows) continue;
         const int64_t R = (int64_t)ti.row0 + m;
         if (EPI == EPI_SWIGLU) {
-            const int64_t nb = n0 + 32 * wave;
             f16* orow = reinterpret_cast<f16*>(a.out) + R * a.ldo;
+            u32x2 o[4];
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
-                const int64_t n = nb + 8 * vq + 4 * h;
-                if (n >= N) continue;
-                f16x4 o;
+                f16x4 v;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    o[e] = (f16)(silu(acc[0][mb][4 * vq + e]) * acc[1][mb][4 * vq + e]);
-                *reinterpret_cast<f16x4*>(orow + n) = o;
+                    v[e] = (f16)(silu(acc[0][mb][4 * vq + e]) * acc[1][mb][4 * vq + e]);
+                o[vq] = __builtin_bit_cast(u32x2, v);
             }
+            store16(orow, n0 + 32 * wave, o);
         } else {
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
@@ -611,30 +634,26 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                         for (int e = 0; e < 4; ++e) o[e] = acc[s][mb][4 * vq + e];
                         *reinterpret_cast<f32x4*>(orow + n) = o;
                     }
-                } else if (EPI == EPI_STORE) {
-                    f16* orow = reinterpret_cast<f16*>(a.out) + R * a.ldo;
-#pragma unroll
-                    for (int vq = 0; vq < 4; ++vq) {
-                        const int64_t n = nb + 8 * vq + 4 * h;
-                        if (n >= N) continue;
-                        f16x4 o;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = (f16)acc[s][mb][4 * vq + e];
-                        *reinterpret_cast<f16x4*>(orow + n) = o;
-                    }
                 } else {
-                    const int64_t orow_i = a.out_rows ? (int64_t)a.out_rows[R] : R;
-                    const float sc = a.out_scale ? a.out_scale[orow_i] : 1.0f;
-                    f16* orow = reinterpret_cast<f16*>(a.out) + (int64_t)bz * a.out_split_stride + orow_i * a.ldo;
+                    f16* orow;
+                    float sc = 1.0f;
+                    if (EPI == EPI_STORE) {
+                        orow = reinterpret_cast<f16*>(a.out) + R * a.ldo;
+                    } else {
+                        const int64_t orow_i = a.out_rows ? (int64_t)a.out_rows[R] : R;
+                        if (a.out_scale) sc = a.out_scale[orow_i];
+                        orow = reinterpret_cast<f16*>(a.out) + (int64_t)bz * a.out_split_stride + orow_i * a.ldo;
+                    }
+                    u32x2 o[4];
 #pragma unroll
                     for (int vq = 0; vq < 4; ++vq) {
-                        const int64_t n = nb + 8 * vq + 4 * h;
-                        if (n >= N) continue;
-                        f16x4 o;
+                        f16x4 v;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = (f16)(sc * acc[s][mb][4 * vq + e]);
-                        *reinterpret_cast<f16x4*>(orow + n) = o;
+                        for (int e = 0; e < 4; ++e)
+                            v[e] = (f16)(EPI == EPI_STORE ? acc[s][mb][4 * vq + e] : sc * acc[s][mb][4 * vq + e]);
+                        o[vq] = __builtin_bit_cast(u32x2, v);
                     }
+                    store16(orow, nb, o);
                 }
             }
         }
