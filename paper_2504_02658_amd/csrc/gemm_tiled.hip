@@ -320,18 +320,27 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     constexpr int PER = NCP + 4;                 // vector memory instructions a wave issues per chunk
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];      // PD stages
 
-    // Placement.  The hardware hands workgroups to the eight XCDs (each with its own L2) round
-    // robin in grid order.  With many M-tiles the grid is therefore read as eight sequences,
-    // hardware index mod 8, and sequence k works through a contiguous range of the (K split,
-    // M-tile) rows, all column tiles of a row one after the other: the workgroups that share an
-    // activation tile meet in one L2.  (With few tiles a fixed share per XCD balances worse than
-    // the common queue, and the grid is taken as it is.)  Whatever the hardware really does with
-    // the index, every logical workgroup is taken by exactly one hardware workgroup.
-    const uint32_t gx = gridDim.x;
+    // Placement.  The grid is one-dimensional; what a workgroup does follows from its index hw.
+    // The hardware hands workgroups to the eight XCDs (each with its own L2) round robin in index
+    // order.  A row is one M-tile in one K split: first the v_tiles workgroups that form T (first
+    // split only), then the gxm column tiles.
+    //   Few M-tiles: all T workgroups of the launch come first, then the column tiles of every
+    //   (split, tile) row in order, nothing in between - so the working workgroups spread evenly
+    //   over the XCDs and a launch sized for the chip is resident at once.
+    //   Many M-tiles: the indices are read as eight sequences, hw mod 8, and sequence k works
+    //   through a contiguous range of the rows, all workgroups of a row back to back: those that
+    //   share an activation tile meet in one L2.  (With few tiles a fixed share per XCD balances
+    //   worse than the common queue.)
+    // Either way every logical workgroup is taken by exactly one hardware workgroup, whatever the
+    // hardware does with the index, and the T workgroups of a tile have lower indices than (are
+    // dispatched before) the workgroups that wait for them.
+    const uint32_t gxm = (uint32_t)((a.N + BN - 1) / BN);
+    const uint32_t gx = gxm + (uint32_t)a.v_tiles;
     const uint32_t n_act = a.rs.tiles ? (uint32_t)*a.rs.n_tiles : (uint32_t)((a.rs.M + BM - 1) / BM);
-    uint32_t bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    const uint32_t hw = blockIdx.x;
+    if (n_act == 0) return;
+    uint32_t bx, by, bz;
     if (n_act >= kXcdPlacementTiles) {
-        const uint32_t hw = blockIdx.x + gx * (blockIdx.y + gridDim.y * blockIdx.z);
         const uint32_t xcd = hw & 7u, seq = hw >> 3;
         const uint32_t n_rows = n_act * (uint32_t)a.ksplit, base = n_rows >> 3, rem = n_rows & 7u;
         const uint32_t cnt = base + (xcd < rem ? 1u : 0u), first = xcd * base + (xcd < rem ? xcd : rem);
@@ -340,15 +349,28 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
         bx = seq - rl * gx;
         bz = (first + rl) / n_act;
         by = (first + rl) - bz * n_act;
+        if (bx < (uint32_t)a.v_tiles && bz != 0) return;        // T belongs to the first split
+    } else {
+        const uint32_t nv = (uint32_t)a.m_tiles * (uint32_t)a.v_tiles;
+        if (hw < nv) {
+            by = hw / (uint32_t)a.v_tiles;
+            bx = hw - by * (uint32_t)a.v_tiles;
+            bz = 0;
+            if (by >= n_act) return;
+        } else {
+            const uint32_t m = hw - nv, t = m / gxm;
+            bx = m - t * gxm + (uint32_t)a.v_tiles;
+            bz = t / n_act;
+            by = t - bz * n_act;
+            if (bz >= (uint32_t)a.ksplit) return;
+        }
     }
 
     const TileInfo ti = resolve_tile<NW>(a.rs, (int)by, BM);
     if (!ti.valid) return;
     const bool any_rank = ti.w[0].r > 0 || ti.w[1].r > 0;
     if ((int)bx < a.v_tiles) {
-        // leading workgroup columns of the first K split: each forms one part of T = X V^T for this
-        // M-tile (see v_tile_body).  They come first in the row of the workgroups that wait for
-        // them, i.e. earlier in the same sequence, hence are dispatched before those.
+        // forms one part of T = X V^T for this M-tile (see v_tile_body)
         if (any_rank && bz == 0) v_tile_body<NW, MB>(a, ti, smem, (int)bx, by);
         return;
     }
@@ -695,15 +717,17 @@ int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipSt
     if (n_tiles > 0x7fffffff || m_tiles > 65535) return MILO_ERR_SHAPE;
     if (a.ksplit < 1 || a.ksplit > 64 || a.v_tiles != a.t_parts || (epi == EPI_SWIGLU && a.ksplit != 1))
         return MILO_ERR_SHAPE;
-    // every one of the eight sequences needs ceil(m_tiles * ksplit / 8) rows of the grid
+    // every one of the eight sequences may need ceil(m_tiles * ksplit / 8) rows of n_tiles indices
+    // (this also covers the other numbering: m_tiles * (v_tiles + columns * ksplit) indices)
     const int64_t rows8 = (((int64_t)m_tiles * a.ksplit + 7) / 8) * 8;
-    const int64_t gy = (rows8 + a.ksplit - 1) / a.ksplit;
-    if (gy > 65535) return MILO_ERR_SHAPE;
-    dim3 grid((unsigned)n_tiles, (unsigned)gy, (unsigned)a.ksplit);
-    if (nw == 2 && epi == EPI_SWIGLU) return launch_tiled_mb<2, EPI_SWIGLU>(a, mb, grid, stream);
-    if (nw == 1 && epi == EPI_STORE) return launch_tiled_mb<1, EPI_STORE>(a, mb, grid, stream);
+    if (n_tiles * rows8 > 0x7fffffff) return MILO_ERR_SHAPE;
+    TiledArgs b = a;
+    b.m_tiles = m_tiles;
+    dim3 grid((unsigned)(n_tiles * rows8));
+    if (nw == 2 && epi == EPI_SWIGLU) return launch_tiled_mb<2, EPI_SWIGLU>(b, mb, grid, stream);
+    if (nw == 1 && epi == EPI_STORE) return launch_tiled_mb<1, EPI_STORE>(b, mb, grid, stream);
     if (nw == 1 && epi == EPI_SCALE_SCATTER)
-        return launch_tiled_mb<1, EPI_SCALE_SCATTER>(a, mb, grid, stream);
+        return launch_tiled_mb<1, EPI_SCALE_SCATTER>(b, mb, grid, stream);
     return MILO_ERR_SHAPE;
 }
 
