@@ -53,6 +53,14 @@ def test_tiled_shapes(N, K, r):
     _check_case(96, N, K, r, seed=N + K + r)
 
 
+@pytest.mark.parametrize("M,N,K,r", [(8, 1024, 1024, 512), (12, 528, 2112, 136), (200, 1024, 1024, 512),
+                                     (96, 512, 2048, 300)])
+def test_high_rank_compensators(M, N, K, r):
+    # ranks of the size the paper gives dense layers (Section 3.2.2, "Dense-512"): beyond what the
+    # staged low-rank paths hold at once, so the generic path / several passes over the ranks run
+    _check_case(M, N, K, r, seed=500 + M)
+
+
 def test_rank_zero_equals_no_compensator_and_is_deterministic():
     import torch
     from paper_2504_02658_amd import api
