@@ -217,6 +217,25 @@ def main():
                      for e in range(mc.E + mc.n_shared))
             extra[mc.name] = {"us_per_layer": round(ms * 1e3, 1), "TFLOPs": round(fl / ms / 1e9, 1),
                               "frac_mfma_peak": round(fl / ms / 1e9 / MFMA_FP16_PEAK_TFLOPS, 4)}
+            if mc is wl.C3:
+                # the same layer at a decode-sized batch (16 tokens): every expert's weights are
+                # streamed for a handful of rows, so the figure of merit is HBM bytes per second
+                import dataclasses
+                md = dataclasses.replace(mc, T=16)
+                Xd = torch.from_numpy(wl.moe_activations(md)).to(dev)
+                idd_np, gd_np = wl.moe_routing(md)
+                idd, gd = torch.from_numpy(idd_np).to(dev), torch.from_numpy(gd_np).to(dev)
+                Yd = torch.empty((md.T, md.H), dtype=torch.float16, device=dev)
+                wsd = api.new_workspace(layer.workspace_bytes(md.T, idd.shape[1]), dev)
+                msd, _ = time_steps(lambda i: layer.forward(Xd, idd, gd, out=Yd, workspace=wsd), 30, 10, 10)
+                msd /= 30
+                used = sorted(set(idd_np.reshape(-1).tolist()))
+                wb = sum(3 * md.H * md.F * 7 / 16 + 3 * 2 * ranks[e] * (md.H + md.F) for e in used)
+                extra["c3_shape_16_tokens"] = {"us_per_layer": round(msd * 1e3, 1), "experts_used": len(used),
+                                               "weight_MB": round(wb / 1e6, 1),
+                                               "GBps": round(wb / (msd * 1e-3) / 1e9, 1),
+                                               "frac_hbm_peak": round(wb / (msd * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                del Xd, Yd, wsd
             del layer, experts, Xm, Ym, wsm
             torch.cuda.empty_cache()
         # Context: what library kernels reach on this machine (not this repository's code): a plain
@@ -243,8 +262,17 @@ def main():
         gemm_tf = 2.0 * 8192 ** 3 / (ms * 1e-3) / 1e12
         del A, B
         torch.cuda.empty_cache()
+        # ... and a copy of exactly the bytes one c1 launch reads (26.9 MB, sources rotated like the
+        # weight copies, 24 copies per graph): what a kernel launch of that size costs on this machine
+        small = [torch.empty(wbytes, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(24)]
+        small_dst = torch.empty(wbytes, dtype=torch.uint8, device=dev)
+        ms, _ = time_steps(lambda i: small_dst.copy_(small[i % 24]), 240, 24, 48)
+        small_us = ms / 240 * 1e3
+        del small, small_dst
+        torch.cuda.empty_cache()
         extra["achievable_context"] = {"torch_copy_1GiB_GBps": round(copy_gbs, 1),
-                                       "torch_fp16_gemm_8192_TFLOPs": round(gemm_tf, 1)}
+                                       "torch_fp16_gemm_8192_TFLOPs": round(gemm_tf, 1),
+                                       "torch_copy_of_c1_bytes_us": round(small_us, 2)}
         result["extra"] = extra
 
     if not args.no_cpu_baseline:
