@@ -239,7 +239,10 @@ static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_m
     // activations are addressed with 32-bit offsets inside the kernels
     if ((uint64_t)T * H * 2 >= 0x80000000ull || (uint64_t)P * F * 2 >= 0x80000000ull) return false;
     const int64_t avg = P / E;
-    L->bm = avg >= 96 ? 128 : (avg >= 48 ? 64 : 32);
+    // Tile height: an expert whose rows do not fit one tile streams its weights once more, a
+    // taller tile costs more activation copies and a shallower pipeline; measured on the Mixtral
+    // shape the crossovers lie near 26 and 56 rows per expert.
+    L->bm = avg >= 56 ? 128 : (avg >= 26 ? 64 : 32);
     if (const char* e = getenv("MILO_MOE_BM")) L->bm = atoi(e);        // tuning override
     const int64_t max_tiles32 = (P + 31) / 32 + E;      // bound for the smallest tile height
     const int64_t max_tiles = (P + L->bm - 1) / L->bm + E;
