@@ -45,7 +45,9 @@ static int64_t rank_pad(int r) { return ((int64_t)r + 15) / 16 * 16; }
 
 // Tile height (in blocks of 32 rows) and K splits of the tiled kernel for an [M x N x K] problem.
 static int gemm_mb(int64_t M) {
-    int mb = M <= 32 ? 1 : (M <= 64 ? 2 : 4);
+    // tile height / 32; measured on N = 14336, K = 4096: up to 64 rows the shallow tile wins, up to
+    // a few hundred rows two 64-row tiles beat one tall one
+    int mb = M <= 64 ? 1 : (M <= 384 ? 2 : 4);
     if (const char* e = getenv("MILO_GEMM_MB")) mb = atoi(e);           // tuning override
     return mb;
 }
