@@ -154,7 +154,7 @@ extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t 
     ga.T[0] = ga.T[1] = T; ga.ldt = ldt; ga.t_bytes = (uint64_t)M * ldt * 2;
     ga.Tp[0] = ga.Tp[1] = Tp; ga.tp_bytes = (uint64_t)parts * M * ldt * 4;
     ga.t_part_stride = M * ldt; ga.t_parts = parts; ga.v_tiles = parts; ga.ksplit = splits;
-    ga.flags = flags; ga.flags_status = ctrl + 3;
+    ga.flags = flags; ga.flags_status = ctrl + 3; ga.weights_once = m_tiles == 1;
     ga.out = splits > 1 ? static_cast<void*>(partial) : static_cast<void*>(Y);
     ga.ldo = N; ga.out_split_stride = M * N; ga.out_rows = nullptr; ga.out_scale = nullptr;
     int st = launch_tiled(ga, 1, mb, EPI_STORE, (int)m_tiles, stream);

@@ -456,7 +456,8 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const uint32_t u = (ragged && h == 1) ? (1u << 27) : ucur[s];
-            ru[s] = load_unit_buf(wbuf[NW == 1 ? 0 : s], u);
+            ru[s] = a.weights_once ? load_unit_buf_once(wbuf[NW == 1 ? 0 : s], u)
+                                   : load_unit_buf(wbuf[NW == 1 ? 0 : s], u);
             ucur[s] += 32u;
         }
         asm volatile("" ::: "memory");

@@ -59,6 +59,7 @@ struct TiledArgs {
     int v_tiles;        // leading workgroup columns of the grid: t_parts (they work in split 0 only)
     int ksplit;         // K splits; split z multiplies its share of the chunks
     int m_tiles;        // upper bound of the number of M-tiles (set by launch_tiled)
+    int weights_once;   // non-zero: every weight is read by one M-tile only (non-temporal loads)
     uint32_t* flags;    // per M-tile t: [4t] parts done, [4t+1] T ready, [4t+2] readers done; zero between launches
     uint32_t* flags_status;  // set non-zero if a wait ever gave up
     // EPI 0: fp16 [rows x ldo], or with ksplit > 1 fp32 partial sums, split z at out + z * out_split_stride

@@ -357,6 +357,8 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
     rs.tiles = tiles; rs.n_tiles = header + 1; rs.experts = experts;
     rs.M = P;
     const int mb = L.bm / 32;
+    // with few rows per expert nearly every expert is a single tile: its weights are read once
+    const int once = (getenv("MILO_ONCE") ? atoi(getenv("MILO_ONCE")) : (L.bm < 64)) ? 1 : 0;
 
     // gate / up projection
     rs.which[0] = 0; rs.which[1] = 1;
@@ -368,7 +370,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         ga.T[0] = T1; ga.T[1] = T3; ga.ldt = L.ldt; ga.t_bytes = (uint64_t)P * L.ldt * 2;
         ga.Tp[0] = Tp1; ga.Tp[1] = Tp3; ga.tp_bytes = (uint64_t)L.parts_up * P * L.ldt * 4;
         ga.t_part_stride = (int64_t)P * L.ldt; ga.t_parts = L.parts_up; ga.v_tiles = L.parts_up; ga.ksplit = 1;
-        ga.out_split_stride = 0; ga.flags = flags;
+        ga.out_split_stride = 0; ga.flags = flags; ga.weights_once = once;
         ga.flags_status = reinterpret_cast<uint32_t*>(header + 2);
         ga.out = Hbuf; ga.ldo = F; ga.out_rows = nullptr; ga.out_scale = nullptr;
         st = launch_tiled(ga, 2, mb, EPI_SWIGLU, L.max_tiles, stream);
@@ -384,7 +386,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         da.T[0] = T1; da.T[1] = T1; da.ldt = L.ldt; da.t_bytes = (uint64_t)P * L.ldt * 2;
         da.Tp[0] = Tp1; da.Tp[1] = Tp1; da.tp_bytes = (uint64_t)L.parts_down * P * L.ldt * 4;
         da.t_part_stride = (int64_t)P * L.ldt; da.t_parts = L.parts_down; da.v_tiles = L.parts_down;
-        da.ksplit = L.splits_down; da.out_split_stride = (int64_t)P * H; da.flags = flags;
+        da.ksplit = L.splits_down; da.out_split_stride = (int64_t)P * H; da.flags = flags; da.weights_once = once;
         da.flags_status = reinterpret_cast<uint32_t*>(header + 2);
         da.out = O; da.ldo = H; da.out_rows = sorted; da.out_scale = topk_weights;
         st = launch_tiled(da, 1, mb, EPI_SCALE_SCATTER, L.max_tiles, stream);
