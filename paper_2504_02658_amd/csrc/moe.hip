@@ -203,15 +203,27 @@ __global__ __launch_bounds__(256) void combine_kernel(const f16* __restrict__ O,
     const int64_t t = blockIdx.y;
     const int64_t h = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
     if (h >= H) return;
+    // rows are added slot by slot, split by split; eight loads are in flight at a time
     f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int j = 0; j < topk; ++j) {
-        const int id = ids[t * topk + j];
-        if (id < 0 || id >= E) continue;
-        for (int s = 0; s < splits; ++s) {
-            const f16x4 v = *reinterpret_cast<const f16x4*>(O + s * split_stride + (t * topk + j) * H + h);
+    const int total = topk * splits;
+    for (int base = 0; base < total; base += 8) {
+        f16x4 v[8];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) sum[e] += (float)v[e];
+        for (int i = 0; i < 8; ++i) {
+            const int q = base + i;
+            const int j = q / splits, s = q - j * splits;
+            bool ok = q < total;
+            if (ok) {
+                const int id = ids[t * topk + j];
+                ok = id >= 0 && id < E;
+            }
+            v[i] = f16x4{(f16)0.0f, (f16)0.0f, (f16)0.0f, (f16)0.0f};
+            if (ok) v[i] = *reinterpret_cast<const f16x4*>(O + s * split_stride + (t * topk + j) * H + h);
         }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sum[e] += (float)v[i][e];
     }
     f16x4 o;
 #pragma unroll
