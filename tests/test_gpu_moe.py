@@ -32,8 +32,49 @@ def _check(case, what=None):
 def test_tiny_layer_all_tile_heights():
     base = wl.MoECase("tiny", T=40, H=256, F=384, E=4, topk=2, seed=11, rank_choices=(0, 8, 16))
     _check(base)                                              # ~20 rows per expert: 32-row tiles
-    _check(wl.scaled(base, T=150, name="tiny64"))            # ~75 rows: 64-row tiles
+    _check(wl.scaled(base, T=80, name="tiny64"))             # ~40 rows: 64-row tiles
+    _check(wl.scaled(base, T=150, name="tiny128a"))          # ~75 rows: 128-row tiles, partly filled
     _check(wl.scaled(base, T=400, name="tiny128"))           # ~200 rows: 128-row tiles, several per expert
+
+
+def test_many_tiles_take_the_xcd_placement_path():
+    # 16 800 routed rows -> more than 128 M-tiles: the grouped kernels renumber their workgroups
+    # per XCD and the work list is dealt over the eight ranges
+    case = wl.MoECase("many", T=4200, H=256, F=384, E=8, topk=4, seed=14, rank_choices=(0, 8, 24))
+    _check(case)
+
+
+def test_graph_replay_of_a_layer():
+    # routing, flags and partial buffers are re-initialised by the kernels themselves: a captured
+    # layer replays bit for bit with eager work on the same workspace in between
+    import torch
+    case = wl.MoECase("replay", T=150, H=256, F=384, E=4, topk=2, seed=15, rank_choices=(8, 16))
+    _, layer = build_moe(case)
+    X = torch.from_numpy(wl.moe_activations(case)).cuda()
+    ids_np, gates_np = wl.moe_routing(case)
+    ids, gates = torch.from_numpy(ids_np).cuda(), torch.from_numpy(gates_np).cuda()
+    from paper_2504_02658_amd import api
+    ws = api.new_workspace(layer.workspace_bytes(case.T, case.topk), X.device)
+    out = torch.empty((case.T, case.H), dtype=torch.float16, device=X.device)
+    eager = layer.forward(X, ids, gates, workspace=ws).clone()
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        layer.forward(X, ids, gates, out=out, workspace=ws)
+    torch.cuda.current_stream().wait_stream(stream)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        layer.forward(X, ids, gates, out=out, workspace=ws)
+        layer.forward(X, ids, gates, out=out, workspace=ws)
+    for rep in range(3):
+        out.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
+        again = layer.forward(X, ids, gates, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(again, eager)
 
 
 def test_single_token_and_empty_experts():
