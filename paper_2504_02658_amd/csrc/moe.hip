@@ -142,54 +142,87 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const RouteArgs a)
     }
 }
 
-// Work list of the grouped GEMMs: the slots the experts filled, compacted and put longest first
-// (full tiles in expert order, then the partly filled ones, empty slots dropped, dealt over the
-// eight ranges the tiled kernel works through in parallel), so that each range ends with its short items.  One
-// workgroup; a thread owns a contiguous range of slots and two scans give every tile its place.
+// Work list of the grouped GEMMs: the slots the experts filled, compacted (empty slots dropped) and
+// put longest first: a tile costs about what its number of 32-row blocks says, so tiles go by that
+// number, most blocks first, in expert order within a class.  The dispatcher hands out workgroups
+// in list order, so the launch ends with the short items.  One workgroup; a thread owns a
+// contiguous range of slots and a scan per class gives every tile its place.
 __global__ __launch_bounds__(kRouteThreads) void order_tiles_kernel(const TileDesc* __restrict__ slots,
                                                                     int n_slots, int bm,
                                                                     TileDesc* __restrict__ tiles,
                                                                     int32_t* __restrict__ header) {
-    __shared__ int32_t wfull[kRouteThreads / 64], wpart[kRouteThreads / 64];
+    constexpr int NC = 4;                               // classes: bm / 32 blocks down to one
+    __shared__ int32_t wsum[NC][kRouteThreads / 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int per = (n_slots + kRouteThreads - 1) / kRouteThreads;
     const int lo = tid * per < n_slots ? tid * per : n_slots;
     const int hi = lo + per < n_slots ? lo + per : n_slots;
-    int nfull = 0, npart = 0;
+    const int mb = bm / 32;
+    auto cls = [&](int rows) {                          // 0: as many blocks as a full tile
+        const int nb = (rows + 31) / 32;
+        return mb - (nb < mb ? nb : mb);
+    };
+    int cnt[NC] = {0, 0, 0, 0};
     for (int i = lo; i < hi; ++i) {
         const int rows = slots[i].rows;
-        nfull += rows >= bm;
-        npart += rows > 0 && rows < bm;
+        if (rows > 0) {
+            const int c = cls(rows);
+#pragma unroll
+            for (int k = 0; k < NC; ++k) cnt[k] += c == k;
+        }
     }
-    int sfull = nfull, spart = npart;          // inclusive scans within the wave
+    int scan[NC];                                       // inclusive scans within the wave
+#pragma unroll
+    for (int k = 0; k < NC; ++k) scan[k] = cnt[k];
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
-        const int a = __shfl_up(sfull, d, 64), b = __shfl_up(spart, d, 64);
-        if (lane >= d) { sfull += a; spart += b; }
+#pragma unroll
+        for (int k = 0; k < NC; ++k) {
+            const int v = __shfl_up(scan[k], d, 64);
+            if (lane >= d) scan[k] += v;
+        }
     }
-    if (lane == 63) { wfull[wave] = sfull; wpart[wave] = spart; }
+    if (lane == 63) {
+#pragma unroll
+        for (int k = 0; k < NC; ++k) wsum[k][wave] = scan[k];
+    }
     __syncthreads();
-    int bfull = 0, bpart = 0, tfull = 0, tpart = 0;
-    for (int w = 0; w < kRouteThreads / 64; ++w) {
-        if (w < wave) { bfull += wfull[w]; bpart += wpart[w]; }
-        tfull += wfull[w];
-        tpart += wpart[w];
+    int before[NC], total[NC];
+#pragma unroll
+    for (int k = 0; k < NC; ++k) {
+        before[k] = 0;
+        total[k] = 0;
+        for (int w = 0; w < kRouteThreads / 64; ++w) {
+            if (w < wave) before[k] += wsum[k][w];
+            total[k] += wsum[k][w];
+        }
     }
     // From kXcdPlacementTiles tiles on, the tiled kernel reads the list as eight contiguous ranges,
-    // one per sequence of workgroups (range k starts at k * (n / 8) + min(k, n % 8)).  Position p of the order "full tiles, then
-    // partly filled ones" goes to range p % 8, place p / 8, so that every range gets the same mix
-    // and ends with its short items.
-    const int n = tfull + tpart, base = n >> 3, rem = n & 7;
+    // one per sequence of workgroups (range k starts at k * (n / 8) + min(k, n % 8)).  Position p of
+    // the order goes to range p % 8, place p / 8, so that every range gets the same mix and ends
+    // with its short items.
+    const int n = total[0] + total[1] + total[2] + total[3], base = n >> 3, rem = n & 7;
     auto place = [&](int p) {
         if (n < (int)kXcdPlacementTiles) return p;          // the kernel takes the list in order
         const int k = p & 7;
         return k * base + (k < rem ? k : rem) + (p >> 3);
     };
-    int pf = bfull + sfull - nfull, pp = tfull + bpart + spart - npart;
+    int pos[NC];
+    int start = 0;
+#pragma unroll
+    for (int k = 0; k < NC; ++k) {
+        pos[k] = start + before[k] + scan[k] - cnt[k];
+        start += total[k];
+    }
     for (int i = lo; i < hi; ++i) {
         const TileDesc td = slots[i];
-        if (td.rows >= bm) tiles[place(pf++)] = td;
-        else if (td.rows > 0) tiles[place(pp++)] = td;
+        if (td.rows <= 0) continue;
+        const int c = cls(td.rows);
+        int p = 0;
+#pragma unroll
+        for (int k = 0; k < NC; ++k)
+            if (c == k) p = pos[k]++;
+        tiles[place(p)] = td;
     }
     if (tid == 0) header[1] = n;
 }
