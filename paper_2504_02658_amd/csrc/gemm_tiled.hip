@@ -325,7 +325,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     // order.  A row is one M-tile in one K split: first the v_tiles workgroups that form T (first
     // split only), then the gxm column tiles.
     //   Few M-tiles: all T workgroups of the launch come first, then the column tiles of every
-    //   (split, tile) row in order, nothing in between - so the working workgroups spread evenly
+    //   (tile, split) row in order, nothing in between - so the working workgroups spread evenly
     //   over the XCDs and a launch sized for the chip is resident at once.
     //   Many M-tiles: the indices are read as eight sequences, hw mod 8, and sequence k works
     //   through a contiguous range of the rows, all workgroups of a row back to back: those that
@@ -360,9 +360,19 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
         } else {
             const uint32_t m = hw - nv, t = m / gxm;
             bx = m - t * gxm + (uint32_t)a.v_tiles;
-            bz = t / n_act;
-            by = t - bz * n_act;
-            if (bz >= (uint32_t)a.ksplit) return;
+            // first split of every tile first (it also applies the low-rank term, so it is the
+            // longest), then the other splits tile by tile: the list is ordered longest first,
+            // and so is the grid
+            if (t < n_act) {
+                by = t;
+                bz = 0;
+            } else {
+                const uint32_t rest = (uint32_t)a.ksplit - 1u, t2 = t - n_act;
+                if (rest == 0) return;
+                by = t2 / rest;
+                bz = 1u + (t2 - by * rest);
+                if (by >= n_act) return;
+            }
         }
     }
 
