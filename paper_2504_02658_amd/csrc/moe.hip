@@ -143,30 +143,35 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const RouteArgs a)
 }
 
 // Work list of the grouped GEMMs: the slots the experts filled, compacted (empty slots dropped) and
-// put longest first: a tile costs about what its number of 32-row blocks says, so tiles go by that
-// number, most blocks first, in expert order within a class.  The dispatcher hands out workgroups
+// put longest first: a tile costs about what its number of 32-row blocks says, and more with a
+// compensator of high rank, so tiles go by that number, most blocks first, within it those of
+// experts with a rank above 32 first, in expert order within a class.  The dispatcher hands out workgroups
 // in list order, so the launch ends with the short items.  One workgroup; a thread owns a
 // contiguous range of slots and a scan per class gives every tile its place.
 __global__ __launch_bounds__(kRouteThreads) void order_tiles_kernel(const TileDesc* __restrict__ slots,
                                                                     int n_slots, int bm,
                                                                     TileDesc* __restrict__ tiles,
-                                                                    int32_t* __restrict__ header) {
-    constexpr int NC = 4;                               // classes: bm / 32 blocks down to one
+                                                                    int32_t* __restrict__ header,
+                                                                    const milo_w3lr_expert* __restrict__ experts) {
+    constexpr int NC = 8;                               // classes: bm / 32 blocks down to one, x rank
     __shared__ int32_t wsum[NC][kRouteThreads / 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int per = (n_slots + kRouteThreads - 1) / kRouteThreads;
     const int lo = tid * per < n_slots ? tid * per : n_slots;
     const int hi = lo + per < n_slots ? lo + per : n_slots;
     const int mb = bm / 32;
-    auto cls = [&](int rows) {                          // 0: as many blocks as a full tile
-        const int nb = (rows + 31) / 32;
-        return mb - (nb < mb ? nb : mb);
+    auto cls = [&](const TileDesc& td) {                // 0: as many blocks as a full tile, high rank
+        const int nb = (td.rows + 31) / 32;
+        const milo_w3lr_expert& ex = experts[td.expert];
+        const int low = (ex.w1.r <= 32 && ex.w3.r <= 32 && ex.w2.r <= 32) ? 1 : 0;
+        return 2 * (mb - (nb < mb ? nb : mb)) + low;
     };
-    int cnt[NC] = {0, 0, 0, 0};
+    int cnt[NC] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int i = lo; i < hi; ++i) {
-        const int rows = slots[i].rows;
+        const TileDesc td0 = slots[i];
+        const int rows = td0.rows;
         if (rows > 0) {
-            const int c = cls(rows);
+            const int c = cls(td0);
 #pragma unroll
             for (int k = 0; k < NC; ++k) cnt[k] += c == k;
         }
@@ -201,7 +206,10 @@ __global__ __launch_bounds__(kRouteThreads) void order_tiles_kernel(const TileDe
     // one per sequence of workgroups (range k starts at k * (n / 8) + min(k, n % 8)).  Position p of
     // the order goes to range p % 8, place p / 8, so that every range gets the same mix and ends
     // with its short items.
-    const int n = total[0] + total[1] + total[2] + total[3], base = n >> 3, rem = n & 7;
+    int n = 0;
+#pragma unroll
+    for (int k = 0; k < NC; ++k) n += total[k];
+    const int base = n >> 3, rem = n & 7;
     auto place = [&](int p) {
         if (n < (int)kXcdPlacementTiles) return p;          // the kernel takes the list in order
         const int k = p & 7;
@@ -217,7 +225,7 @@ __global__ __launch_bounds__(kRouteThreads) void order_tiles_kernel(const TileDe
     for (int i = lo; i < hi; ++i) {
         const TileDesc td = slots[i];
         if (td.rows <= 0) continue;
-        const int c = cls(td.rows);
+        const int c = cls(td);
         int p = 0;
 #pragma unroll
         for (int k = 0; k < NC; ++k)
@@ -394,7 +402,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
     route_kernel<<<dim3((unsigned)E), dim3(kRouteThreads), 0, stream>>>(ra);
     int st = launch_status();
     if (st != MILO_OK) return st;
-    order_tiles_kernel<<<dim3(1), dim3(kRouteThreads), 0, stream>>>(slots, L.max_tiles, L.bm, tiles, header);
+    order_tiles_kernel<<<dim3(1), dim3(kRouteThreads), 0, stream>>>(slots, L.max_tiles, L.bm, tiles, header, experts);
     st = launch_status();
     if (st != MILO_OK) return st;
 
