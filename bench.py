@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--copies", type=int, default=24)
     ap.add_argument("--extra", action="store_true", help="also measure M=1/4, hot, c2, c3, c4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-c2", action="store_true",
+                    help="run only the c2 prefill GEMM (for counter runs of the tiled kernel)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB elementwise copy kernel 20 times (counter "
                          "calibration for --pmc runs)")
@@ -120,6 +122,19 @@ def main():
                                            case.outlier_gain)).to(dev)
         pw = compress.fit_compensator(W, api.pack_w3(W), case.r, seed=case.seed)
         return W, pw
+
+    if args.only_c2:
+        c2 = wl.C2
+        _, pw2 = build_linear(c2)
+        X2 = torch.from_numpy(wl.gen_activations(c2.M, c2.K, c2.seed)).to(dev)
+        Y2 = torch.empty((c2.M, c2.N), dtype=torch.float16, device=dev)
+        ws2 = api.new_workspace(api.gemm_workspace_bytes(c2.M, c2.N, c2.K, c2.r), dev)
+        ms, _ = time_steps(lambda i: api.w3lr_gemm(X2, pw2, out=Y2, workspace=ws2), 50, 10, 10)
+        ms /= 50
+        f2 = 2.0 * c2.M * (c2.N * c2.K + c2.r * (c2.N + c2.K))
+        print(json.dumps({"c2_prefill": {"us": round(ms * 1e3, 2), "TFLOPs": round(f2 / ms / 1e9, 1),
+                                         "flops_per_call": f2}}))
+        return
 
     case = wl.C1[16]
     W, pw = build_linear(case)
