@@ -559,8 +559,8 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     nvalid[1] = nrow[1] < N;
 
     // Low-rank term: r extra k-steps with A = U rows and B = T rows.  T of this M-tile is formed
-    // by the leading workgroup of the same grid row during this launch: wait for its flag (it was
-    // dispatched before this workgroup and never waits itself), then read T coherently.
+    // by other workgroups of this launch (see v_tile_body): wait for the tile's flag (they were
+    // dispatched before this workgroup and never wait themselves), then read T coherently.
     if (any_rank && bz == 0) {
         const BufRsrc tb0 = make_rsrc(a.T[0], a.t_bytes);
         const BufRsrc tb1 = make_rsrc(a.T[1], a.t_bytes);

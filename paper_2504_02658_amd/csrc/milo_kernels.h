@@ -46,7 +46,7 @@ struct TiledArgs {
     uint64_t x_bytes;   // size of the X buffer in bytes (< 2 GiB: it is addressed with 32-bit offsets)
     int64_t N, K;       // weight shape (out x in)
     // T = X V^T per weight stream, [rows x ldt] fp16, zero beyond the rank.  It is formed during the
-    // launch by the leading workgroup columns: column p multiplies its share of K into the fp32
+    // launch by v_tiles extra workgroups per M-tile: workgroup p multiplies its share of K into the fp32
     // partial Tp[.] + p * t_part_stride, and whichever column finishes last adds the partials in
     // column order, writes T and raises the tile's flag; the other workgroups read T after that.
     f16* T[2];
@@ -56,7 +56,7 @@ struct TiledArgs {
     uint64_t tp_bytes;  // size of each partial buffer in bytes (all parts)
     int64_t t_part_stride;   // elements between consecutive parts
     int t_parts;        // 0 when no weight has a compensator
-    int v_tiles;        // leading workgroup columns of the grid: t_parts (they work in split 0 only)
+    int v_tiles;        // workgroups per M-tile that form T: t_parts (they belong to split 0)
     int ksplit;         // K splits; split z multiplies its share of the chunks
     int m_tiles;        // upper bound of the number of M-tiles (set by launch_tiled)
     int weights_once;   // non-zero: every weight is read by one M-tile only (non-temporal loads)
