@@ -1,5 +1,5 @@
 // Tiled MFMA kernel for the compensated W3A16 linear at M > 16, single or grouped per expert,
-// and the small kernel that forms T = X V^T for the low-rank term.
+// including the workgroups of the same launch that form T = X V^T for the low-rank term.
 //
 // Work split.  A workgroup of four waves owns BM = 32*MB rows of the (expert-sorted) row space
 // and a band of output features.  Each wave keeps two 32-row blocks of weights ("streams")
