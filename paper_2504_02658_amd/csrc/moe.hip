@@ -411,7 +411,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
     rs.M = P;
     const int mb = L.bm / 32;
     // with few rows per expert nearly every expert is a single tile: its weights are read once
-    const int once = (getenv("MILO_ONCE") ? atoi(getenv("MILO_ONCE")) : (L.bm < 64)) ? 1 : 0;
+    const int once = L.bm < 64 ? 1 : 0;
 
     // gate / up projection
     rs.which[0] = 0; rs.which[1] = 1;
