@@ -48,7 +48,10 @@ static int gemm_mb(int64_t M) {
     // tile height / 32; measured on N = 14336, K = 4096: up to 64 rows the shallow tile wins, up to
     // a few hundred rows two 64-row tiles beat one tall one
     int mb = M <= 64 ? 1 : (M <= 384 ? 2 : 4);
-    if (const char* e = getenv("MILO_GEMM_MB")) mb = atoi(e);           // tuning override
+    if (const char* e = getenv("MILO_GEMM_MB")) {                       // tuning override
+        const int v = atoi(e);
+        if (v == 1 || v == 2 || v == 4) mb = v;
+    }
     return mb;
 }
 static int gemm_splits(int64_t M, int64_t N, int64_t K, int r) {

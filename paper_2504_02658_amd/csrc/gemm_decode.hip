@@ -498,7 +498,10 @@ int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream) {
     int R = 4;
     const int64_t want = (int64_t)(cap - workers) * 3 / 4;
     while (R > 1 && (a.N + 16 * R - 1) / (16 * R) < want) R >>= 1;
-    if (const char* e = getenv("MILO_DEC_R")) R = atoi(e);      // tuning override
+    if (const char* e = getenv("MILO_DEC_R")) {                 // tuning override
+        const int v = atoi(e);
+        if (v == 1 || v == 2 || v == 4) R = v;
+    }
     const int rows = 16 * R;
     const int64_t blocks = (a.N + rows - 1) / rows;
     const int grid = (int)(blocks < cap - workers ? blocks : cap - workers) + workers;

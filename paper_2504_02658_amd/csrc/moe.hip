@@ -296,7 +296,10 @@ static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_m
     // taller tile costs more activation copies and a shallower pipeline; measured on the Mixtral
     // shape the crossovers lie near 26 and 56 rows per expert.
     L->bm = avg >= 56 ? 128 : (avg >= 26 ? 64 : 32);
-    if (const char* e = getenv("MILO_MOE_BM")) L->bm = atoi(e);        // tuning override
+    if (const char* e = getenv("MILO_MOE_BM")) {                       // tuning override
+        const int v = atoi(e);
+        if (v == 32 || v == 64 || v == 128) L->bm = v;
+    }
     const int64_t max_tiles32 = (P + 31) / 32 + E;      // bound for the smallest tile height
     const int64_t max_tiles = (P + L->bm - 1) / L->bm + E;
     if (max_tiles > 65535) return false;
