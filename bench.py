@@ -191,6 +191,17 @@ def main():
         del copies[1:]
         torch.cuda.empty_cache()
 
+        # c0: the small parity configuration (launch-latency bound; reported in microseconds only)
+        c0 = wl.C0
+        W0, pw0 = build_linear(c0)
+        del W0
+        X0 = torch.from_numpy(wl.gen_activations(c0.M, c0.K, c0.seed)).to(dev)
+        Y0 = torch.empty((c0.M, c0.N), dtype=torch.float16, device=dev)
+        ws0 = api.new_workspace(api.gemm_workspace_bytes(c0.M, c0.N, c0.K, c0.r), dev)
+        ms, _ = time_steps(lambda i: api.w3lr_gemm(X0, pw0, out=Y0, workspace=ws0), 240, 24, 48)
+        extra["c0_small"] = {"us": round(ms / 240 * 1e3, 3)}
+        del pw0, X0, Y0, ws0
+
         # c2: prefill GEMM
         c2 = wl.C2
         W2, pw2 = build_linear(c2)
