@@ -84,3 +84,13 @@ def test_host_side_argument_errors(L):
     assert f(X=null) == 1 and f(T=0) == 2 and f(topk=0) == 2
     assert f(ws=null) == 5 and f(wsb=1024) == 5
     assert f(r=1000) == 4
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the benchmark measures one GPU; asking for more ends with a message, before any GPU work
+    import subprocess, sys, os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert p.returncode != 0
+    assert "one GPU" in (p.stderr + p.stdout)
