@@ -42,6 +42,25 @@ def test_decode_shapes(N, K, r):
     _check_case(5, N, K, r, seed=N + K + r + 1)
 
 
+@pytest.mark.parametrize("N,K,r", [
+    (256, 14336, 32),      # K > 4096: several pieces of 16 chunks per workgroup; staged low-rank path
+    (256, 14336, 64),      # the same with more T fragments than the staged path holds: plain loads
+    (20480, 256, 16),      # more row blocks than resident workgroups: second turn of the block loop
+    (272, 1408, 20),       # rank not a multiple of 8 at decode: element-wise U loads
+    (4096, 14336, 32),     # Mixtral's own down projection at decode (Section 4 shapes)
+])
+@pytest.mark.parametrize("M", [1, 16])
+def test_decode_long_k_many_blocks_odd_rank(N, K, r, M):
+    _check_case(M, N, K, r, seed=N + K + r + M)
+
+
+def test_decode_block_loop_second_turn_with_staged_low_rank():
+    # many row blocks with a rank the staged path takes (U fragments are re-copied per turn), and
+    # a long K on top of it
+    _check_case(16, 36864, 512, 32, seed=811)
+    _check_case(3, 16400, 4352, 24, seed=812)
+
+
 @pytest.mark.parametrize("M", [17, 32, 33, 64, 100, 130, 257])
 def test_tiled_rows(M):
     _check_case(M, 272, 1408, 8, seed=60 + M)
