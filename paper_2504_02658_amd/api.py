@@ -12,6 +12,8 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libmilo.so")
+# the same library with every hand-counted memory wait replaced by a wait for everything (a check build)
+FULLWAITS_LIB_PATH = os.path.join(_HERE, "lib", "libmilo_fullwaits.so")
 
 STATUS_NAMES = {0: "MILO_OK", 1: "MILO_ERR_NULL", 2: "MILO_ERR_SHAPE", 3: "MILO_ERR_GROUP",
                 4: "MILO_ERR_RANK", 5: "MILO_ERR_WORKSPACE", 6: "MILO_ERR_ROUTING",
@@ -44,43 +46,48 @@ class Expert(ctypes.Structure):
 _lib = None
 
 
+def bind(path):
+    """Load a build of the library and declare the C signatures of include/milo.h on it."""
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is not built; run __graft_entry__.build() "
+                          "(or paper_2504_02658_amd/csrc/build.sh)")
+    L = ctypes.CDLL(path)
+    vp, i64, ci, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    L.milo_status_string.restype = ctypes.c_char_p
+    L.milo_status_string.argtypes = [ci]
+    L.milo_version.restype = ci
+    L.milo_w3_packed_bytes.restype = sz
+    L.milo_w3_packed_bytes.argtypes = [i64, i64]
+    L.milo_pack_w3.restype = ci
+    L.milo_pack_w3.argtypes = [vp, i64, i64, ci, vp, vp]
+    L.milo_pack_w3_sym.restype = ci
+    L.milo_pack_w3_sym.argtypes = [vp, i64, i64, ci, vp, vp]
+    L.milo_unpack_w3.restype = ci
+    L.milo_unpack_w3.argtypes = [vp, i64, i64, vp, vp, vp, vp]
+    L.milo_dequant_w3.restype = ci
+    L.milo_dequant_w3.argtypes = [vp, i64, i64, vp, vp]
+    L.milo_workspace_init.restype = ci
+    L.milo_workspace_init.argtypes = [vp, sz, vp]
+    L.milo_w3lr_gemm_workspace.restype = sz
+    L.milo_w3lr_gemm_workspace.argtypes = [i64, i64, i64, ci]
+    L.milo_w3lr_gemm.restype = ci
+    L.milo_w3lr_gemm.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, vp, vp, sz, vp]
+    L.milo_moe_w3lr_check_experts.restype = ci
+    L.milo_moe_w3lr_check_experts.argtypes = [ctypes.POINTER(Expert), ci, i64, i64,
+                                              ctypes.POINTER(ci)]
+    L.milo_moe_w3lr_workspace.restype = sz
+    L.milo_moe_w3lr_workspace.argtypes = [i64, i64, i64, ci, ci, ci]
+    L.milo_moe_w3lr_forward.restype = ci
+    L.milo_moe_w3lr_forward.argtypes = [vp, i64, i64, i64, vp, ci, ci, vp, vp, ci, vp, vp, sz, vp]
+    L.milo_moe_w3lr_routing_status.restype = ci
+    L.milo_moe_w3lr_routing_status.argtypes = [vp, vp]
+    return L
+
+
 def lib():
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise ImportError(f"{LIB_PATH} is not built; run __graft_entry__.build() "
-                              "(or paper_2504_02658_amd/csrc/build.sh)")
-        L = ctypes.CDLL(LIB_PATH)
-        vp, i64, ci, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
-        L.milo_status_string.restype = ctypes.c_char_p
-        L.milo_status_string.argtypes = [ci]
-        L.milo_version.restype = ci
-        L.milo_w3_packed_bytes.restype = sz
-        L.milo_w3_packed_bytes.argtypes = [i64, i64]
-        L.milo_pack_w3.restype = ci
-        L.milo_pack_w3.argtypes = [vp, i64, i64, ci, vp, vp]
-        L.milo_pack_w3_sym.restype = ci
-        L.milo_pack_w3_sym.argtypes = [vp, i64, i64, ci, vp, vp]
-        L.milo_unpack_w3.restype = ci
-        L.milo_unpack_w3.argtypes = [vp, i64, i64, vp, vp, vp, vp]
-        L.milo_dequant_w3.restype = ci
-        L.milo_dequant_w3.argtypes = [vp, i64, i64, vp, vp]
-        L.milo_workspace_init.restype = ci
-        L.milo_workspace_init.argtypes = [vp, sz, vp]
-        L.milo_w3lr_gemm_workspace.restype = sz
-        L.milo_w3lr_gemm_workspace.argtypes = [i64, i64, i64, ci]
-        L.milo_w3lr_gemm.restype = ci
-        L.milo_w3lr_gemm.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, vp, vp, sz, vp]
-        L.milo_moe_w3lr_check_experts.restype = ci
-        L.milo_moe_w3lr_check_experts.argtypes = [ctypes.POINTER(Expert), ci, i64, i64,
-                                                  ctypes.POINTER(ci)]
-        L.milo_moe_w3lr_workspace.restype = sz
-        L.milo_moe_w3lr_workspace.argtypes = [i64, i64, i64, ci, ci, ci]
-        L.milo_moe_w3lr_forward.restype = ci
-        L.milo_moe_w3lr_forward.argtypes = [vp, i64, i64, i64, vp, ci, ci, vp, vp, ci, vp, vp, sz, vp]
-        L.milo_moe_w3lr_routing_status.restype = ci
-        L.milo_moe_w3lr_routing_status.argtypes = [vp, vp]
-        _lib = L
+        _lib = bind(LIB_PATH)
     return _lib
 
 

@@ -11,45 +11,51 @@ hipcc $FLAGS -c gemm_tiled.hip -o _build/gemm_tiled.o & pids+=($!)
 hipcc $FLAGS -c gemm_decode.hip -o _build/gemm_decode.o & pids+=($!)
 hipcc $FLAGS -c moe.hip -o _build/moe.o & pids+=($!)
 hipcc $FLAGS -c api.hip -o _build/api.o & pids+=($!)
+# the same two GEMM kernels with every hand-counted wait replaced by a wait for everything
+hipcc $FLAGS -DMILO_FULL_WAITS -c gemm_tiled.hip -o _build/gemm_tiled_fw.o & pids+=($!)
+hipcc $FLAGS -DMILO_FULL_WAITS -c gemm_decode.hip -o _build/gemm_decode_fw.o & pids+=($!)
 for p in "${pids[@]}"; do wait $p; done
-# The decode kernel counts outstanding memory operations by hand (see gemm_decode.hip): all loads
-# of a piece are issued in a fixed order (per chunk eight buffer-to-LDS copies, then per row block
-# a 16-byte and a 12-byte load) before the first hand-written "s_waitcnt vmcnt(N)",
-# and the compiler must neither reorder them nor add memory operations of its own (spills).
+# The decode kernel counts outstanding memory operations by hand (see gemm_decode.hip): a streaming
+# wave requests in a fixed order (per chunk XC buffer-to-LDS copies of activations and per row block a
+# 16-byte and a 12-byte load of weights) and waits with "s_waitcnt vmcnt(N)".  The compiler must not
+# reorder these requests; memory operations of its own (register spills) after a counted request only
+# make a counted wait longer, never too short, but they must stay out of the streaming loop.
 hipcc $FLAGS -S --cuda-device-only gemm_decode.hip -o _build/gemm_decode.s
 python3 - <<'PY'
 import re, sys
 txt = open("_build/gemm_decode.s").read()
-checked = 0
 VMEM = re.compile(r"\s+(buffer_|global_|scratch_|flat_)(\S+)")
-CPW = 2
-for m in re.finditer(r"^(_ZN4milo18w3lr_decode_kernelILi(\d+)ELi(\d+)\S*):[^\n]*\n(.*?)^\.Lfunc_end", txt, re.S | re.M):
-    name, R, body = m.group(1), int(m.group(2)), m.group(4).split("\n")
-    meta = re.search(r"\.name:\s+%s\b(.*?)\.wavefront_size" % re.escape(name), txt, re.S)
-    if int(re.search(r"\.private_segment_fixed_size:\s+(\d+)", meta.group(1)).group(1)):
-        sys.exit("%s uses scratch memory" % name)
-    total = CPW * (8 + 2 * R)
-    first = total - (8 + 2)
-    hits = [i for i, line in enumerate(body)
-            if i > 0 and "ASMSTART" in body[i - 1] and re.search(r"s_waitcnt vmcnt\(%d\)" % first, line)]
-    if not hits:
-        sys.exit("%s: no hand-written s_waitcnt vmcnt(%d) found" % (name, first))
-    for i in hits:
-        seen, j = [], i - 1
-        while j >= 0 and len(seen) < total:
-            v = VMEM.match(body[j])
-            if v:
-                seen.append(v.group(1) + v.group(2) + (" lds" if " lds" in body[j] else ""))
-            j -= 1
-        seen.reverse()
-        unit = ["buffer_load_dwordx4", "buffer_load_dwordx3"]
-        want = (["buffer_load_dwordx4 lds"] * 8 + unit * R) * CPW
-        if seen != want:
-            sys.exit("%s: the loads before s_waitcnt vmcnt(%d) are not in the counted order:\n%r" % (name, first, seen))
-        checked += 1
+checked = 0
+for m in re.finditer(r"^(_ZN4milo18w3lr_decode_kernelILi(\d+)ELi(\d+)ELi(\d+)E\S*):[^\n]*\n(.*?)^\.Lfunc_end", txt, re.S | re.M):
+    name = m.group(1)
+    R, LR, XC = (int(m.group(i)) for i in (2, 3, 4))
+    body = m.group(5).split("\n")
+    ev = []
+    for i, line in enumerate(body):
+        w = re.search(r"s_waitcnt vmcnt\((\d+)\)", line)
+        if w and i > 0 and "ASMSTART" in body[i - 1]:
+            if int(w.group(1)) > 0:
+                ev.append(int(w.group(1)))
+            continue
+        v = VMEM.match(line)
+        if v:
+            ev.append(v.group(1) + v.group(2) + (" lds" if " lds" in line else ""))
+    unit = ["buffer_load_dwordx4", "buffer_load_dwordx3"]
+    xcp = ["buffer_load_dwordx4 lds"] * XC
+    nz = lambda seq: [x for x in seq if x != 0]
+    want = xcp + unit * R                                           # first chunk, up front
+    want += nz([2 * (R - 1)]) + xcp + unit                          # loop: unit 0, next activations, next unit 0
+    for b in range(1, R):
+        want += [2 * (R - 1) + XC] + unit                           #       unit b, next unit b
+    want += nz([2 * (R - 1 - b) for b in range(R)])                 # last chunk
+    first = next((i for i, e in enumerate(ev) if e == "buffer_load_dwordx4 lds"), None)
+    got = ev[first:first + len(want)] if first is not None else None
+    if got != want:
+        sys.exit("%s: requests and waits of the streaming loop are not in the counted order:\n%r\nexpected\n%r" % (name, got, want))
+    checked += 1
 if checked == 0:
     sys.exit("decode kernel: nothing checked; the check is out of date")
-print("decode kernel: load order before %d hand-counted wait sequences verified" % checked)
+print("decode kernel: request order around the hand-counted waits verified in %d variants" % checked)
 PY
 # The tiled kernel counts outstanding memory operations by hand too (in its K loop); that is safe as
 # long as the compiler adds none of its own there: no scratch access may sit between the barriers
@@ -79,11 +85,14 @@ if bad or n == 0 or waits == 0:
 print("tiled kernel: no scratch access around %d hand-counted waits in %d variants" % (waits, n))
 PY
 hipcc --offload-arch=gfx950 -shared -fPIC -o "$OUT/libmilo.so" _build/pack.o _build/gemm_tiled.o _build/gemm_decode.o _build/moe.o _build/api.o
+hipcc --offload-arch=gfx950 -shared -fPIC -o "$OUT/libmilo_fullwaits.so" _build/pack.o _build/gemm_tiled_fw.o _build/gemm_decode_fw.o _build/moe.o _build/api.o
 # Every kernel the host code launches must have its launch stub in the library (a stub that the
 # compiler failed to emit only shows up as an undefined symbol when the library is loaded).
-if nm -u "$OUT/libmilo.so" | grep -q "__device_stub__"; then
-    echo "libmilo.so has undefined kernel launch stubs:" >&2
-    nm -u "$OUT/libmilo.so" | grep "__device_stub__" >&2
-    exit 1
-fi
-echo "built $OUT/libmilo.so"
+for lib in libmilo.so libmilo_fullwaits.so; do
+    if nm -u "$OUT/$lib" | grep -q "__device_stub__"; then
+        echo "$lib has undefined kernel launch stubs:" >&2
+        nm -u "$OUT/$lib" | grep "__device_stub__" >&2
+        exit 1
+    fi
+done
+echo "built $OUT/libmilo.so and $OUT/libmilo_fullwaits.so"

@@ -542,7 +542,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
             for (int slot = 0; slot < PD; ++slot) {
                 const int c = c0 + slot;
                 if (c >= c_end) break;
-                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PD - 2) * PER) : "memory");
+                MILO_WAIT_VMEM((PD - 2) * PER);
                 __syncthreads();        // everyone's copies of chunk c landed; everyone left chunk c-1
                 issue(c + PD - 1, (slot + PD - 1) % PD, ring[(slot + PD - 1) % PD]);
                 compute(slot, ring[slot], [](int) {});

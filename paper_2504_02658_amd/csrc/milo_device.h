@@ -98,6 +98,16 @@ __device__ __forceinline__ u32x3 buf_load12(BufRsrc r, uint32_t off) {
 // have completed; nothing may be moved across.
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// A hand-counted wait: at most N of this wave's vector memory operations are still outstanding
+// (they complete in order).  Built with MILO_FULL_WAITS every such wait is for everything, which
+// assumes nothing about what else is in flight: the build script makes a second library that way,
+// and a GPU test compares the two bit for bit.
+#ifdef MILO_FULL_WAITS
+#define MILO_WAIT_VMEM(N) asm volatile("s_waitcnt vmcnt(0)" ::: "memory")
+#else
+#define MILO_WAIT_VMEM(N) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory")
+#endif
+
 // The two planes of a packed weight as buffers.
 struct W3Buf {
     BufRsrc a, b;

@@ -99,6 +99,7 @@ struct DecodeArgs {
     int rblocks;        // ceil(r / 16)
     int nt;             // number of T workers (the first nt workgroups)
     int kh;             // K parts of T (2048 columns each)
+    uint32_t spin_limit;    // polls after which a wait inside the kernel gives up
 };
 size_t decode_workspace_bytes(int r, int64_t K);
 int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream);
