@@ -8,8 +8,10 @@ Infinity Cache) so that every step streams its weight from HBM ("cold" protocol)
 captured in a HIP graph so that Python call overhead does not throttle a microsecond-scale kernel.
 value = (packed blob: codes, scales, zero-points; + U + V bytes) / time per step.
 
-Prints ONE JSON line.  --extra adds M = 1 / 4, cache-resident ("hot") numbers, the prefill GEMM
-(c2) and the two MoE layers (c3, c4) to an "extra" object.
+Prints ONE JSON line.  Besides the headline it carries, under "extra", the other workloads of the
+metric, each with its own roofline object: c1 at M = 1 and 4, Mixtral's down projection at decode,
+the small configuration c0, the prefill GEMM c2 and the two MoE layers c3 and c4 (plus c3's shape at
+a decode-sized batch).  --only NAME[,NAME...] restricts the run to some legs (for profiler runs).
 """
 import argparse
 import json
@@ -22,6 +24,8 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_FP16_PEAK_TFLOPS = 2500.0
+MIN_TIMED_MS = 20.0             # a timed region shorter than this is repeated until it is not
+LEGS = ("c1", "c1_small_m", "w2_decode", "c0", "c2", "c3", "c4")
 
 
 def measured_traffic():
@@ -43,10 +47,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=240)
     ap.add_argument("--warmup", type=int, default=48)
     ap.add_argument("--copies", type=int, default=24)
-    ap.add_argument("--extra", action="store_true", help="also measure M=1/4, hot, c2, c3, c4")
+    ap.add_argument("--only", type=str, default="",
+                    help="comma-separated legs to run (of: %s); default all" % ", ".join(LEGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only-c2", action="store_true",
-                    help="run only the c2 prefill GEMM (for counter runs of the tiled kernel)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB elementwise copy kernel 20 times (counter "
                          "calibration for --pmc runs)")
@@ -56,8 +59,10 @@ def parse():
 
 
 def time_steps(fn_step, n_steps, period, warmup):
-    """Time exactly n_steps calls of fn_step(i) (i cycles through `period` variants) inside HIP
-    graphs: one graph of `period` steps replayed, plus one for the remainder.  Returns ms total."""
+    """Time n_steps calls of fn_step(i) (i cycles through `period` variants) captured in HIP graphs
+    (one graph of `period` steps, one for the remainder) with HIP events on the launching stream.
+    A block of n_steps that takes less than MIN_TIMED_MS is repeated, so that the timed region never
+    is a single short replay.  Returns (ms per step, steps timed)."""
     import torch
     stream = torch.cuda.Stream()
     stream.wait_stream(torch.cuda.current_stream())
@@ -74,23 +79,82 @@ def time_steps(fn_step, n_steps, period, warmup):
                 fn_step(i)
         return g
 
-    g_full = capture(period)
-    rem = n_steps % period
+    full, rem = divmod(n_steps, period)
+    g_full = capture(period) if full else None
     g_rem = capture(rem) if rem else None
-    for _ in range(max(1, warmup // period)):
-        g_full.replay()
+
+    def block():
+        for _ in range(full):
+            g_full.replay()
+        if g_rem is not None:
+            g_rem.replay()
+
+    done = 0
+    while done < max(warmup, 1):
+        block()
+        done += n_steps
     torch.cuda.synchronize()
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    start.record()
-    for _ in range(n_steps // period):
-        g_full.replay()
-    if g_rem is not None:
-        g_rem.replay()
-    stop.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    return start.elapsed_time(stop), wall_ms
+    total_ms, timed, reps = 0.0, 0, 1
+    while True:
+        start.record()
+        for _ in range(reps):
+            block()
+        stop.record()
+        torch.cuda.synchronize()
+        total_ms += start.elapsed_time(stop)
+        timed += reps * n_steps
+        if total_ms >= MIN_TIMED_MS or timed >= 200000:
+            break
+        per = total_ms / timed
+        reps = max(1, int((MIN_TIMED_MS - total_ms) / (per * n_steps)) + 1)
+    return total_ms / timed, timed
+
+
+def fit_compensator(W, pw, r, niter=2, oversample=10, seed=0):
+    """Workload preparation (not part of the library): rank-r compensator of a packed weight, with
+    the residual E = W - W_dq from the library's own dequantization kernel and U = U^_r sqrt(S_r),
+    V = sqrt(S_r) V^_r (Section 3.2.3, Eq. UV) from the randomized SVD the paper's implementation
+    uses (appendix "Implementation": torch.svd_lowrank)."""
+    import torch
+    from paper_2504_02658_amd import api
+    if r == 0:
+        return pw
+    E = W - api.dequant_w3(pw).float()
+    gen_state = torch.random.get_rng_state()
+    torch.manual_seed(seed)
+    try:
+        Uh, S, Vh = torch.svd_lowrank(E, q=min(r + oversample, min(E.shape)), niter=niter)
+    finally:
+        torch.random.set_rng_state(gen_state)
+    rs = torch.sqrt(S[:r])
+    U = (Uh[:, :r] * rs[None, :]).to(torch.float16).contiguous()
+    V = (rs[:, None] * Vh[:, :r].T).to(torch.float16).contiguous()
+    return pw.with_compensator(U, V)
+
+
+def clone_weight(pw):
+    """A byte-identical copy at new addresses (to rotate weights through HBM)."""
+    from paper_2504_02658_amd import api
+    return api.PackedWeight(pw.N, pw.K, pw.q3.clone(),
+                            None if pw.U is None else pw.U.clone(),
+                            None if pw.V is None else pw.V.clone())
+
+
+def hbm_roofline(nbytes, ms, kernel, **more):
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    d = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "kernel": kernel, "bytes_per_launch": int(nbytes)}
+    d.update(more)
+    return d
+
+
+def mfma_roofline(flops, ms, kernel, **more):
+    tf = flops / (ms * 1e-3) / 1e12
+    d = {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_FP16_PEAK_TFLOPS, "unit": "TFLOP/s",
+         "frac": round(tf / MFMA_FP16_PEAK_TFLOPS, 4), "traffic": None, "kernel": kernel, "flops_per_step": flops}
+    d.update(more)
+    return d
 
 
 def main():
@@ -99,9 +163,14 @@ def main():
         print("bench.py: this build runs on exactly one GPU (--gpus 1); collectives and sharding "
               "are not part of it.", file=sys.stderr)
         sys.exit(2)
+    legs = set(LEGS) if not args.only else set(x.strip() for x in args.only.split(",") if x.strip())
+    unknown = legs - set(LEGS)
+    if unknown:
+        print("bench.py: unknown legs %s (known: %s)" % (sorted(unknown), ", ".join(LEGS)), file=sys.stderr)
+        sys.exit(2)
     import numpy as np
     import torch
-    from paper_2504_02658_amd import api, compress, workloads as wl
+    from paper_2504_02658_amd import api, workloads as wl
 
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
@@ -120,185 +189,148 @@ def main():
     def build_linear(case):
         W = torch.from_numpy(wl.gen_weight(case.N, case.K, case.seed, case.outlier_frac,
                                            case.outlier_gain)).to(dev)
-        pw = compress.fit_compensator(W, api.pack_w3(W), case.r, seed=case.seed)
+        pw = fit_compensator(W, api.pack_w3(W), case.r, seed=case.seed)
         return W, pw
 
-    if args.only_c2:
-        c2 = wl.C2
-        _, pw2 = build_linear(c2)
-        X2 = torch.from_numpy(wl.gen_activations(c2.M, c2.K, c2.seed)).to(dev)
-        Y2 = torch.empty((c2.M, c2.N), dtype=torch.float16, device=dev)
-        ws2 = api.new_workspace(api.gemm_workspace_bytes(c2.M, c2.N, c2.K, c2.r), dev)
-        ms, _ = time_steps(lambda i: api.w3lr_gemm(X2, pw2, out=Y2, workspace=ws2), 50, 10, 10)
-        ms /= 50
-        f2 = 2.0 * c2.M * (c2.N * c2.K + c2.r * (c2.N + c2.K))
-        print(json.dumps({"c2_prefill": {"us": round(ms * 1e3, 2), "TFLOPs": round(f2 / ms / 1e9, 1),
-                                         "flops_per_call": f2}}))
-        return
-
-    case = wl.C1[16]
-    W, pw = build_linear(case)
-    copies = [pw] + [compress.clone_weight(pw) for _ in range(args.copies - 1)]
-    wbytes = pw.weight_bytes()
-    code_bytes = pw.q3.numel()           # codes, scales and zero-points
-
-    def decode_bench(M, weights, steps, warmup):
-        X = torch.from_numpy(wl.gen_activations(M, case.K, case.seed)).to(dev)
-        Y = torch.empty((M, case.N), dtype=torch.float16, device=dev)
-        ws = api.new_workspace(api.gemm_workspace_bytes(M, case.N, case.K, case.r), dev)
+    def gemm_leg(M, K, N, r, weights, steps, warmup):
+        X = torch.from_numpy(wl.gen_activations(M, K, 1001)).to(dev)
+        Y = torch.empty((M, N), dtype=torch.float16, device=dev)
+        ws = api.new_workspace(api.gemm_workspace_bytes(M, N, K, r), dev)
         step = lambda i: api.w3lr_gemm(X, weights[i % len(weights)], out=Y, workspace=ws)
-        ev_ms, wall_ms = time_steps(step, steps, len(weights), warmup)
-        return ev_ms / steps, wall_ms / steps
+        ms, timed = time_steps(step, steps, len(weights), warmup)
+        assert api.workspace_status(ws) == 0, "a wait inside a GEMM kernel gave up"
+        return ms, timed
 
-    ms_step, wall_step = decode_bench(16, copies, args.steps, args.warmup)
-    gbs = wbytes / (ms_step * 1e-3) / 1e9
-    flops = 2.0 * 16 * (case.N * case.K + case.r * (case.N + case.K))
+    result, extra = None, {}
+    case = wl.C1[16]
+    W1 = pw1 = copies = None
+    if legs & {"c1", "c1_small_m"} or not args.no_cpu_baseline:
+        W1, pw1 = build_linear(case)
+    if legs & {"c1", "c1_small_m"}:
+        copies = [pw1] + [clone_weight(pw1) for _ in range(args.copies - 1)]
+    wbytes = pw1.weight_bytes() if pw1 is not None else 0
+    code_bytes = pw1.q3.numel() if pw1 is not None else 0
 
-    result = {
-        "metric": "W3+low-rank GEMM HBM GB/s (M<=16)",
-        "value": round(gbs, 1),
-        "unit": "GB/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": round(ms_step, 6),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f16",
-        "data": "synthetic",
-        "config": {"workload": "c1: Mixtral-8x7B expert up-projection at decode, M=16, N=14336, "
-                               "K=4096, W3 g64 asym + rank-32 fp16 compensator, "
-                               f"{args.copies} weight copies rotated (cold HBM)",
-                   "M": 16, "N": case.N, "K": case.K, "r": case.r, "copies": args.copies},
-        "us_per_call": round(ms_step * 1e3, 3),
-        "tflops": round(flops / (ms_step * 1e-3) / 1e12, 3),
-        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic(),
-                     "kernel": "w3lr_decode_kernel",
-                     "bytes_per_launch": wbytes, "weight_only_bytes": code_bytes,
-                     "weight_only_frac": round(code_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
-    }
+    if "c1" in legs:
+        ms_step, timed = gemm_leg(16, case.K, case.N, case.r, copies, args.steps, args.warmup)
+        gbs = wbytes / (ms_step * 1e-3) / 1e9
+        flops = 2.0 * 16 * (case.N * case.K + case.r * (case.N + case.K))
+        result = {
+            "metric": "W3+low-rank GEMM HBM GB/s (M<=16)",
+            "value": round(gbs, 1),
+            "unit": "GB/s",
+            "n_gpus": 1,
+            "steps": args.steps,
+            "warmup": args.warmup,
+            "ms_per_step": round(ms_step, 6),
+            "higher_is_better": True,
+            "scaling": "weak",
+            "vs_baseline": None,
+            "dtype": "f16",
+            "data": "synthetic",
+            "config": {"workload": "c1: Mixtral-8x7B expert up-projection at decode, M=16, N=14336, "
+                                   "K=4096, W3 g64 asym + rank-32 fp16 compensator, "
+                                   f"{args.copies} weight copies rotated (cold HBM)",
+                       "M": 16, "N": case.N, "K": case.K, "r": case.r, "copies": args.copies},
+            "timed_steps": timed,
+            "us_per_call": round(ms_step * 1e3, 3),
+            "tflops": round(flops / (ms_step * 1e-3) / 1e12, 3),
+            "roofline": hbm_roofline(wbytes, ms_step, "w3lr_decode_kernel", traffic=measured_traffic(),
+                                     weight_only_bytes=code_bytes,
+                                     weight_only_frac=round(code_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)),
+        }
+    else:
+        result = {"metric": "W3+low-rank GEMM HBM GB/s (M<=16)", "value": None, "unit": "GB/s", "n_gpus": 1,
+                  "steps": args.steps, "warmup": args.warmup, "note": "headline leg not run (--only)"}
 
-    if args.extra:
-        extra = {}
+    if "c1_small_m" in legs:
         for M in (1, 4):
-            ms, _ = decode_bench(M, copies, args.steps, args.warmup)
+            ms, _ = gemm_leg(M, case.K, case.N, case.r, copies, args.steps, args.warmup)
             extra[f"c1_M{M}_cold"] = {"us": round(ms * 1e3, 3),
-                                      "GBps": round(wbytes / (ms * 1e-3) / 1e9, 1)}
-        ms, _ = decode_bench(16, copies[:1] * 24, args.steps, args.warmup)
-        extra["c1_M16_hot"] = {"us": round(ms * 1e3, 3), "GBps": round(wbytes / (ms * 1e-3) / 1e9, 1)}
+                                      "roofline": hbm_roofline(wbytes, ms, "w3lr_decode_kernel")}
+        ms, _ = gemm_leg(16, case.K, case.N, case.r, copies[:1] * 24, args.steps, args.warmup)
+        extra["c1_M16_hot"] = {"us": round(ms * 1e3, 3), "note": "one weight copy, cache resident; not an HBM figure"}
+    if copies is not None:
         del copies[1:]
+        copies = None
         torch.cuda.empty_cache()
 
+    if "w2_decode" in legs:
+        # Mixtral's down projection at decode (the other expert GEMM shape of Section 4): long K
+        wc = wl.LinearCase("w2_decode", M=16, N=4096, K=14336, r=32, seed=1005)
+        _, pww = build_linear(wc)
+        wcopies = [pww] + [clone_weight(pww) for _ in range(args.copies - 1)]
+        ms, _ = gemm_leg(16, wc.K, wc.N, wc.r, wcopies, args.steps, args.warmup)
+        extra["w2_decode_M16_cold"] = {"us": round(ms * 1e3, 3), "N": wc.N, "K": wc.K, "r": wc.r,
+                                       "roofline": hbm_roofline(pww.weight_bytes(), ms, "w3lr_decode_kernel")}
+        del wcopies, pww
+        torch.cuda.empty_cache()
+
+    if "c0" in legs:
         # c0: the small parity configuration (launch-latency bound; reported in microseconds only)
         c0 = wl.C0
-        W0, pw0 = build_linear(c0)
-        del W0
-        X0 = torch.from_numpy(wl.gen_activations(c0.M, c0.K, c0.seed)).to(dev)
-        Y0 = torch.empty((c0.M, c0.N), dtype=torch.float16, device=dev)
-        ws0 = api.new_workspace(api.gemm_workspace_bytes(c0.M, c0.N, c0.K, c0.r), dev)
-        ms, _ = time_steps(lambda i: api.w3lr_gemm(X0, pw0, out=Y0, workspace=ws0), 240, 24, 48)
-        extra["c0_small"] = {"us": round(ms / 240 * 1e3, 3)}
-        del pw0, X0, Y0, ws0
+        _, pw0 = build_linear(c0)
+        ms, _ = gemm_leg(c0.M, c0.K, c0.N, c0.r, [pw0] * 24, 240, 48)
+        extra["c0_small"] = {"us": round(ms * 1e3, 3)}
+        del pw0
 
-        # c2: prefill GEMM
+    if "c2" in legs:
         c2 = wl.C2
-        W2, pw2 = build_linear(c2)
-        del W2
-        X2 = torch.from_numpy(wl.gen_activations(c2.M, c2.K, c2.seed)).to(dev)
-        Y2 = torch.empty((c2.M, c2.N), dtype=torch.float16, device=dev)
-        ws2 = api.new_workspace(api.gemm_workspace_bytes(c2.M, c2.N, c2.K, c2.r), dev)
-        ms, _ = time_steps(lambda i: api.w3lr_gemm(X2, pw2, out=Y2, workspace=ws2), 50, 10, 10)
-        ms /= 50
+        _, pw2 = build_linear(c2)
+        ms, _ = gemm_leg(c2.M, c2.K, c2.N, c2.r, [pw2] * 10, 50, 10)
         f2 = 2.0 * c2.M * (c2.N * c2.K + c2.r * (c2.N + c2.K))
-        extra["c2_prefill"] = {"us": round(ms * 1e3, 2), "TFLOPs": round(f2 / ms / 1e9, 1),
-                               "frac_mfma_peak": round(f2 / ms / 1e9 / MFMA_FP16_PEAK_TFLOPS, 4)}
-        del pw2, X2, Y2, ws2
+        extra["c2_prefill"] = {"us": round(ms * 1e3, 2),
+                               "roofline": mfma_roofline(f2, ms, "w3lr_tiled_kernel<1,4,0> (+ splitk_sum_kernel)")}
+        del pw2
         torch.cuda.empty_cache()
 
-        # c3 / c4: MoE layers (weights drawn on the GPU with the same distribution)
-        for mc in (wl.C3, wl.C4):
-            gen = torch.Generator(device=dev)
-            gen.manual_seed(mc.seed)
-            ranks = wl.expert_ranks(mc)
-            experts = []
-            for e in range(mc.E + mc.n_shared):
-                trip = []
-                for (N, K) in ((mc.F, mc.H), (mc.F, mc.H), (mc.H, mc.F)):
-                    We = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * wl.WEIGHT_STD
-                    trip.append(compress.fit_compensator(We, api.pack_w3(We), ranks[e], seed=e))
-                    del We
-                experts.append(tuple(trip))
-            layer = api.MoELayer(experts, mc.H, mc.F)
-            Xm = torch.from_numpy(wl.moe_activations(mc)).to(dev)
-            ids_np, gates_np = wl.moe_routing(mc)
+    # c3 / c4: MoE layers (weights drawn on the GPU with the same distribution as the numpy recipe)
+    for leg, mc in (("c3", wl.C3), ("c4", wl.C4)):
+        if leg not in legs:
+            continue
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(mc.seed)
+        ranks = wl.expert_ranks(mc)
+        experts = []
+        for e in range(mc.E + mc.n_shared):
+            trip = []
+            for (N, K) in ((mc.F, mc.H), (mc.F, mc.H), (mc.H, mc.F)):
+                We = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * wl.WEIGHT_STD
+                trip.append(fit_compensator(We, api.pack_w3(We), ranks[e], seed=e))
+                del We
+            experts.append(tuple(trip))
+        layer = api.MoELayer(experts, mc.H, mc.F)
+
+        def moe_leg(mcase):
+            Xm = torch.from_numpy(wl.moe_activations(mcase)).to(dev)
+            ids_np, gates_np = wl.moe_routing(mcase)
             ids, gates = torch.from_numpy(ids_np).to(dev), torch.from_numpy(gates_np).to(dev)
-            Ym = torch.empty((mc.T, mc.H), dtype=torch.float16, device=dev)
-            wsm = api.new_workspace(layer.workspace_bytes(mc.T, ids.shape[1]), dev)
+            Ym = torch.empty((mcase.T, mcase.H), dtype=torch.float16, device=dev)
+            wsm = api.new_workspace(layer.workspace_bytes(mcase.T, ids.shape[1]), dev)
             ms, _ = time_steps(lambda i: layer.forward(Xm, ids, gates, out=Ym, workspace=wsm), 30, 10, 10)
-            ms /= 30
-            pairs = np.bincount(ids_np.reshape(-1), minlength=mc.E + mc.n_shared)
-            fl = sum(2.0 * int(pairs[e]) * (3 * mc.H * mc.F + 3 * ranks[e] * (mc.H + mc.F))
-                     for e in range(mc.E + mc.n_shared))
-            extra[mc.name] = {"us_per_layer": round(ms * 1e3, 1), "TFLOPs": round(fl / ms / 1e9, 1),
-                              "frac_mfma_peak": round(fl / ms / 1e9 / MFMA_FP16_PEAK_TFLOPS, 4)}
-            if mc is wl.C3:
-                # the same layer at a decode-sized batch (16 tokens): every expert's weights are
-                # streamed for a handful of rows, so the figure of merit is HBM bytes per second
-                import dataclasses
-                md = dataclasses.replace(mc, T=16)
-                Xd = torch.from_numpy(wl.moe_activations(md)).to(dev)
-                idd_np, gd_np = wl.moe_routing(md)
-                idd, gd = torch.from_numpy(idd_np).to(dev), torch.from_numpy(gd_np).to(dev)
-                Yd = torch.empty((md.T, md.H), dtype=torch.float16, device=dev)
-                wsd = api.new_workspace(layer.workspace_bytes(md.T, idd.shape[1]), dev)
-                msd, _ = time_steps(lambda i: layer.forward(Xd, idd, gd, out=Yd, workspace=wsd), 30, 10, 10)
-                msd /= 30
-                used = sorted(set(idd_np.reshape(-1).tolist()))
-                wb = sum(3 * md.H * md.F * 7 / 16 + 3 * 2 * ranks[e] * (md.H + md.F) for e in used)
-                extra["c3_shape_16_tokens"] = {"us_per_layer": round(msd * 1e3, 1), "experts_used": len(used),
-                                               "weight_MB": round(wb / 1e6, 1),
-                                               "GBps": round(wb / (msd * 1e-3) / 1e9, 1),
-                                               "frac_hbm_peak": round(wb / (msd * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-                del Xd, Yd, wsd
-            del layer, experts, Xm, Ym, wsm
-            torch.cuda.empty_cache()
-        # Context: what library kernels reach on this machine (not this repository's code): a plain
-        # device-to-device copy of 1 GiB (bytes read + written) and a dense fp16 GEMM of 8192^3.
-        def eager_ms(fn, n):
-            for _ in range(3):
-                fn()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(n):
-                fn()
-            e1.record()
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / n
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        ms = eager_ms(lambda: dst.copy_(src), 20)
-        copy_gbs = 2.0 * (1 << 30) / (ms * 1e-3) / 1e9
-        del src, dst
-        A = torch.randn((8192, 8192), device=dev, dtype=torch.float16)
-        B = torch.randn((8192, 8192), device=dev, dtype=torch.float16)
-        ms = eager_ms(lambda: torch.matmul(A, B), 10)
-        gemm_tf = 2.0 * 8192 ** 3 / (ms * 1e-3) / 1e12
-        del A, B
+            assert layer.routing_status() == 0, "the MoE layer reported an error"
+            return ms, ids_np
+
+        ms, ids_np = moe_leg(mc)
+        pairs = np.bincount(ids_np.reshape(-1), minlength=mc.E + mc.n_shared)
+        fl = sum(2.0 * int(pairs[e]) * (3 * mc.H * mc.F + 3 * ranks[e] * (mc.H + mc.F))
+                 for e in range(mc.E + mc.n_shared))
+        extra[mc.name] = {"us_per_layer": round(ms * 1e3, 1), "tokens": mc.T,
+                          "roofline": mfma_roofline(fl, ms, "w3lr_tiled_kernel<2,4,1> + <1,4,2> (+ route, order, combine)")}
+        if mc is wl.C3:
+            # the same layer at a decode-sized batch (16 tokens): every routed expert's weights are
+            # streamed for a handful of rows, so the figure of merit is HBM bytes per second
+            import dataclasses
+            md = dataclasses.replace(mc, T=16)
+            msd, idd_np = moe_leg(md)
+            used = sorted(set(idd_np.reshape(-1).tolist()))
+            wb = sum(3 * md.H * md.F * 7 / 16 + 3 * 2 * ranks[e] * (md.H + md.F) for e in used)
+            extra["c3_shape_16_tokens"] = {"us_per_layer": round(msd * 1e3, 1), "experts_used": len(used),
+                                           "roofline": hbm_roofline(wb, msd, "grouped W3 kernels of the MoE layer")}
+        del layer, experts
         torch.cuda.empty_cache()
-        # ... and a copy of exactly the bytes one c1 launch reads (26.9 MB, sources rotated like the
-        # weight copies, 24 copies per graph): what a kernel launch of that size costs on this machine
-        small = [torch.empty(wbytes, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(24)]
-        small_dst = torch.empty(wbytes, dtype=torch.uint8, device=dev)
-        ms, _ = time_steps(lambda i: small_dst.copy_(small[i % 24]), 240, 24, 48)
-        small_us = ms / 240 * 1e3
-        del small, small_dst
-        torch.cuda.empty_cache()
-        extra["achievable_context"] = {"torch_copy_1GiB_GBps": round(copy_gbs, 1),
-                                       "torch_fp16_gemm_8192_TFLOPs": round(gemm_tf, 1),
-                                       "torch_copy_of_c1_bytes_us": round(small_us, 2)}
+
+    if extra:
         result["extra"] = extra
 
     if not args.no_cpu_baseline:
@@ -310,10 +342,10 @@ def main():
             blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             blas_threads = os.cpu_count()
-        Wh = W.cpu().numpy()
+        Wh = W1.cpu().numpy()
         q, s, z = oracle.quantize_rtn(Wh)
-        U = pw.U.cpu().numpy()
-        V = pw.V.cpu().numpy()
+        U = pw1.U.cpu().numpy()
+        V = pw1.V.cpu().numpy()
         Xh = wl.gen_activations(16, case.K, case.seed)
         calls, t0 = 0, time.perf_counter()
         while True:

@@ -64,6 +64,7 @@ enum milo_status {
     MILO_ERR_WORKSPACE = 5,  /* workspace NULL or smaller than the *_workspace() size       */
     MILO_ERR_ROUTING = 6,    /* an expert id outside 0..E-1 was met (reported after the run)*/
     MILO_ERR_ALIGN = 7,      /* a pointer is not 16-byte aligned                            */
+    MILO_ERR_WAIT = 8,       /* a bounded wait inside a kernel gave up (see milo_workspace_status) */
     MILO_ERR_HIP = 100       /* a HIP runtime call failed (launch error, no device, ...)    */
 };
 
@@ -116,12 +117,27 @@ int milo_dequant_w3(const void* q3, int64_t N, int64_t K, milo_half* W_dq, void*
  * Prepare a freshly allocated workspace (for milo_w3lr_gemm or milo_moe_w3lr_forward): zero-fills
  * all `workspace_bytes` with a small fill kernel on `stream` (the kernels synchronise through
  * counters and flags in it that must start at zero).  Call it once after allocating the workspace
- * and again after a call on it returned an error or reported a wait that gave up; the kernels leave
- * their counters and flags cleared when they finish, so successive calls need no further
- * preparation and no memset (which makes them safe to capture in a HIP graph and replay).
+ * and again after a call on it returned an error or milo_workspace_status reported MILO_ERR_WAIT;
+ * the kernels leave their counters and flags cleared when they finish, so successive calls need no
+ * further preparation and no memset (which makes them safe to capture in a HIP graph and replay).
  * Errors: NULL, WORKSPACE (fewer than 256 bytes), ALIGN, HIP.
  */
 int milo_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Waits for `stream`, then reports whether a kernel that used this workspace (of milo_w3lr_gemm or
+ * of milo_moe_w3lr_forward) gave up a wait.  The kernels hand T = X V^T from the workgroups that form
+ * it to the ones that use it inside one launch; the consumers' wait is bounded (about a second), and
+ * one that runs out sets a word in the control block and goes on with whatever T holds, so the
+ * output of that call is not to be used.  This needs the whole launch to make progress together: the
+ * launches are sized for an otherwise idle device, and the producers have the lowest workgroup ids,
+ * which the hardware dispatches first; a device kept busy by other streams' kernels can break that.
+ * MILO_ERR_WAIT: discard the outputs written since the last MILO_OK and call milo_workspace_init
+ * before the next use (a GEMM workspace keeps the word until then; the MoE call clears its own at
+ * the start of every forward, so there the status refers to the last forward).
+ * Errors: NULL, ALIGN, WAIT, HIP.
+ */
+int milo_workspace_status(const void* workspace, void* stream);
 
 /*
  * One compensated W3A16 linear:  Y = X dequant(Q3)^T + (X V^T) U^T.
@@ -193,7 +209,8 @@ int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, int64_t F,
 
 /*
  * Waits for `stream` and returns MILO_ERR_ROUTING if the last milo_moe_w3lr_forward that used
- * this workspace met an expert id out of range, MILO_OK otherwise.
+ * this workspace met an expert id out of range, MILO_ERR_WAIT if a wait inside it gave up (see
+ * milo_workspace_status), MILO_OK otherwise.
  */
 int milo_moe_w3lr_routing_status(const void* workspace, void* stream);
 

@@ -5,4 +5,4 @@ binding over its C ABI and `workloads` draws the seeded synthetic inputs.
 Nothing is imported eagerly so that the input generators stay usable on a
 machine where the library has not been built.
 """
-__all__ = ["api", "workloads", "compress"]
+__all__ = ["api", "workloads"]

@@ -17,11 +17,11 @@ FULLWAITS_LIB_PATH = os.path.join(_HERE, "lib", "libmilo_fullwaits.so")
 
 STATUS_NAMES = {0: "MILO_OK", 1: "MILO_ERR_NULL", 2: "MILO_ERR_SHAPE", 3: "MILO_ERR_GROUP",
                 4: "MILO_ERR_RANK", 5: "MILO_ERR_WORKSPACE", 6: "MILO_ERR_ROUTING",
-                7: "MILO_ERR_ALIGN", 100: "MILO_ERR_HIP"}
+                7: "MILO_ERR_ALIGN", 8: "MILO_ERR_WAIT", 100: "MILO_ERR_HIP"}
 
 # every symbol include/milo.h declares
 EXPORTS = ("milo_status_string", "milo_version", "milo_w3_packed_bytes", "milo_pack_w3",
-           "milo_pack_w3_sym", "milo_workspace_init",
+           "milo_pack_w3_sym", "milo_workspace_init", "milo_workspace_status",
            "milo_unpack_w3", "milo_dequant_w3", "milo_w3lr_gemm_workspace", "milo_w3lr_gemm",
            "milo_moe_w3lr_check_experts", "milo_moe_w3lr_workspace", "milo_moe_w3lr_forward",
            "milo_moe_w3lr_routing_status")
@@ -68,6 +68,8 @@ def bind(path):
     L.milo_dequant_w3.argtypes = [vp, i64, i64, vp, vp]
     L.milo_workspace_init.restype = ci
     L.milo_workspace_init.argtypes = [vp, sz, vp]
+    L.milo_workspace_status.restype = ci
+    L.milo_workspace_status.argtypes = [vp, vp]
     L.milo_w3lr_gemm_workspace.restype = sz
     L.milo_w3lr_gemm_workspace.argtypes = [i64, i64, i64, ci]
     L.milo_w3lr_gemm.restype = ci
@@ -178,6 +180,11 @@ def new_workspace(nbytes, device="cuda"):
     ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
     _check(lib().milo_workspace_init(_ptr(ws), ws.numel(), _stream()), "milo_workspace_init")
     return ws
+
+
+def workspace_status(workspace):
+    """milo_workspace_status: 0, or MILO_ERR_WAIT (8) if a kernel's bounded wait gave up."""
+    return int(lib().milo_workspace_status(_ptr(workspace), _stream()))
 
 
 def gemm_workspace_bytes(M, N, K, r):

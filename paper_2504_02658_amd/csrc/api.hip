@@ -16,12 +16,13 @@ extern "C" const char* milo_status_string(int status) {
         case MILO_ERR_WORKSPACE: return "workspace missing or too small";
         case MILO_ERR_ROUTING: return "expert id out of range";
         case MILO_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+        case MILO_ERR_WAIT: return "a bounded wait inside a kernel gave up; re-initialise the workspace";
         case MILO_ERR_HIP: return "HIP runtime error";
         default: return "unknown status";
     }
 }
 
-extern "C" int milo_version(void) { return 100; }
+extern "C" int milo_version(void) { return 200; }
 
 namespace milo {
 __global__ void clear_kernel(u32x4* p, size_t n16) {
@@ -48,10 +49,13 @@ static int gemm_mb(int64_t M) {
     // tile height / 32; measured on N = 14336, K = 4096: up to 64 rows the shallow tile wins, up to
     // a few hundred rows two 64-row tiles beat one tall one
     int mb = M <= 64 ? 1 : (M <= 384 ? 2 : 4);
-    if (const char* e = getenv("MILO_GEMM_MB")) {                       // tuning override
-        const int v = atoi(e);
-        if (v == 1 || v == 2 || v == 4) mb = v;
-    }
+    // tuning override, read once per process so that the workspace query and the call agree
+    static const int mb_override = [] {
+        const char* e = getenv("MILO_GEMM_MB");
+        const int v = e ? atoi(e) : 0;
+        return (v == 1 || v == 2 || v == 4) ? v : 0;
+    }();
+    if (mb_override) mb = mb_override;
     return mb;
 }
 static int gemm_splits(int64_t M, int64_t N, int64_t K, int r) {
@@ -168,4 +172,15 @@ extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t 
     splitk_sum_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(partial, splits, n4, M * N,
                                                                         reinterpret_cast<f16*>(Y));
     return launch_status();
+}
+
+// Word 3 of every workspace's control block is the "a wait gave up" word of the kernels that use it.
+extern "C" int milo_workspace_status(const void* workspace, void* stream) {
+    if (!workspace) return MILO_ERR_NULL;
+    if (!aligned16(workspace)) return MILO_ERR_ALIGN;
+    uint32_t words[4] = {0u, 0u, 0u, 0u};
+    if (hipMemcpyAsync(words, workspace, sizeof(words), hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess)
+        return MILO_ERR_HIP;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return MILO_ERR_HIP;
+    return words[3] != 0u ? MILO_ERR_WAIT : MILO_OK;
 }

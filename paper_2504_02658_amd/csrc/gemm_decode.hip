@@ -559,10 +559,12 @@ int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream) {
     const int workers = r > 0 ? nt : 0;
     if (cap <= workers || (size_t)cap * 4 > kDecDoneBytes) return MILO_ERR_HIP;
     int R = decode_rows_per_workgroup(a.N, a.K, cap - workers);
-    if (const char* e = getenv("MILO_DEC_R")) {                 // tuning override
-        const int v = atoi(e);
-        if (v == 1 || v == 2 || v == 4) R = v;
-    }
+    static const int r_override = [] {                          // tuning override, read once per process
+        const char* e = getenv("MILO_DEC_R");
+        const int v = e ? atoi(e) : 0;
+        return (v == 1 || v == 2 || v == 4) ? v : 0;
+    }();
+    if (r_override) R = r_override;
     const int rows = 16 * R;
     const int64_t blocks = (a.N + rows - 1) / rows;
     const int grid = (int)(blocks < cap - workers ? blocks : cap - workers) + workers;

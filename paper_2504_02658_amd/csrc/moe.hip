@@ -27,7 +27,7 @@ struct RouteArgs {
     int32_t* sorted;        // [P] pair indices grouped by expert, original order inside a group
     int32_t* sorted_token;  // [P] token of each sorted pair (pair / topk)
     TileDesc* tiles;
-    int32_t* header;        // [0] routing status, [1] number of tiles, [2] wait status
+    int32_t* header;        // [0] routing status, [1] number of tiles, [3] wait status (a wait gave up)
     uint32_t* flags;        // per-tile control words of the GEMM kernels, cleared here
     int32_t n_flags;
     int32_t max_tiles;      // slots of the tile list: ceil(P / bm) + E
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(const RouteArgs a)
         if (tid == 0) {
             a.header[0] = s_bad ? MILO_ERR_ROUTING : MILO_OK;
             a.header[1] = a.max_tiles;
-            a.header[2] = 0;
+            a.header[3] = 0;
         }
     }
 }
@@ -296,10 +296,13 @@ static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_m
     // taller tile costs more activation copies and a shallower pipeline; measured on the Mixtral
     // shape the crossovers lie near 26 and 56 rows per expert.
     L->bm = avg >= 56 ? 128 : (avg >= 26 ? 64 : 32);
-    if (const char* e = getenv("MILO_MOE_BM")) {                       // tuning override
-        const int v = atoi(e);
-        if (v == 32 || v == 64 || v == 128) L->bm = v;
-    }
+    // tuning override, read once per process so that the workspace query and the call agree
+    static const int bm_override = [] {
+        const char* e = getenv("MILO_MOE_BM");
+        const int v = e ? atoi(e) : 0;
+        return (v == 32 || v == 64 || v == 128) ? v : 0;
+    }();
+    if (bm_override) L->bm = bm_override;
     const int64_t max_tiles32 = (P + 31) / 32 + E;      // bound for the smallest tile height
     const int64_t max_tiles = (P + L->bm - 1) / L->bm + E;
     if (max_tiles > 65535) return false;
@@ -427,7 +430,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         ga.Tp[0] = Tp1; ga.Tp[1] = Tp3; ga.tp_bytes = (uint64_t)L.parts_up * P * L.ldt * 4;
         ga.t_part_stride = (int64_t)P * L.ldt; ga.t_parts = L.parts_up; ga.v_tiles = L.parts_up; ga.ksplit = 1;
         ga.out_split_stride = 0; ga.flags = flags; ga.weights_once = once;
-        ga.flags_status = reinterpret_cast<uint32_t*>(header + 2);
+        ga.flags_status = reinterpret_cast<uint32_t*>(header + 3);
         ga.out = Hbuf; ga.ldo = F; ga.out_rows = nullptr; ga.out_scale = nullptr;
         st = launch_tiled(ga, 2, mb, EPI_SWIGLU, L.max_tiles, stream);
         if (st != MILO_OK) return st;
@@ -443,7 +446,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         da.Tp[0] = Tp1; da.Tp[1] = Tp1; da.tp_bytes = (uint64_t)L.parts_down * P * L.ldt * 4;
         da.t_part_stride = (int64_t)P * L.ldt; da.t_parts = L.parts_down; da.v_tiles = L.parts_down;
         da.ksplit = L.splits_down; da.out_split_stride = (int64_t)P * H; da.flags = flags; da.weights_once = once;
-        da.flags_status = reinterpret_cast<uint32_t*>(header + 2);
+        da.flags_status = reinterpret_cast<uint32_t*>(header + 3);
         da.out = O; da.ldo = H; da.out_rows = sorted; da.out_scale = topk_weights;
         st = launch_tiled(da, 1, mb, EPI_SCALE_SCATTER, L.max_tiles, stream);
         if (st != MILO_OK) return st;
@@ -474,6 +477,6 @@ extern "C" int milo_moe_w3lr_routing_status(const void* workspace, void* stream)
                        (hipStream_t)stream) != hipSuccess)
         return MILO_ERR_HIP;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return MILO_ERR_HIP;
-    if (header[2] != 0) return MILO_ERR_HIP;        // a wait inside a kernel gave up
+    if (header[3] != 0) return MILO_ERR_WAIT;       // a wait inside a kernel gave up
     return header[0] == MILO_OK ? MILO_OK : MILO_ERR_ROUTING;
 }

@@ -84,6 +84,9 @@ def test_host_side_argument_errors(L):
     assert f(X=null) == 1 and f(T=0) == 2 and f(topk=0) == 2
     assert f(ws=null) == 5 and f(wsb=1024) == 5
     assert f(r=1000) == 4
+    # status query
+    assert L.milo_workspace_status(null, st) == 1
+    assert L.milo_workspace_status(odd, st) == 7
 
 
 def test_bench_refuses_more_than_one_gpu():

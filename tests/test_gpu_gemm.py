@@ -249,3 +249,28 @@ def test_graph_replay_matches_eager_and_needs_no_reset():
         again = api.w3lr_gemm(cases[0][0], cases[0][1], workspace=cases[0][2])
         torch.cuda.synchronize()
         assert torch.equal(again, eager[0])
+
+
+def test_workspace_status_reports_a_wait_that_gave_up():
+    # The give-up word is forced from the host (no kernel spins): status turns to MILO_ERR_WAIT and
+    # stays there until the workspace is prepared again; a clean run reports MILO_OK.
+    import torch
+    from paper_2504_02658_amd import api
+    for M in (16, 96):                                  # decode and tiled workspaces
+        case = wl.LinearCase("t", M=M, N=512, K=1024, r=16, seed=31)
+        X, W = wl.linear_inputs(case)
+        ow = oracle_weight(W, 16)
+        pw = gpu_weight(W, ow, check_pack=False)
+        ws = api.new_workspace(api.gemm_workspace_bytes(M, 512, 1024, 16))
+        Xd = torch.from_numpy(X).cuda()
+        Y = api.w3lr_gemm(Xd, pw, workspace=ws)
+        assert api.workspace_status(ws) == 0
+        assert_close(Y.cpu().numpy(), oracle.w3lr_linear(X, **ow), "before")
+        ws.view(torch.int32)[3] = 1                     # what a kernel writes when its wait runs out
+        assert api.workspace_status(ws) == 8
+        api.w3lr_gemm(Xd, pw, workspace=ws)
+        assert api.workspace_status(ws) == 8            # sticky for a GEMM workspace
+        api.lib().milo_workspace_init(ws.data_ptr(), ws.numel(), None)
+        Y = api.w3lr_gemm(Xd, pw, workspace=ws)
+        assert api.workspace_status(ws) == 0
+        assert_close(Y.cpu().numpy(), oracle.w3lr_linear(X, **ow), "after re-init")
