@@ -159,6 +159,26 @@ int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t K,
                    const void* q3, const milo_half* U, const milo_half* V, int r,
                    milo_half* Y, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * milo_w3lr_gemm for callers that cannot allocate and cannot bring a workspace: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * result and errors as milo_w3lr_gemm, bit for bit, without `workspace`: the scratch memory is a
+ * fixed array of MILO_STATIC_SCRATCH_BYTES inside the library's device image (every GPU the library
+ * runs on holds its copy until the process ends).  The call allocates nothing; a problem whose
+ * milo_w3lr_gemm_workspace(M, N, K, r) exceeds MILO_STATIC_SCRATCH_BYTES is refused with
+ * MILO_ERR_WORKSPACE (all decode shapes fit; large M with a K split may not).  The control words
+ * of the array are cleared by a small fill kernel at the start of every call (no memset, so the call
+ * can be captured), then the kernels of milo_w3lr_gemm run on it.  All calls on one GPU share that
+ * GPU's array: calls that overlap in time on one GPU (different streams) race; order them.  The
+ * array's device address is looked up on the first call on a device (make that call outside a
+ * graph capture).  milo_workspace_status does not apply; a wait that gave up inside this call is
+ * not reported.
+ */
+#define MILO_STATIC_SCRATCH_BYTES (4u << 20)
+int milo_w3lr_gemm_static(const milo_half* X, int64_t M, int64_t N, int64_t K,
+                          const void* q3, const milo_half* U, const milo_half* V, int r,
+                          milo_half* Y, void* stream);
+
 /* One packed weight with its compensator (all device pointers). */
 typedef struct milo_w3lr_weight {
     const void* q3;

@@ -23,6 +23,7 @@ STATUS_NAMES = {0: "MILO_OK", 1: "MILO_ERR_NULL", 2: "MILO_ERR_SHAPE", 3: "MILO_
 EXPORTS = ("milo_status_string", "milo_version", "milo_w3_packed_bytes", "milo_pack_w3",
            "milo_pack_w3_sym", "milo_workspace_init", "milo_workspace_status",
            "milo_unpack_w3", "milo_dequant_w3", "milo_w3lr_gemm_workspace", "milo_w3lr_gemm",
+           "milo_w3lr_gemm_static",
            "milo_moe_w3lr_check_experts", "milo_moe_w3lr_workspace", "milo_moe_w3lr_forward",
            "milo_moe_w3lr_routing_status")
 
@@ -74,6 +75,8 @@ def bind(path):
     L.milo_w3lr_gemm_workspace.argtypes = [i64, i64, i64, ci]
     L.milo_w3lr_gemm.restype = ci
     L.milo_w3lr_gemm.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, vp, vp, sz, vp]
+    L.milo_w3lr_gemm_static.restype = ci
+    L.milo_w3lr_gemm_static.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, vp, vp]
     L.milo_moe_w3lr_check_experts.restype = ci
     L.milo_moe_w3lr_check_experts.argtypes = [ctypes.POINTER(Expert), ci, i64, i64,
                                               ctypes.POINTER(ci)]
@@ -204,6 +207,19 @@ def w3lr_gemm(X, pw, out=None, workspace=None):
         workspace = new_workspace(need, X.device)
     _check(lib().milo_w3lr_gemm(_ptr(X), M, pw.N, K, _ptr(pw.q3), _ptr(pw.U), _ptr(pw.V), pw.r, _ptr(out), _ptr(workspace),
                                 workspace.numel(), _stream()), "milo_w3lr_gemm")
+    return out
+
+
+def w3lr_gemm_static(X, pw, out=None):
+    """milo_w3lr_gemm_static: the same linear on the library's own scratch array (no workspace)."""
+    X = _dev(X, torch.float16, "X")
+    M, K = X.shape
+    if K != pw.K:
+        raise ValueError("X and weight disagree on K")
+    if out is None:
+        out = torch.empty((M, pw.N), dtype=torch.float16, device=X.device)
+    _check(lib().milo_w3lr_gemm_static(_ptr(X), M, pw.N, K, _ptr(pw.q3), _ptr(pw.U), _ptr(pw.V), pw.r, _ptr(out),
+                                       _stream()), "milo_w3lr_gemm_static")
     return out
 
 
