@@ -160,6 +160,32 @@ int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t K,
                    milo_half* Y, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same with weight flags (see above): `U` and `V` are fp16 arrays, or with MILO_LR_INT3 the two
+ * blobs of milo_pack_lr3.  milo_w3lr_gemm is this call with flags = 0.
+ * Errors: as milo_w3lr_gemm; RANK also for MILO_LR_INT3 with r > MILO_LR3_MAX_RANK, SHAPE for
+ * MILO_LR_INT3 with N % 64 != 0 or unknown flag bits.
+ */
+int milo_w3lr_gemm_flags(const milo_half* X, int64_t M, int64_t N, int64_t K,
+                         const void* q3, const void* U, const void* V, int r, unsigned flags,
+                         milo_half* Y, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * INT3 compensator (Section 3.2.3, Eq. symm_int3; Algorithm 1's output step "Quantize U, V").
+ * Both factors are quantized with the symmetric INT3 quantizer of milo_pack_w3_sym in groups of 64
+ * along their long dimension: U [N x r] along N (64 consecutive output features of one rank share a
+ * step), V [r x K] along K.  The blobs have the Q3 layout described at the top of this file, of the
+ * matrices U^T [rp x N] and V [rp x K] with rp = r rounded up to a multiple of 16 (the added rows are
+ * zero): 3.5 bits per element of the compensator instead of 16.  The kernels dequantize them like
+ * weights (one fp16 rounding per element) while they form X V^T and add T U^T.
+ *   U [N x r], V [r x K]  fp32 row-major (device, read only)
+ *   u3, v3                out, *u_bytes and *v_bytes of milo_lr3_packed_bytes(N, K, r, ..)
+ * Errors: NULL, SHAPE (also N % 64 != 0), RANK (r < 1 or r > MILO_LR3_MAX_RANK), ALIGN, HIP.
+ */
+int milo_lr3_packed_bytes(int64_t N, int64_t K, int r, size_t* u_bytes, size_t* v_bytes);
+int milo_pack_lr3(const float* U, const float* V, int64_t N, int64_t K, int r,
+                  void* u3, void* v3, void* stream);
+
+/*
  * milo_w3lr_gemm for callers that cannot allocate and cannot bring a workspace: code that runs
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
  * result and errors as milo_w3lr_gemm, bit for bit, without `workspace`: the scratch memory is a
@@ -179,13 +205,27 @@ int milo_w3lr_gemm_static(const milo_half* X, int64_t M, int64_t N, int64_t K,
                           const void* q3, const milo_half* U, const milo_half* V, int r,
                           milo_half* Y, void* stream);
 
+/*
+ * Weight flags (the `flags` argument of milo_w3lr_gemm_flags and the `flags` field of milo_w3lr_weight).
+ *   MILO_W3_SYMMETRIC  the Q3 blob was written by milo_pack_w3_sym, so every zero-point is 4: the
+ *                      kernels may use the conversion without zero-point arithmetic (Section 3.3,
+ *                      the symmetric kernel).  The result is the same bit for bit with or without
+ *                      the flag; setting it on a blob that is not symmetric gives wrong results.
+ *   MILO_LR_INT3       U and V are not fp16 arrays but the INT3 blobs written by milo_pack_lr3
+ *                      (Section 3.2.3, "Quantized low-rank mixture compensators"; the last step of
+ *                      Algorithm 1).  Needs r <= MILO_LR3_MAX_RANK and N % 64 == 0.
+ */
+#define MILO_W3_SYMMETRIC 1u
+#define MILO_LR_INT3 2u
+#define MILO_LR3_MAX_RANK 128
+
 /* One packed weight with its compensator (all device pointers). */
 typedef struct milo_w3lr_weight {
     const void* q3;
-    const milo_half* U;      /* [N x r] or NULL when r == 0 */
-    const milo_half* V;      /* [r x K] or NULL when r == 0 */
+    const void* U;           /* fp16 [N x r], or the U blob of milo_pack_lr3; NULL when r == 0 */
+    const void* V;           /* fp16 [r x K], or the V blob of milo_pack_lr3; NULL when r == 0 */
     int32_t r;
-    int32_t reserved;        /* must be 0 */
+    uint32_t flags;          /* MILO_W3_SYMMETRIC | MILO_LR_INT3, else 0 */
 } milo_w3lr_weight;
 
 /* A SwiGLU expert: w1, w3 are [F x H] (gate, up), w2 is [H x F] (down). */

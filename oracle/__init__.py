@@ -18,5 +18,6 @@ from .quantize import quantize_rtn, quantize_sym, dequantize   # noqa: F401
 from .packing import (pack_w3, unpack_w3, unit_index, to_unit_order,  # noqa: F401
                       from_unit_order, packed_bytes, code_bytes)
 from .linear import w3lr_linear, linear_from_dense        # noqa: F401
-from .compensator import svd_compensator, randomized_svd_compensator  # noqa: F401
+from .compensator import (svd_compensator, randomized_svd_compensator,  # noqa: F401
+                          quantize_compensator, dequantize_compensator)
 from .moe import moe_forward, silu                        # noqa: F401

@@ -43,3 +43,29 @@ def randomized_svd_compensator(E, r, seed, oversample=10, power_iters=2):
     B = Q.T @ E
     Ub, S, Vh = np.linalg.svd(B, full_matrices=False)
     return _split(Q @ Ub, S, Vh, r)
+
+
+def quantize_compensator(U, V):
+    """INT3 compensator (Section 3.2.3, Eq. symm_int3; the last step of Algorithm 1): both factors go
+    through the symmetric INT3 quantizer in groups of 64 along their long dimension, U [N x r] along N
+    and V [r x K] along K.  (The paper does not print the group axis; its memory table grows in exact
+    proportion to the rank, which a group along the rank would not, and 64 is the group size of all its
+    kernels.)  Returned in the stored form: (codes, scales, zeros) of U^T [rp x N] and of V [rp x K],
+    rp = r rounded up to a multiple of 16 with zero rows added.
+    """
+    from .quantize import quantize_sym
+    U = np.asarray(U, dtype=np.float32)
+    V = np.asarray(V, dtype=np.float32)
+    N, r = U.shape
+    rp = (r + 15) // 16 * 16
+    Ut = np.zeros((rp, N), np.float32)
+    Ut[:r] = U.T
+    Vp = np.zeros((rp, V.shape[1]), np.float32)
+    Vp[:r] = V
+    return quantize_sym(Ut), quantize_sym(Vp)
+
+
+def dequantize_compensator(uq, vq, r):
+    """fp64 U [N x r] and V [r x K] of a quantized compensator."""
+    from .quantize import dequantize
+    return dequantize(*uq)[:r].T.copy(), dequantize(*vq)[:r].copy()

@@ -19,11 +19,14 @@ STATUS_NAMES = {0: "MILO_OK", 1: "MILO_ERR_NULL", 2: "MILO_ERR_SHAPE", 3: "MILO_
                 4: "MILO_ERR_RANK", 5: "MILO_ERR_WORKSPACE", 6: "MILO_ERR_ROUTING",
                 7: "MILO_ERR_ALIGN", 8: "MILO_ERR_WAIT", 100: "MILO_ERR_HIP"}
 
+W3_SYMMETRIC = 1          # weight flags of include/milo.h
+LR_INT3 = 2
+
 # every symbol include/milo.h declares
 EXPORTS = ("milo_status_string", "milo_version", "milo_w3_packed_bytes", "milo_pack_w3",
            "milo_pack_w3_sym", "milo_workspace_init", "milo_workspace_status",
            "milo_unpack_w3", "milo_dequant_w3", "milo_w3lr_gemm_workspace", "milo_w3lr_gemm",
-           "milo_w3lr_gemm_static",
+           "milo_w3lr_gemm_static", "milo_w3lr_gemm_flags", "milo_lr3_packed_bytes", "milo_pack_lr3",
            "milo_moe_w3lr_check_experts", "milo_moe_w3lr_workspace", "milo_moe_w3lr_forward",
            "milo_moe_w3lr_routing_status")
 
@@ -37,7 +40,7 @@ class MiloError(RuntimeError):
 
 class Weight(ctypes.Structure):
     _fields_ = [("q3", ctypes.c_void_p), ("U", ctypes.c_void_p), ("V", ctypes.c_void_p), ("r", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("flags", ctypes.c_uint32)]
 
 
 class Expert(ctypes.Structure):
@@ -75,6 +78,12 @@ def bind(path):
     L.milo_w3lr_gemm_workspace.argtypes = [i64, i64, i64, ci]
     L.milo_w3lr_gemm.restype = ci
     L.milo_w3lr_gemm.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, vp, vp, sz, vp]
+    L.milo_w3lr_gemm_flags.restype = ci
+    L.milo_w3lr_gemm_flags.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, ctypes.c_uint, vp, vp, sz, vp]
+    L.milo_lr3_packed_bytes.restype = ci
+    L.milo_lr3_packed_bytes.argtypes = [i64, i64, ci, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    L.milo_pack_lr3.restype = ci
+    L.milo_pack_lr3.argtypes = [vp, vp, i64, i64, ci, vp, vp, vp]
     L.milo_w3lr_gemm_static.restype = ci
     L.milo_w3lr_gemm_static.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, vp, vp]
     L.milo_moe_w3lr_check_experts.restype = ci
@@ -116,16 +125,21 @@ def _dev(t, dtype, name):
 
 
 class PackedWeight:
-    """Device buffers of one packed [N x K] weight and its optional compensator."""
+    """Device buffers of one packed [N x K] weight and its optional compensator (fp16 U [N, r] and
+    V [r, K], or with the LR_INT3 flag the two blobs of pack_lr3)."""
 
-    def __init__(self, N, K, q3, U=None, V=None):
+    def __init__(self, N, K, q3, U=None, V=None, flags=0, r=None):
         self.N, self.K = int(N), int(K)
         self.q3 = q3                    # uint8 blob: codes, scales and zero-points
         self.U, self.V = U, V
+        self.flags = int(flags)
+        self._r = r
 
     @property
     def r(self):
-        return 0 if self.U is None else int(self.U.shape[1])
+        if self.U is None:
+            return 0
+        return int(self._r) if self._r is not None else int(self.U.shape[1])
 
     def with_compensator(self, U, V):
         U = _dev(U, torch.float16, "U")
@@ -133,17 +147,22 @@ class PackedWeight:
         assert U.shape[0] == self.N and V.shape[1] == self.K and U.shape[1] == V.shape[0]
         if U.shape[1] == 0:
             U = V = None
-        return PackedWeight(self.N, self.K, self.q3, U, V)
+        return PackedWeight(self.N, self.K, self.q3, U, V, self.flags & ~LR_INT3)
+
+    def with_int3_compensator(self, u3, v3, r):
+        """u3, v3: the blobs written by pack_lr3 for this weight's shape and rank r."""
+        return PackedWeight(self.N, self.K, self.q3, _dev(u3, torch.uint8, "u3"), _dev(v3, torch.uint8, "v3"),
+                            self.flags | LR_INT3, r=int(r))
 
     def weight_bytes(self):
         n = self.q3.numel()
         if self.U is not None:
-            n += 2 * self.U.numel() + 2 * self.V.numel()
+            n += self.U.numel() * self.U.element_size() + self.V.numel() * self.V.element_size()
         return n
 
     def c_struct(self):
         return Weight(self.q3.data_ptr(), 0 if self.U is None else self.U.data_ptr(),
-                      0 if self.V is None else self.V.data_ptr(), self.r, 0)
+                      0 if self.V is None else self.V.data_ptr(), self.r, self.flags)
 
 
 def packed_bytes(N, K):
@@ -158,7 +177,22 @@ def pack_w3(W, group_size=64, symmetric=False):
     q3 = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=W.device)
     fn, name = (lib().milo_pack_w3_sym, "milo_pack_w3_sym") if symmetric else (lib().milo_pack_w3, "milo_pack_w3")
     _check(fn(_ptr(W), N, K, group_size, _ptr(q3), _stream()), name)
-    return PackedWeight(N, K, q3[:nbytes])
+    return PackedWeight(N, K, q3[:nbytes], flags=W3_SYMMETRIC if symmetric else 0)
+
+
+def pack_lr3(U, V):
+    """milo_pack_lr3: fp32 CUDA U [N, r], V [r, K] -> (u3, v3) uint8 blobs of the INT3 compensator."""
+    U = _dev(U, torch.float32, "U")
+    V = _dev(V, torch.float32, "V")
+    N, r = U.shape
+    K = V.shape[1]
+    assert V.shape[0] == r
+    ub, vb = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(lib().milo_lr3_packed_bytes(N, K, r, ctypes.byref(ub), ctypes.byref(vb)), "milo_lr3_packed_bytes")
+    u3 = torch.empty(ub.value, dtype=torch.uint8, device=U.device)
+    v3 = torch.empty(vb.value, dtype=torch.uint8, device=U.device)
+    _check(lib().milo_pack_lr3(_ptr(U), _ptr(V), N, K, r, _ptr(u3), _ptr(v3), _stream()), "milo_pack_lr3")
+    return u3, v3
 
 
 def unpack_w3(pw):
@@ -205,8 +239,13 @@ def w3lr_gemm(X, pw, out=None, workspace=None):
     need = gemm_workspace_bytes(M, pw.N, K, pw.r)
     if workspace is None:
         workspace = new_workspace(need, X.device)
-    _check(lib().milo_w3lr_gemm(_ptr(X), M, pw.N, K, _ptr(pw.q3), _ptr(pw.U), _ptr(pw.V), pw.r, _ptr(out), _ptr(workspace),
-                                workspace.numel(), _stream()), "milo_w3lr_gemm")
+    if pw.flags == 0:
+        _check(lib().milo_w3lr_gemm(_ptr(X), M, pw.N, K, _ptr(pw.q3), _ptr(pw.U), _ptr(pw.V), pw.r, _ptr(out),
+                                    _ptr(workspace), workspace.numel(), _stream()), "milo_w3lr_gemm")
+    else:
+        _check(lib().milo_w3lr_gemm_flags(_ptr(X), M, pw.N, K, _ptr(pw.q3), _ptr(pw.U), _ptr(pw.V), pw.r, pw.flags,
+                                          _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
+               "milo_w3lr_gemm_flags")
     return out
 
 

@@ -99,13 +99,24 @@ extern "C" size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int 
 }
 
 extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t K, const void* q3,
-                              const milo_half* U,
-                              const milo_half* V, int r, milo_half* Y, void* workspace,
+                              const milo_half* U, const milo_half* V, int r, milo_half* Y, void* workspace,
                               size_t workspace_bytes, void* stream_) {
+    return milo_w3lr_gemm_flags(X, M, N, K, q3, U, V, r, 0u, Y, workspace, workspace_bytes, stream_);
+}
+
+extern "C" int milo_w3lr_gemm_flags(const milo_half* X, int64_t M, int64_t N, int64_t K, const void* q3,
+                                    const void* U, const void* V, int r, unsigned flags, milo_half* Y,
+                                    void* workspace, size_t workspace_bytes, void* stream_) {
     if (!X || !q3 || !Y) return MILO_ERR_NULL;
     if (!gemm_shape_ok(M, N, K)) return MILO_ERR_SHAPE;
+    if (flags & ~(MILO_W3_SYMMETRIC | MILO_LR_INT3)) return MILO_ERR_SHAPE;
     if (r < 0 || r > N || r > K) return MILO_ERR_RANK;
     if (r > 0 && (!U || !V)) return MILO_ERR_RANK;
+    if (r == 0) flags &= ~MILO_LR_INT3;
+    if (flags & MILO_LR_INT3) {
+        if (r > MILO_LR3_MAX_RANK) return MILO_ERR_RANK;
+        if ((N % kGroup) != 0) return MILO_ERR_SHAPE;
+    }
     if (!workspace || workspace_bytes < milo_w3lr_gemm_workspace(M, N, K, r))
         return MILO_ERR_WORKSPACE;
     if (!aligned16(X) || !aligned16(q3) ||
@@ -118,7 +129,7 @@ extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t 
     w.U = reinterpret_cast<const f16*>(U);
     w.V = reinterpret_cast<const f16*>(V);
     w.r = r;
-    w.reserved = 0;
+    w.flags = flags;
     const bool decode = M <= 16;
     if (decode) {
         // 32-bit buffer offsets in the decode kernel
@@ -132,7 +143,7 @@ extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t 
     }
     char* ws = reinterpret_cast<char*>(workspace);
     uint32_t* ctrl = reinterpret_cast<uint32_t*>(ws);
-    uint32_t* flags = reinterpret_cast<uint32_t*>(ws + 256);
+    uint32_t* tile_flags = reinterpret_cast<uint32_t*>(ws + 256);
     f16* T = reinterpret_cast<f16*>(ws + 256 + align_up((size_t)((M + 31) / 32) * 16, 256));
     const int64_t ldt = rank_pad(r);
 
@@ -161,7 +172,8 @@ extern "C" int milo_w3lr_gemm(const milo_half* X, int64_t M, int64_t N, int64_t 
     ga.T[0] = ga.T[1] = T; ga.ldt = ldt; ga.t_bytes = (uint64_t)M * ldt * 2;
     ga.Tp[0] = ga.Tp[1] = Tp; ga.tp_bytes = (uint64_t)parts * M * ldt * 4;
     ga.t_part_stride = M * ldt; ga.t_parts = parts; ga.v_tiles = parts; ga.ksplit = splits;
-    ga.flags = flags; ga.flags_status = ctrl + 3; ga.weights_once = m_tiles == 1;
+    ga.flags = tile_flags; ga.flags_status = ctrl + 3; ga.weights_once = m_tiles == 1;
+    ga.lr3_rank = (w.flags & MILO_LR_INT3) ? r : 0;
     ga.out = splits > 1 ? static_cast<void*>(partial) : static_cast<void*>(Y);
     ga.ldo = N; ga.out_split_stride = M * N; ga.out_rows = nullptr; ga.out_scale = nullptr;
     int st = launch_tiled(ga, 1, mb, EPI_STORE, (int)m_tiles, stream);

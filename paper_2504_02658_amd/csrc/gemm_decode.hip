@@ -117,7 +117,10 @@ __device__ __forceinline__ void read_bfrags(const unsigned char* slot, int j16, 
 // path (coalesced 1-KB buffer-to-LDS copies into a wave-private slot, xor-swizzled), and all
 // copies of an item are requested at once.  The upper half of the workgroup's waves has no work
 // here and only takes part in the barriers.
-template <int XC>
+// Q: V is the INT3 blob of milo_pack_lr3, [16 rblocks x K] in the layout of a weight: a lane loads
+// the unit of rank 16 jb + lane % 16, group 4c + lane / 16, exactly as a streaming wave does for a
+// row block, and converts it with the zero-point-free conversion (the quantizer is symmetric).
+template <int XC, bool Q>
 __device__ __forceinline__ void decode_t_worker(const DecodeArgs& a, unsigned char* smem) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const bool active = wave < kDecTWaves;
@@ -136,16 +139,26 @@ __device__ __forceinline__ void decode_t_worker(const DecodeArgs& a, unsigned ch
         const int jb = item / a.kh, h = item - jb * a.kh;
         f32x4 tacc = {0.0f, 0.0f, 0.0f, 0.0f};
         if (active) {
-            const uint32_t kc = (uint32_t)(h * kDecTWaves + wave) * 256u;
+            const uint32_t c = (uint32_t)(h * kDecTWaves + wave), kc = c * 256u;
             xc.issue<XC>(xb, xs, kc, K, true);
-            // rows >= r lie past the end of V and read as zero
-            xc.issue<8>(vb, vs, kc, K, true, (uint32_t)(16 * jb) * K * 2u);
-            wait_vmem();
-            f16x8 bfrag[8], afrag[8];
-            read_bfrags(xs, j16, q, bfrag);
-            read_bfrags(vs, j16, q, afrag);
+            if (Q) {
+                const uint32_t G = K / kGroup;
+                const W3Buf vq = make_w3buf(a.w.V, a.ldt, a.K);
+                const RawUnit u = load_unit_buf(vq, 4u * c + q < G ? ((uint32_t)jb * G + 4u * c) * 16u + lane : (1u << 27));
+                wait_vmem();
+                f16x8 bfrag[8];
+                read_bfrags(xs, j16, q, bfrag);
+                dequant_unit_steps<true>(u, [&](int t, f16x8 frag) { tacc = mfma16(frag, bfrag[t], tacc); });
+            } else {
+                // rows >= r lie past the end of V and read as zero
+                xc.issue<8>(vb, vs, kc, K, true, (uint32_t)(16 * jb) * K * 2u);
+                wait_vmem();
+                f16x8 bfrag[8], afrag[8];
+                read_bfrags(xs, j16, q, bfrag);
+                read_bfrags(vs, j16, q, afrag);
 #pragma unroll
-            for (int t = 0; t < 8; ++t) tacc = mfma16(afrag[t], bfrag[t], tacc);
+                for (int t = 0; t < 8; ++t) tacc = mfma16(afrag[t], bfrag[t], tacc);
+            }
         }
         __syncthreads();                                    // every wave has read its slots
         if (active) red[wave * 64 + lane] = tacc;
@@ -192,8 +205,8 @@ __device__ __forceinline__ void decode_wait_t(const DecodeArgs& a) {
 constexpr int kDecKS = 4;                                       // k-steps of 32 ranks, LR == 1
 constexpr int kDecULds = kDecLdsBytes;                          // U fragments [R][kDecKS][64] x 16 B
 constexpr int kDecTLds = kDecULds + 4 * kDecKS * 1024;          // T fragments [kDecTFrags][64] x 16 B
-constexpr int kDecTFrags = 8;                                   // (K parts) x (k-steps used) at most, LR == 1
-constexpr int kDecLdsTotal = kDecTLds + kDecTFrags * 1024;      // 152 KB
+constexpr int kDecTFrags = 16;                                  // (K parts) x (k-steps used) at most, LR == 1
+constexpr int kDecLdsTotal = kDecTLds + kDecTFrags * 1024;      // 160 KB, all a workgroup can have
 
 // One turn of a streaming wave: R row blocks x the wave's chunks of K (chunks wave, wave + 16, ...,
 // rotated per workgroup so that the workgroups, which all read the same X, do not walk the same
@@ -210,7 +223,7 @@ constexpr int kDecLdsTotal = kDecTLds + kDecTFrags * 1024;      // 152 KB
 //   unit (j, b>0):  2 (R - 1) + XC         (the rest of chunk j, X(j+1), the first b units of chunk j + 1)
 //   last chunk:     2 (R - 1 - b)          (nothing is requested any more)
 // For K up to 4096 a wave has a single chunk and everything is requested up front.
-template <int R, int XC>
+template <int R, int XC, bool SYM>
 struct DecodeStream {
     const W3Buf& wb;
     BufRsrc xb;
@@ -251,7 +264,7 @@ struct DecodeStream {
                 }
             }
             pin_unit_params(u[b]);          // nothing is computed from this unit before the wait
-            dequant_unit_steps(u[b], [&](int t, f16x8 frag) { acc[b] = mfma16(frag, bfrag[t], acc[b]); });
+            dequant_unit_steps<SYM>(u[b], [&](int t, f16x8 frag) { acc[b] = mfma16(frag, bfrag[t], acc[b]); });
             if (!LAST) {
                 __builtin_amdgcn_sched_barrier(0);
                 issue_w(j + 1, rb0 + b, u[b]);
@@ -270,14 +283,33 @@ struct DecodeStream {
 };
 
 
-template <int R, int LR, int XC>
+// Scatters the dequantized unit of one rank (64 consecutive output features, w[P] = features 2P and
+// 2P + 1 of the group) into the U fragments of the R row blocks that start O16 blocks into the
+// group: feature 16 (O16 + b) + jj of rank j goes to fragment (b, j / 32), lane (jj, (j % 32) / 8),
+// element j % 8.  `frag0` points at that element of block 0's fragment for jj = 0.
+template <int R, int O16>
+__device__ __forceinline__ void scatter_u_rank(const uint32_t (&w)[32], unsigned char* frag0) {
+#pragma unroll
+    for (int b = 0; b < R; ++b)
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+            const int n = 16 * (O16 + b) + jj;
+            const uint32_t v = w[n >> 1];
+            *reinterpret_cast<unsigned short*>(frag0 + b * (kDecKS * 1024) + jj * 16) =
+                (unsigned short)((n & 1) ? (v >> 16) : v);
+        }
+}
+
+// SYM: the weight blob is symmetric (zero-point-free conversion).  Q (with LR == 1): the compensator
+// is the pair of INT3 blobs of milo_pack_lr3.
+template <int R, int LR, int XC, bool SYM, bool Q>
 __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int nworkers = LR > 0 ? a.nt : 0;
     if (LR > 0 && (int)blockIdx.x < nworkers) {
-        decode_t_worker<XC>(a, smem);
+        decode_t_worker<XC, Q>(a, smem);
     } else {
         const int j16 = lane & 15, q = lane >> 4;
         const int M = a.M;
@@ -295,7 +327,7 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
         bool t_ready = false;
 
         const int wave_s = __builtin_amdgcn_readfirstlane(wave);        // known to be uniform
-        DecodeStream<R, XC> st{wb,
+        DecodeStream<R, XC, SYM> st{wb,
                                make_rsrc(a.X, (uint64_t)M * K * 2u),
                                XCopy(lane, K),
                                smem + wave_s * kDecSlotBytes,
@@ -325,7 +357,31 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
                 // U[n][32i + 8q ..]), then, once every T worker has been counted, T as B
                 // fragments with device-coherent reads: the workers wrote it during this launch.
                 __builtin_amdgcn_s_setprio(3);
-                if (LR == 1) {
+                if (LR == 1 && Q) {
+                    // INT3 U: the blob holds U^T [ldt x N] with groups of 64 along N, and this
+                    // workgroup's 16 R rows lie inside one group.  Lane l takes rank l (then l +
+                    // 64): one unit, converted, and scattered into the fragment layout the
+                    // epilogue reads.  Ranks past the compensator's read as zero units, which
+                    // also clears the rest of the last k-step.
+                    const W3Buf uq = make_w3buf(a.w.U, a.ldt, a.N);
+                    const uint32_t GN = (uint32_t)(a.N >> 6), g = rb0 >> 2, o16 = rb0 & 3u;
+                    for (uint32_t j = (uint32_t)lane; j < 32u * (uint32_t)ksu; j += 64u) {
+                        const bool ok = j < (uint32_t)a.ldt && rb0 < NB;
+                        const RawUnit u = load_unit_buf(uq, ok ? ((j >> 4) * GN + g) * 16u + (j & 15u) : (1u << 27));
+                        uint32_t w[32];
+                        dequant_unit<true>(u, w);
+                        unsigned char* const frag0 =
+                            smem + kDecULds + (((j >> 5) * 64u + ((j & 31u) >> 3) * 16u) * 16u + (j & 7u) * 2u);
+                        if (R == 4) scatter_u_rank<R, 0>(w, frag0);
+                        else if (R == 2) { if (o16 == 0) scatter_u_rank<R, 0>(w, frag0); else scatter_u_rank<R, 2>(w, frag0); }
+                        else {
+                            if (o16 == 0) scatter_u_rank<R, 0>(w, frag0);
+                            else if (o16 == 1) scatter_u_rank<R, 1>(w, frag0);
+                            else if (o16 == 2) scatter_u_rank<R, 2>(w, frag0);
+                            else scatter_u_rank<R, 3>(w, frag0);
+                        }
+                    }
+                } else if (LR == 1) {
                     const BufRsrc ub = make_rsrc(a.w.U, (uint64_t)a.N * (uint64_t)r * 2u);
 #pragma unroll 1
                     for (int b = 0; b < R; ++b) {
@@ -463,27 +519,37 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
 // Workgroups the device keeps resident at once (one 128-KB-LDS workgroup per CU), cached per
 // device; also raises the kernels' dynamic LDS limit once.
 typedef void (*DecodeKernel)(const DecodeArgs);
-template <int R, int LR>
+// Variants: R x LR x XC for plain weights with an fp16 compensator (the generic path LR == 2 is not
+// specialised by XC); with an INT3 compensator R x XC (LR == 1); with the symmetric conversion the
+// shape that matters for speed, R == 4 with LR 0 or 1 (other shapes take the plain conversion, which
+// gives the same bits).
+template <int R, int LR, bool SYM, bool Q>
 static DecodeKernel decode_variant_xc(int xc) {
     if constexpr (LR == 2) {
-        return w3lr_decode_kernel<R, LR, 8>;      // the generic path is not specialised
+        return w3lr_decode_kernel<R, LR, 8, false, false>;
     } else {
-        if (xc == 1) return w3lr_decode_kernel<R, LR, 1>;
-        if (xc == 2) return w3lr_decode_kernel<R, LR, 2>;
-        if (xc == 4) return w3lr_decode_kernel<R, LR, 4>;
-        return w3lr_decode_kernel<R, LR, 8>;
+        if (xc == 1) return w3lr_decode_kernel<R, LR, 1, SYM, Q>;
+        if (xc == 2) return w3lr_decode_kernel<R, LR, 2, SYM, Q>;
+        if (xc == 4) return w3lr_decode_kernel<R, LR, 4, SYM, Q>;
+        return w3lr_decode_kernel<R, LR, 8, SYM, Q>;
     }
 }
-template <int LR>
-static DecodeKernel decode_variant_lr(int R, int xc) {
-    if (R == 4) return decode_variant_xc<4, LR>(xc);
-    if (R == 2) return decode_variant_xc<2, LR>(xc);
-    return decode_variant_xc<1, LR>(xc);
+template <int LR, bool SYM, bool Q>
+static DecodeKernel decode_variant_r(int R, int xc) {
+    if (R == 4) return decode_variant_xc<4, LR, SYM, Q>(xc);
+    if constexpr (SYM) {
+        return nullptr;
+    } else {
+        if (R == 2) return decode_variant_xc<2, LR, SYM, Q>(xc);
+        return decode_variant_xc<1, LR, SYM, Q>(xc);
+    }
 }
-static DecodeKernel decode_variant(int R, int lr, int xc) {
-    if (lr == 0) return decode_variant_lr<0>(R, xc);
-    if (lr == 1) return decode_variant_lr<1>(R, xc);
-    return decode_variant_lr<2>(R, xc);
+static DecodeKernel decode_variant(int R, int lr, int xc, bool sym, bool q) {
+    if (q) return lr == 1 ? decode_variant_r<1, false, true>(R, xc) : nullptr;
+    if (sym && R == 4 && lr < 2) return lr == 0 ? decode_variant_r<0, true, false>(R, xc) : decode_variant_r<1, true, false>(R, xc);
+    if (lr == 0) return decode_variant_r<0, false, false>(R, xc);
+    if (lr == 1) return decode_variant_r<1, false, false>(R, xc);
+    return decode_variant_r<2, false, false>(R, xc);
 }
 static int decode_capacity() {
     static int cached[64] = {0};
@@ -496,9 +562,13 @@ static int decode_capacity() {
         for (int R = 1; R <= 4; R *= 2)
             for (int lr = 0; lr < 3; ++lr)
                 for (int xc = 1; xc <= 8; xc *= 2)
-                    if (hipFuncSetAttribute(reinterpret_cast<const void*>(decode_variant(R, lr, xc)),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, kDecLdsTotal) != hipSuccess)
-                        return 0;
+                    for (int v = 0; v < 3; ++v) {       // plain, symmetric, INT3 compensator
+                        const DecodeKernel k = decode_variant(R, lr, xc, v == 1, v == 2);
+                        if (k && hipFuncSetAttribute(reinterpret_cast<const void*>(k),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                     kDecLdsTotal) != hipSuccess)
+                            return 0;
+                    }
         cached[dev] = cus;
     }
     return cached[dev];
@@ -568,12 +638,17 @@ int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream) {
     const int rows = 16 * R;
     const int64_t blocks = (a.N + rows - 1) / rows;
     const int grid = (int)(blocks < cap - workers ? blocks : cap - workers) + workers;
-    const bool lds_path = (r & 7) == 0 && r <= 32 * kDecKS && a.kh * ((r + 31) / 32) <= kDecTFrags &&
+    const bool int3 = (a.w.flags & MILO_LR_INT3) != 0;
+    const bool lds_path = ((r & 7) == 0 || int3) && r <= 32 * kDecKS && a.kh * ((r + 31) / 32) <= kDecTFrags &&
                           (uint64_t)a.N * (uint64_t)r * 2u < 0xFFFFFFF0ull;
     const int lr = r == 0 ? 0 : lds_path ? 1 : 2;
     const int xc = a.M <= 2 ? 1 : a.M <= 4 ? 2 : a.M <= 8 ? 4 : 8;    // activation copies per chunk: rows 2i, 2i+1
-    decode_variant(R, lr, xc)<<<dim3((unsigned)grid), dim3(kDecThreads),
-                                lr == 1 ? kDecLdsTotal : kDecLdsBytes, stream>>>(a);
+    const bool q = r > 0 && (a.w.flags & MILO_LR_INT3) != 0;
+    // an INT3 compensator only runs on the staged path: its T fragments must fit the workgroup's LDS
+    if (q && lr != 1) return MILO_ERR_SHAPE;
+    const DecodeKernel kernel = decode_variant(R, lr, xc, (a.w.flags & MILO_W3_SYMMETRIC) != 0, q);
+    if (!kernel) return MILO_ERR_HIP;
+    kernel<<<dim3((unsigned)grid), dim3(kDecThreads), lr == 1 ? kDecLdsTotal : kDecLdsBytes, stream>>>(a);
     return launch_status();
 }
 

@@ -166,7 +166,57 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
             return buf_load16(vb[s], out ? kOobOffset : voff[s] + (uint32_t)c * 256u + 16u * t);
         };
 
+        // INT3 compensator (MILO_LR_INT3): V is a packed blob [pad16(r) x K] in the layout of a weight,
+        // so lane (i32, h) loads the unit of rank rank0 + i32, group 2c + h, and converts it (symmetric
+        // quantizer: no zero-point arithmetic) into the same eight fragments per chunk.
+        const bool vq = ((ti.w[0].flags | ti.w[1].flags) & MILO_LR_INT3) != 0;     // (one setting per tile)
+        if (vq) {
+            W3Buf vqb[2];
+            uint32_t vu[2];
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const WeightDev& w = ti.w[NW == 1 ? 0 : s];
+                const int rp = (w.r + 15) & ~15;
+                vqb[s] = make_w3buf(w.V, rp, K);
+                const int rank = rank0[s] + i32;
+                vu[s] = (active[s] && rank < rp) ? (uint32_t)unit_index(rank, 0, G) : kOobUnit;
+            }
+            auto load_vq = [&](int c, int s) -> RawUnit {
+                const bool out = vu[s] == kOobUnit || c >= c_hi || (ktail && c == nchunks - 1 && h == 1);
+                return load_unit_buf(vqb[s], out ? (1u << 27) : vu[s] + (uint32_t)(2 * c + h) * 16u);
+            };
+            RawUnit cur[2], nxt[2];
+            __syncthreads();            // a previous pass is done with the stages
+            if (c_lo < c_hi) issue_x(c_lo);
+            cur[0] = load_vq(c_lo, 0);
+            cur[1] = load_vq(c_lo, 1);
+            for (int c = c_lo; c < c_hi; ++c) {
+                wait_vmem();
+                pin_unit(cur[0]);
+                pin_unit(cur[1]);
+                __syncthreads();
+                if (c + 1 < c_hi) issue_x(c + 1);
+                nxt[0] = load_vq(c + 1, 0);
+                nxt[1] = load_vq(c + 1, 1);
+                const unsigned char* xs = smem + (c & 1) * STAGE + i32 * 256;
+                const int sx = i32 & 15;
+                if (active[0] || active[1]) {
+                    dequant_units2_steps<true>(cur[0], cur[1], [&](int t, f16x8 a0, f16x8 a1) {
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb) {
+                            const f16x8 b = __builtin_bit_cast(
+                                f16x8, *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h + t) ^ sx) << 4)));
+                            acc[0][mb] = mfma32(a0, b, acc[0][mb]);
+                            acc[1][mb] = mfma32(a1, b, acc[1][mb]);
+                        }
+                    });
+                }
+                cur[0] = nxt[0];
+                cur[1] = nxt[1];
+            }
+        }
         u32x4 va[2][8];
+        if (!vq) {
         __syncthreads();            // a previous pass is done with the stages
         if (c_lo < c_hi) issue_x(c_lo);
 #pragma unroll
@@ -201,6 +251,7 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
                     va[1][t] = load_v(c + 1, 1, t);
                 }
             }
+        }
         }
         // D[v] of (s, mb): rank rank0 + 8*(v/4) + 4*h + v%4, row 32*mb + i32; ranks up to the next
         // multiple of 16 are written (they are exact zeros) because the consumers read that far.
@@ -568,6 +619,37 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
         // their T fragments are all requested before the first is used, so that a rank-128
         // compensator costs four memory round trips instead of forty.
         bool waited = false;
+        // INT3 compensator: the U blob holds U^T [pad16(r) x N] with groups of 64 along N.  The band of
+        // this workgroup is four groups (NW = 1) or two groups of each of the two weights (NW = 2):
+        // thread (wave w, lane l) converts the unit of rank l (then l + 64) of the w-th of them and
+        // writes its 64 features as a column of the LDS array UL[band feature][rank] (fp16, row length
+        // ldu), from which every lane then reads the eight ranks of a k-step of its feature with one
+        // 16-byte load.  The array takes the place of the activation stages, which are dead by now.
+        const bool uq = ((ti.w[0].flags | ti.w[1].flags) & MILO_LR_INT3) != 0;
+        const int ldu = (((ti.w[0].r > ti.w[1].r ? ti.w[0].r : ti.w[1].r) + 15) & ~15) + 8;     // (+8: rows on different banks)
+        if (uq) {
+            __syncthreads();                // every wave is done with the stages
+            const int gsel = wave_s;
+            const bool second = NW == 2 && gsel >= 2;       // (selected field by field: no indexing of ti.w)
+            const int rp = ((second ? ti.w[1].r : ti.w[0].r) + 15) & ~15;
+            const int GN = (int)(N >> 6);
+            const int64_t g = (n0 >> 6) + (NW == 1 ? gsel : (gsel & 1));
+            const W3Buf ub = make_w3buf(second ? ti.w[1].U : ti.w[0].U, rp, N);
+            f16* const UL = reinterpret_cast<f16*>(smem);
+            for (int j = lane; j < rp; j += 64) {
+                const RawUnit u = load_unit_buf(ub, g < GN ? (uint32_t)unit_index(j, g, GN) : (1u << 27));
+                uint32_t wv[32];
+                dequant_unit<true>(u, wv);
+                f16* col = UL + (int64_t)(64 * gsel) * ldu + j;
+#pragma unroll
+                for (int P = 0; P < 32; ++P) {
+                    const f16x2 pr = __builtin_bit_cast(f16x2, wv[P]);
+                    col[(2 * P) * ldu] = pr[0];
+                    col[(2 * P + 1) * ldu] = pr[1];
+                }
+            }
+            __syncthreads();
+        }
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const WeightDev& w = ti.w[NW == 1 ? 0 : s];
@@ -577,13 +659,20 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
             const f16* urow = w.U + (nvalid[s] ? nrow[s] : 0) * (int64_t)r;
             const bool ualigned = (r & 7) == 0;
             const int rpad = (r + 15) & ~15;            // T is written (with zeros) up to here
+            // row of this lane's feature in UL: band feature index (NW = 2: the second weight's follow)
+            const f16* ulrow = reinterpret_cast<const f16*>(smem) +
+                               (int64_t)((NW == 1) ? (64 * wave + 32 * s + i32) : (128 * s + 32 * wave + i32)) * ldu;
             for (int ks = 0; ks < r; ks += 32) {
                 f16x8 av[2];
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const int k0 = ks + 16 * j + 8 * h;
                     av[j] = zero_f16x8();
-                    if (nvalid[s] && k0 < r) av[j] = load_row8(urow, k0, r, ualigned);
+                    if (uq) {
+                        if (k0 < rpad) av[j] = load_f16x8(ulrow + k0);
+                    } else if (nvalid[s] && k0 < r) {
+                        av[j] = load_row8(urow, k0, r, ualigned);
+                    }
                 }
                 if (!waited) {
                     if (tid == 0) wait_flag(a.flags + 4 * by + 1, 1u, a.flags_status);
@@ -695,14 +784,17 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
 
 template <int NW, int MB, int EPI>
 static int launch_one(const TiledArgs& a, dim3 grid, hipStream_t stream) {
-    constexpr int lds = (MB == 4 ? 2 : kTiledStages) * 32 * MB * 256;
+    constexpr int lds_stages = (MB == 4 ? 2 : kTiledStages) * 32 * MB * 256;
+    // room for the U array of an INT3 compensator: 256 band features x (pad16(rank) + 8) fp16
+    const int lds_u = a.lr3_rank > 0 ? 256 * (((a.lr3_rank + 15) & ~15) + 8) * 2 : 0;
+    const int lds = lds_u > lds_stages ? lds_u : lds_stages;
     static bool raised[64] = {false};
     if (lds > 64 * 1024) {
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MILO_ERR_HIP;
         if (!raised[dev]) {
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(w3lr_tiled_kernel<NW, MB, EPI>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024) != hipSuccess)
                 return MILO_ERR_HIP;
             raised[dev] = true;
         }

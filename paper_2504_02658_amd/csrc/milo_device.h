@@ -197,15 +197,26 @@ __device__ __forceinline__ f16x8 unit_frag(const uint32_t (&w)[32], int t);
 struct UnitConsts {
     uint32_t A0, A3, A6, S2, C2;
 };
+// SYM: the unit comes from the symmetric quantizer (Section 3.2.3, Eq. symm_int3; the "symmetric"
+// kernel of Section 3.3): its zero-point is 4 by construction, so the biased zero-points are
+// compile-time constants and the correction term is zero; only the scale is read from the unit.
+template <bool SYM = false>
 __device__ __forceinline__ UnitConsts unit_consts(const RawUnit& ru) {
+    UnitConsts c;
+    c.S2 = pack2(f16_bits(ru.sz));
+    if (SYM) {
+        c.A0 = 0x64046404u;     // 1024 + 4
+        c.A3 = 0x58205820u;     // 128 + 4
+        c.A6 = 0x4D004D00u;     // 16 + 4
+        c.C2 = 0u;
+        return c;
+    }
     const float s = (float)f16_bits(ru.sz);
     const float z = (float)f16_bits(ru.sz >> 16);
     const float zr = __builtin_fminf(__builtin_fmaxf(__builtin_rintf(z), -8.0f), 15.0f);
-    UnitConsts c;
     c.A0 = pack2((f16)(1024.0f + zr));
     c.A3 = pack2((f16)(128.0f + zr));
     c.A6 = pack2((f16)(16.0f + zr));
-    c.S2 = pack2(f16_bits(ru.sz));
     c.C2 = pack2((f16)((zr - z) * s));
     return c;
 }
@@ -218,9 +229,9 @@ __device__ __forceinline__ uint32_t pk_fma(uint32_t a, uint32_t b, uint32_t c) {
                                             __builtin_bit_cast(f16x2, c)));
 }
 
-template <typename OnStep>
+template <bool SYM = false, typename OnStep>
 __device__ __forceinline__ void dequant_unit_steps(const RawUnit& ru, OnStep&& on_step) {
-    const UnitConsts c = unit_consts(ru);
+    const UnitConsts c = unit_consts<SYM>(ru);
     const uint32_t B0 = in_vgpr(0x64006400u), B3 = in_vgpr(0x58005800u), B6 = in_vgpr(0x4C004C00u);
     const uint32_t M0 = in_sgpr(0x00070007u), M3 = in_sgpr(0x00380038u), M6 = in_sgpr(0x01C001C0u);
     const uint32_t d[6] = {ru.a.x, ru.a.y, ru.a.z, ru.a.w, ru.b.x, ru.b.y};
@@ -277,9 +288,9 @@ __device__ __forceinline__ void dequant_unit_steps(const RawUnit& ru, OnStep&& o
 
 // Two units converted in lock step (ten independent operations per group): the tiled kernel
 // feeds two weight streams from one set of B fragments.  on_step(t, frag0, frag1), t = 0..7.
-template <typename OnStep>
+template <bool SYM = false, typename OnStep>
 __device__ __forceinline__ void dequant_units2_steps(const RawUnit& r0, const RawUnit& r1, OnStep&& on_step) {
-    const UnitConsts c0 = unit_consts(r0), c1 = unit_consts(r1);
+    const UnitConsts c0 = unit_consts<SYM>(r0), c1 = unit_consts<SYM>(r1);
     const uint32_t B0 = in_vgpr(0x64006400u), B3 = in_vgpr(0x58005800u), B6 = in_vgpr(0x4C004C00u);
     const uint32_t M0 = in_sgpr(0x00070007u), M3 = in_sgpr(0x00380038u), M6 = in_sgpr(0x01C001C0u);
     const uint32_t S6 = in_sgpr(0x00400040u), S7 = in_sgpr(0x00800080u), S8 = in_sgpr(0x01000100u);
@@ -342,8 +353,9 @@ __device__ __forceinline__ void dequant_units2_steps(const RawUnit& r0, const Ra
 }
 
 // All 32 pairs of a unit at once (for the dense dequantization kernel).
+template <bool SYM = false>
 __device__ __forceinline__ void dequant_unit(const RawUnit& ru, uint32_t (&w)[32]) {
-    dequant_unit_steps(ru, [&](int t, f16x8 frag) {
+    dequant_unit_steps<SYM>(ru, [&](int t, f16x8 frag) {
         const u32x4 v = __builtin_bit_cast(u32x4, frag);
         w[4 * t + 0] = v.x;
         w[4 * t + 1] = v.y;

@@ -8,10 +8,10 @@ namespace milo {
 // Same bytes as the public milo_w3lr_weight.
 struct WeightDev {
     const void* q3;
-    const f16* U;
-    const f16* V;
+    const f16* U;       // fp16 [N x r], or with MILO_LR_INT3 the packed U^T blob [pad16(r) x N]
+    const f16* V;       // fp16 [r x K], or with MILO_LR_INT3 the packed V blob [pad16(r) x K]
     int32_t r;
-    int32_t reserved;
+    uint32_t flags;     // MILO_W3_SYMMETRIC | MILO_LR_INT3
 };
 static_assert(sizeof(WeightDev) == sizeof(milo_w3lr_weight), "weight descriptor layout");
 static_assert(sizeof(milo_w3lr_expert) == 3 * sizeof(WeightDev), "expert descriptor layout");
@@ -59,6 +59,7 @@ struct TiledArgs {
     int v_tiles;        // workgroups per M-tile that form T: t_parts (they belong to split 0)
     int ksplit;         // K splits; split z multiplies its share of the chunks
     int m_tiles;        // upper bound of the number of M-tiles (set by launch_tiled)
+    int lr3_rank;       // largest rank an INT3 compensator of this launch may have (0: none can occur)
     int weights_once;   // non-zero: every weight is read by one M-tile only (non-temporal loads)
     uint32_t* flags;    // per M-tile t: [4t] parts done, [4t+1] T ready, [4t+2] readers done; zero between launches
     uint32_t* flags_status;  // set non-zero if a wait ever gave up

@@ -337,6 +337,11 @@ static int check_weight(const milo_w3lr_weight& w, int64_t N, int64_t K) {
     if (!w.q3) return MILO_ERR_NULL;
     if (w.r < 0 || w.r > N || w.r > K) return MILO_ERR_RANK;
     if (w.r > 0 && (!w.U || !w.V)) return MILO_ERR_RANK;
+    if (w.flags & ~(MILO_W3_SYMMETRIC | MILO_LR_INT3)) return MILO_ERR_SHAPE;
+    if (w.r > 0 && (w.flags & MILO_LR_INT3)) {
+        if (w.r > MILO_LR3_MAX_RANK) return MILO_ERR_RANK;
+        if ((N % kGroup) != 0) return MILO_ERR_SHAPE;
+    }
     if (!aligned16(w.q3) || !aligned16(w.U) || !aligned16(w.V))
         return MILO_ERR_ALIGN;
     return MILO_OK;
@@ -359,6 +364,10 @@ extern "C" int milo_moe_w3lr_check_experts(const milo_w3lr_expert* experts, int 
             if (st != MILO_OK) return st;
             if (ws[i]->r > r_max) r_max = ws[i]->r;
         }
+        // gate and up projection share a launch: their compensators are both INT3 or both fp16
+        if (experts[e].w1.r > 0 && experts[e].w3.r > 0 &&
+            ((experts[e].w1.flags ^ experts[e].w3.flags) & MILO_LR_INT3))
+            return MILO_ERR_SHAPE;
     }
     if (r_max_out) *r_max_out = r_max;
     return MILO_OK;
@@ -431,6 +440,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         ga.t_part_stride = (int64_t)P * L.ldt; ga.t_parts = L.parts_up; ga.v_tiles = L.parts_up; ga.ksplit = 1;
         ga.out_split_stride = 0; ga.flags = flags; ga.weights_once = once;
         ga.flags_status = reinterpret_cast<uint32_t*>(header + 3);
+        ga.lr3_rank = r_max < MILO_LR3_MAX_RANK ? r_max : MILO_LR3_MAX_RANK;    // (any weight's compensator may be INT3)
         ga.out = Hbuf; ga.ldo = F; ga.out_rows = nullptr; ga.out_scale = nullptr;
         st = launch_tiled(ga, 2, mb, EPI_SWIGLU, L.max_tiles, stream);
         if (st != MILO_OK) return st;
@@ -447,6 +457,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         da.t_part_stride = (int64_t)P * L.ldt; da.t_parts = L.parts_down; da.v_tiles = L.parts_down;
         da.ksplit = L.splits_down; da.out_split_stride = (int64_t)P * H; da.flags = flags; da.weights_once = once;
         da.flags_status = reinterpret_cast<uint32_t*>(header + 3);
+        da.lr3_rank = r_max < MILO_LR3_MAX_RANK ? r_max : MILO_LR3_MAX_RANK;
         da.out = O; da.ldo = H; da.out_rows = sorted; da.out_scale = topk_weights;
         st = launch_tiled(da, 1, mb, EPI_SCALE_SCATTER, L.max_tiles, stream);
         if (st != MILO_OK) return st;

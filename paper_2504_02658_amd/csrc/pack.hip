@@ -21,10 +21,13 @@ __device__ __forceinline__ uint32_t shfl_xor16(uint32_t v, int m) {
 
 // SYM = false: asymmetric quantizer (Eq. wq).  SYM = true: the symmetric INT3 quantizer (Eq.
 // symm_int3) in the same storage: the scale word holds the step 2 * max|w| / 7, the zero word 4.
+// The source is element (n, k) = W[n * row_stride + k * col_stride] for n < n_valid and zero for the
+// rows from n_valid up to N (a plain row-major weight has row_stride = K, col_stride = 1, n_valid = N;
+// the compensator factors of milo_pack_lr3 come transposed or with padded rows).
 template <bool SYM>
 __global__ __launch_bounds__(kPackThreads) void pack_w3_kernel(
-    const float* __restrict__ W, int64_t N, int64_t K, uint32_t* __restrict__ planeA,
-    uint32_t* __restrict__ planeB) {
+    const float* __restrict__ W, int64_t N, int64_t K, int64_t row_stride, int64_t col_stride, int64_t n_valid,
+    uint32_t* __restrict__ planeA, uint32_t* __restrict__ planeB) {
     const int64_t G = K / kGroup;
     const int64_t total = N * G;
     const int64_t gu = (int64_t)blockIdx.x * kUnitsPerBlock + (threadIdx.x >> 4);
@@ -33,7 +36,18 @@ __global__ __launch_bounds__(kPackThreads) void pack_w3_kernel(
     const int64_t n = gu / G;
     const int64_t g = gu - n * G;
 
-    const float4 v = *reinterpret_cast<const float4*>(W + n * K + g * kGroup + 4 * l16);
+    float4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (n < n_valid) {
+        const float* src = W + n * row_stride + (g * kGroup + 4 * l16) * col_stride;
+        if (col_stride == 1) {
+            v = *reinterpret_cast<const float4*>(src);
+        } else {
+            v.x = src[0];
+            v.y = src[col_stride];
+            v.z = src[2 * col_stride];
+            v.w = src[3 * col_stride];
+        }
+    }
     float mn = fminf(fminf(v.x, v.y), fminf(v.z, v.w));
     float mx = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
 #pragma unroll
@@ -198,7 +212,46 @@ static int pack_launch(const float* W, int64_t N, int64_t K, int group_size, voi
     if (blocks > 0x7fffffff) return MILO_ERR_SHAPE;
     uint32_t* planeA = reinterpret_cast<uint32_t*>(q3);
     uint32_t* planeB = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(q3) + (N * K) / 4);
-    pack_w3_kernel<SYM><<<dim3((unsigned)blocks), dim3(kPackThreads), 0, (hipStream_t)stream>>>(W, N, K, planeA, planeB);
+    pack_w3_kernel<SYM><<<dim3((unsigned)blocks), dim3(kPackThreads), 0, (hipStream_t)stream>>>(W, N, K, K, 1, N, planeA,
+                                                                                               planeB);
+    return launch_status();
+}
+
+static int64_t rank_rows(int r) { return ((int64_t)r + 15) / 16 * 16; }
+
+extern "C" int milo_lr3_packed_bytes(int64_t N, int64_t K, int r, size_t* u_bytes, size_t* v_bytes) {
+    if (r <= 0 || r > MILO_LR3_MAX_RANK) return MILO_ERR_RANK;
+    if (!weight_shape_ok(N, K) || (N % kGroup) != 0 || !weight_shape_ok(rank_rows(r), N) || !weight_shape_ok(rank_rows(r), K))
+        return MILO_ERR_SHAPE;
+    if (u_bytes) *u_bytes = (size_t)(rank_rows(r) * N / 64 * 28);
+    if (v_bytes) *v_bytes = (size_t)(rank_rows(r) * K / 64 * 28);
+    return MILO_OK;
+}
+
+extern "C" int milo_pack_lr3(const float* U, const float* V, int64_t N, int64_t K, int r, void* u3, void* v3,
+                             void* stream) {
+    if (!U || !V || !u3 || !v3) return MILO_ERR_NULL;
+    const int st = milo_lr3_packed_bytes(N, K, r, nullptr, nullptr);
+    if (st != MILO_OK) return st;
+    if (!aligned16(U) || !aligned16(V) || !aligned16(u3) || !aligned16(v3)) return MILO_ERR_ALIGN;
+    const int64_t rp = rank_rows(r);
+    // U^T: [rp x N], element (j, n) = U[n * r + j], groups of 64 along N
+    {
+        const int64_t units = rp * (N / kGroup), blocks = (units + kUnitsPerBlock - 1) / kUnitsPerBlock;
+        uint32_t* planeA = reinterpret_cast<uint32_t*>(u3);
+        uint32_t* planeB = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(u3) + (rp * N) / 4);
+        pack_w3_kernel<true><<<dim3((unsigned)blocks), dim3(kPackThreads), 0, (hipStream_t)stream>>>(U, rp, N, 1, r, r,
+                                                                                                planeA, planeB);
+        if (launch_status() != MILO_OK) return MILO_ERR_HIP;
+    }
+    // V: [rp x K], element (j, k) = V[j * K + k], groups of 64 along K
+    {
+        const int64_t units = rp * (K / kGroup), blocks = (units + kUnitsPerBlock - 1) / kUnitsPerBlock;
+        uint32_t* planeA = reinterpret_cast<uint32_t*>(v3);
+        uint32_t* planeB = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(v3) + (rp * K) / 4);
+        pack_w3_kernel<true><<<dim3((unsigned)blocks), dim3(kPackThreads), 0, (hipStream_t)stream>>>(V, rp, K, K, 1, r,
+                                                                                                planeA, planeB);
+    }
     return launch_status();
 }
 

@@ -53,8 +53,26 @@ def gpu_weight(W, ow, check_pack=True, symmetric=False):
     return pw
 
 
-def build_moe(case, threads=8):
-    """Both sides of an MoE layer: list of oracle expert dicts and the library's MoELayer."""
+def int3_weight(W, ow):
+    """The same weight with its compensator INT3-quantized on both sides (Section 3.2.3, Eq. symm_int3):
+    returns (oracle dict with the dequantized fp64 factors, library PackedWeight with the two blobs)."""
+    import torch
+    from paper_2504_02658_amd import api
+    r = ow["U"].shape[1]
+    pw = gpu_weight(W, dict(ow, U=np.zeros((W.shape[0], 0), np.float16)))
+    if r == 0:
+        return ow, pw
+    U32, V32 = ow["U"].astype(np.float32), ow["V"].astype(np.float32)
+    uq, vq = oracle.quantize_compensator(U32, V32)
+    Ud, Vd = oracle.dequantize_compensator(uq, vq, r)
+    u3, v3 = api.pack_lr3(torch.from_numpy(U32).cuda(), torch.from_numpy(V32).cuda())
+    assert np.array_equal(u3.cpu().numpy(), oracle.pack_w3(*uq)) and np.array_equal(v3.cpu().numpy(), oracle.pack_w3(*vq))
+    return dict(ow, U=Ud, V=Vd), pw.with_int3_compensator(u3, v3, r)
+
+
+def build_moe(case, threads=8, int3=False):
+    """Both sides of an MoE layer: list of oracle expert dicts and the library's MoELayer.
+    int3: every compensator is INT3-quantized (on both sides)."""
     from paper_2504_02658_amd import api
     ranks = wl.expert_ranks(case)
     n_exp = case.E + case.n_shared
@@ -70,8 +88,13 @@ def build_moe(case, threads=8):
         built = list(pool.map(one, range(n_exp)))
     o_experts, g_experts = [], []
     for b in built:
-        o_experts.append({k: b[k][1] for k in b})
-        g_experts.append(tuple(gpu_weight(b[k][0], b[k][1]) for k in ("w1", "w3", "w2")))
+        if int3:
+            pairs = {k: int3_weight(b[k][0], b[k][1]) for k in ("w1", "w3", "w2")}
+            o_experts.append({k: pairs[k][0] for k in pairs})
+            g_experts.append(tuple(pairs[k][1] for k in ("w1", "w3", "w2")))
+        else:
+            o_experts.append({k: b[k][1] for k in b})
+            g_experts.append(tuple(gpu_weight(b[k][0], b[k][1]) for k in ("w1", "w3", "w2")))
         for k in b:
             b[k] = None
     layer = api.MoELayer(g_experts, case.H, case.F)

@@ -274,3 +274,61 @@ def test_workspace_status_reports_a_wait_that_gave_up():
         Y = api.w3lr_gemm(Xd, pw, workspace=ws)
         assert api.workspace_status(ws) == 0
         assert_close(Y.cpu().numpy(), oracle.w3lr_linear(X, **ow), "after re-init")
+
+
+# ------------------------------------------------------------------ INT3 compensators, weight flags
+
+def _int3_case(M, N, K, r, seed, symmetric=False):
+    """Both sides of a linear whose compensator is INT3-quantized (Section 3.2.3, Eq. symm_int3)."""
+    import torch
+    from paper_2504_02658_amd import api
+    case = wl.LinearCase("t", M=M, N=N, K=K, r=r, seed=seed)
+    X, W = wl.linear_inputs(case)
+    ow = oracle_weight(W, r, seed=seed, symmetric=symmetric)
+    U32, V32 = ow["U"].astype(np.float32), ow["V"].astype(np.float32)
+    uq, vq = oracle.quantize_compensator(U32, V32)
+    Ud, Vd = oracle.dequantize_compensator(uq, vq, r)
+    ref = oracle.w3lr_linear(X, ow["codes"], ow["scales"], ow["zeros"], Ud, Vd)
+    pw = gpu_weight(W, dict(ow, U=np.zeros((N, 0), np.float16)), symmetric=symmetric)
+    u3, v3 = api.pack_lr3(torch.from_numpy(U32).cuda(), torch.from_numpy(V32).cuda())
+    assert np.array_equal(u3.cpu().numpy(), oracle.pack_w3(*uq)), "U blob differs from the oracle's"
+    assert np.array_equal(v3.cpu().numpy(), oracle.pack_w3(*vq)), "V blob differs from the oracle's"
+    return X, pw.with_int3_compensator(u3, v3, r), ref
+
+
+@pytest.mark.parametrize("M,N,K,r", [
+    (16, 1024, 4096, 32), (1, 256, 1408, 8), (5, 320, 2112, 20), (16, 4096, 14336, 64), (7, 20480, 256, 16),
+    (16, 128, 128, 128), (3, 192, 512, 100),
+    (96, 512, 1024, 32), (40, 256, 832, 8), (200, 1024, 2048, 128), (130, 320, 1408, 20), (512, 1024, 4096, 64),
+])
+def test_int3_compensator(M, N, K, r):
+    X, pw, ref = _int3_case(M, N, K, r, seed=M + N + K + r)
+    assert pw.flags == 2 and pw.weight_bytes() == (N * K + ((r + 15) // 16 * 16) * (N + K)) * 7 // 16
+    assert_close(_run(X, pw), ref, f"INT3 compensator M{M} N{N} K{K} r{r}")
+
+
+def test_int3_compensator_full_size_c1_and_a_symmetric_weight():
+    c = wl.C1[16]
+    X, pw, ref = _int3_case(c.M, c.N, c.K, c.r, seed=c.seed)
+    assert_close(_run(X, pw), ref, "c1 with INT3 compensator")
+    X, pw, ref = _int3_case(16, 1024, 4096, 32, seed=5, symmetric=True)
+    assert pw.flags == 3
+    assert_close(_run(X, pw), ref, "symmetric weight + INT3 compensator")
+
+
+@pytest.mark.parametrize("M,N,K,r", [(16, 14336, 4096, 32), (4, 4096, 4096, 0), (16, 272, 1408, 8), (200, 512, 2048, 24)])
+def test_symmetric_flag_changes_nothing_but_the_kernel(M, N, K, r):
+    # MILO_W3_SYMMETRIC selects the conversion without zero-point arithmetic (Section 3.3): same bits
+    import torch
+    from paper_2504_02658_amd import api
+    case = wl.LinearCase("t", M=M, N=N, K=K, r=r, seed=600 + M)
+    X, W = wl.linear_inputs(case)
+    rng = np.random.default_rng(M + r)
+    pw = api.pack_w3(torch.from_numpy(W).cuda(), symmetric=True)
+    assert pw.flags == api.W3_SYMMETRIC
+    if r:
+        pw = pw.with_compensator(torch.from_numpy((0.02 * rng.standard_normal((N, r))).astype(np.float16)).cuda(),
+                                 torch.from_numpy((0.02 * rng.standard_normal((r, K))).astype(np.float16)).cuda())
+    plain = api.PackedWeight(pw.N, pw.K, pw.q3, pw.U, pw.V, flags=0)
+    a, b = _run(X, pw), _run(X, plain)
+    assert np.array_equal(a.view(np.uint16), b.view(np.uint16))

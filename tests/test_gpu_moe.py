@@ -16,8 +16,8 @@ def _forward(layer, X, ids, gates):
     return Y.cpu().numpy()
 
 
-def _check(case, what=None):
-    o_experts, layer = build_moe(case)
+def _check(case, what=None, int3=False):
+    o_experts, layer = build_moe(case, int3=int3)
     X = wl.moe_activations(case)
     ids, gates = wl.moe_routing(case)
     ref = oracle.moe_forward(X, o_experts, ids, gates)
@@ -35,6 +35,13 @@ def test_tiny_layer_all_tile_heights():
     _check(wl.scaled(base, T=80, name="tiny64"))             # ~40 rows: 64-row tiles
     _check(wl.scaled(base, T=150, name="tiny128a"))          # ~75 rows: 128-row tiles, partly filled
     _check(wl.scaled(base, T=400, name="tiny128"))           # ~200 rows: 128-row tiles, several per expert
+
+
+def test_int3_compensators_in_a_layer():
+    # every expert's U, V as INT3 blobs (Section 3.2.3): the grouped kernels unpack them like weights
+    base = wl.MoECase("int3", T=40, H=256, F=384, E=4, topk=2, seed=21, rank_choices=(0, 8, 16, 40))
+    _check(base, int3=True)
+    _check(wl.scaled(base, T=400, name="int3_128", rank_choices=(16, 32, 128)), int3=True)
 
 
 def test_many_tiles_take_the_xcd_placement_path():
