@@ -361,7 +361,9 @@ __device__ __forceinline__ void gather16(u32x2 (&o)[4]) {
     }
 }
 
-template <int NW, int MB, int EPI>
+// SYM: every weight of the launch is a symmetric blob (MILO_W3_SYMMETRIC): conversion without
+// zero-point arithmetic.
+template <int NW, int MB, int EPI, bool SYM = false>
 __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const TiledArgs a) {
     constexpr int BM = 32 * MB;
     constexpr int BN = (NW == 1) ? 256 : 128;
@@ -562,7 +564,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
             f16x8 bc[MBU], bn[MBU];
 #pragma unroll
             for (int mb = 0; mb < MBU; ++mb) bc[mb] = bfrag(mb, 0);
-            dequant_units2_steps(ru[0], ru[1], [&](int t, f16x8 a0, f16x8 a1) {
+            dequant_units2_steps<SYM>(ru[0], ru[1], [&](int t, f16x8 a0, f16x8 a1) {
                 between(t);
                 if (t < 7) {
 #pragma unroll
@@ -782,7 +784,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     }
 }
 
-template <int NW, int MB, int EPI>
+template <int NW, int MB, int EPI, bool SYM = false>
 static int launch_one(const TiledArgs& a, dim3 grid, hipStream_t stream) {
     constexpr int lds_stages = (MB == 4 ? 2 : kTiledStages) * 32 * MB * 256;
     // room for the U array of an INT3 compensator: 256 band features x (pad16(rank) + 8) fp16
@@ -793,22 +795,22 @@ static int launch_one(const TiledArgs& a, dim3 grid, hipStream_t stream) {
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MILO_ERR_HIP;
         if (!raised[dev]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(w3lr_tiled_kernel<NW, MB, EPI>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(w3lr_tiled_kernel<NW, MB, EPI, SYM>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024) != hipSuccess)
                 return MILO_ERR_HIP;
             raised[dev] = true;
         }
     }
-    w3lr_tiled_kernel<NW, MB, EPI><<<grid, dim3(kTiledThreads), lds, stream>>>(a);
+    w3lr_tiled_kernel<NW, MB, EPI, SYM><<<grid, dim3(kTiledThreads), lds, stream>>>(a);
     return launch_status();
 }
 
-template <int NW, int EPI>
+template <int NW, int EPI, bool SYM = false>
 static int launch_tiled_mb(const TiledArgs& a, int mb, dim3 grid, hipStream_t stream) {
     switch (mb) {
-        case 1: return launch_one<NW, 1, EPI>(a, grid, stream);
-        case 2: return launch_one<NW, 2, EPI>(a, grid, stream);
-        case 4: return launch_one<NW, 4, EPI>(a, grid, stream);
+        case 1: return launch_one<NW, 1, EPI, SYM>(a, grid, stream);
+        case 2: return launch_one<NW, 2, EPI, SYM>(a, grid, stream);
+        case 4: return launch_one<NW, 4, EPI, SYM>(a, grid, stream);
         default: return MILO_ERR_SHAPE;
     }
 }
@@ -828,7 +830,11 @@ int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipSt
     b.m_tiles = m_tiles;
     dim3 grid((unsigned)(n_tiles * rows8));
     if (nw == 2 && epi == EPI_SWIGLU) return launch_tiled_mb<2, EPI_SWIGLU>(b, mb, grid, stream);
-    if (nw == 1 && epi == EPI_STORE) return launch_tiled_mb<1, EPI_STORE>(b, mb, grid, stream);
+    if (nw == 1 && epi == EPI_STORE) {
+        // the single linear knows its one weight: a symmetric blob takes the zero-point-free conversion
+        if (!a.rs.tiles && (a.rs.w[0].flags & MILO_W3_SYMMETRIC)) return launch_tiled_mb<1, EPI_STORE, true>(b, mb, grid, stream);
+        return launch_tiled_mb<1, EPI_STORE>(b, mb, grid, stream);
+    }
     if (nw == 1 && epi == EPI_SCALE_SCATTER)
         return launch_tiled_mb<1, EPI_SCALE_SCATTER>(b, mb, grid, stream);
     return MILO_ERR_SHAPE;
