@@ -174,6 +174,7 @@ extern "C" int milo_w3lr_gemm_flags(const milo_half* X, int64_t M, int64_t N, in
     ga.t_part_stride = M * ldt; ga.t_parts = parts; ga.v_tiles = parts; ga.ksplit = splits;
     ga.flags = tile_flags; ga.flags_status = ctrl + 3; ga.weights_once = m_tiles == 1;
     ga.lr3_rank = (w.flags & MILO_LR_INT3) ? r : 0;
+    ga.self_clean = 1;
     ga.out = splits > 1 ? static_cast<void*>(partial) : static_cast<void*>(Y);
     ga.ldo = N; ga.out_split_stride = M * N; ga.out_rows = nullptr; ga.out_scale = nullptr;
     int st = launch_tiled(ga, 1, mb, EPI_STORE, (int)m_tiles, stream);

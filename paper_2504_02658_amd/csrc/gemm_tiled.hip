@@ -138,7 +138,13 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
     };
 
     const int rmax = ti.w[0].r > ti.w[1].r ? ti.w[0].r : ti.w[1].r;
-    for (int pass0 = 0; pass0 < rmax; pass0 += PASS) {
+    // Ranks up to 32 (the experts' compensators) fit one 32-row MFMA stream.  Instead of one wave
+    // multiplying every row block of the tile while three only copy, wave w then takes row block w
+    // (waves past the tile's blocks only copy): the pass below is instantiated for MBT = MB row blocks
+    // starting at block 0, or for MBT = 1 block starting at this wave's.
+    const bool small = MB > 1 && rmax <= 32;
+    auto pass = [&](auto mbt_c, const int blk0, const int pass0) {
+        constexpr int MBT = decltype(mbt_c)::value;
         // rank row of each stream of this wave, and its V as a buffer (rows >= r read as zero)
         BufRsrc vb[2];
         uint32_t voff[2];
@@ -147,23 +153,28 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const WeightDev& w = ti.w[NW == 1 ? 0 : s];
-            rank0[s] = pass0 + ((NW == 1) ? 64 * wave + 32 * s : 32 * wave);
-            active[s] = rank0[s] < w.r;
+            rank0[s] = MBT != MB ? ((NW == 1) ? 32 * s : 0) : pass0 + ((NW == 1) ? 64 * wave + 32 * s : 32 * wave);
+            active[s] = rank0[s] < w.r && (MBT == MB || wave < MB);
             vb[s] = make_rsrc(w.V, (uint64_t)(w.r > 0 ? w.r : 0) * (uint64_t)K * 2u);
             voff[s] = active[s] ? (uint32_t)(((int64_t)(rank0[s] + i32) * K + 64 * h) * 2) : kOobOffset;
         }
-        f32x16 acc[2][MB];
+        f32x16 acc[2][MBT];
 #pragma unroll
         for (int s = 0; s < 2; ++s)
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+            for (int mb = 0; mb < MBT; ++mb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[s][mb][v] = 0.0f;
-
-        // V fragment of step t of chunk c; out of range (inactive stream, ragged K tail) reads zero
-        auto load_v = [&](int c, int s, int t) -> u32x4 {
-            const bool out = !active[s] || c >= c_hi || (ktail && c == nchunks - 1 && h == 1);
-            return buf_load16(vb[s], out ? kOobOffset : voff[s] + (uint32_t)c * 256u + 16u * t);
+        // one step of the product: A fragments a0, a1 (streams 0, 1) against the B fragments of this
+        // wave's row blocks; xs points at row i32 of block 0 in the stage
+        auto mfma_step = [&](const unsigned char* xs, int sx, int t, f16x8 a0, f16x8 a1) {
+#pragma unroll
+            for (int mb = 0; mb < MBT; ++mb) {
+                const f16x8 b = __builtin_bit_cast(
+                    f16x8, *reinterpret_cast<const u32x4*>(xs + (blk0 + mb) * 32 * 256 + (((8 * h + t) ^ sx) << 4)));
+                if (active[0]) acc[0][mb] = mfma32(a0, b, acc[0][mb]);
+                if (active[1]) acc[1][mb] = mfma32(a1, b, acc[1][mb]);
+            }
         };
 
         // INT3 compensator (MILO_LR_INT3): V is a packed blob [pad16(r) x K] in the layout of a weight,
@@ -201,75 +212,65 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
                 const unsigned char* xs = smem + (c & 1) * STAGE + i32 * 256;
                 const int sx = i32 & 15;
                 if (active[0] || active[1]) {
-                    dequant_units2_steps<true>(cur[0], cur[1], [&](int t, f16x8 a0, f16x8 a1) {
-#pragma unroll
-                        for (int mb = 0; mb < MB; ++mb) {
-                            const f16x8 b = __builtin_bit_cast(
-                                f16x8, *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h + t) ^ sx) << 4)));
-                            acc[0][mb] = mfma32(a0, b, acc[0][mb]);
-                            acc[1][mb] = mfma32(a1, b, acc[1][mb]);
-                        }
-                    });
+                    dequant_units2_steps<true>(cur[0], cur[1],
+                                               [&](int t, f16x8 a0, f16x8 a1) { mfma_step(xs, sx, t, a0, a1); });
                 }
                 cur[0] = nxt[0];
                 cur[1] = nxt[1];
             }
-        }
-        u32x4 va[2][8];
-        if (!vq) {
-        __syncthreads();            // a previous pass is done with the stages
-        if (c_lo < c_hi) issue_x(c_lo);
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
-#pragma unroll
-            for (int t = 0; t < 8; ++t) va[s][t] = load_v(c_lo, s, t);
-        for (int c = c_lo; c < c_hi; ++c) {
-            wait_vmem();
+        } else {
+            // V fragment of step t of chunk c; out of range (inactive stream, ragged K tail) reads zero
+            auto load_v = [&](int c, int s, int t) -> u32x4 {
+                const bool out = !active[s] || c >= c_hi || (ktail && c == nchunks - 1 && h == 1);
+                return buf_load16(vb[s], out ? kOobOffset : voff[s] + (uint32_t)c * 256u + 16u * t);
+            };
+            u32x4 va[2][8];
+            __syncthreads();            // a previous pass is done with the stages
+            if (c_lo < c_hi) issue_x(c_lo);
 #pragma unroll
             for (int s = 0; s < 2; ++s)
 #pragma unroll
-                for (int t = 0; t < 8; ++t)
-                    asm volatile("" : "+v"(va[s][t].x), "+v"(va[s][t].y), "+v"(va[s][t].z), "+v"(va[s][t].w));
-            __syncthreads();
-            if (c + 1 < c_hi) issue_x(c + 1);
-            const unsigned char* xs = smem + (c & 1) * STAGE + i32 * 256;
-            const int sx = i32 & 15;
-            // A wave whose ranks lie past the compensator's (with a small rank, all but wave 0) only
-            // takes part in the copies and barriers.
-            if (active[0] || active[1]) {
+                for (int t = 0; t < 8; ++t) va[s][t] = load_v(c_lo, s, t);
+            for (int c = c_lo; c < c_hi; ++c) {
+                wait_vmem();
 #pragma unroll
-                for (int t = 0; t < 8; ++t) {
+                for (int s = 0; s < 2; ++s)
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        const f16x8 b = __builtin_bit_cast(
-                            f16x8, *reinterpret_cast<const u32x4*>(xs + mb * 32 * 256 + (((8 * h + t) ^ sx) << 4)));
-                        acc[0][mb] = mfma32(__builtin_bit_cast(f16x8, va[0][t]), b, acc[0][mb]);
-                        acc[1][mb] = mfma32(__builtin_bit_cast(f16x8, va[1][t]), b, acc[1][mb]);
+                    for (int t = 0; t < 8; ++t)
+                        asm volatile("" : "+v"(va[s][t].x), "+v"(va[s][t].y), "+v"(va[s][t].z), "+v"(va[s][t].w));
+                __syncthreads();
+                if (c + 1 < c_hi) issue_x(c + 1);
+                const unsigned char* xs = smem + (c & 1) * STAGE + i32 * 256;
+                const int sx = i32 & 15;
+                // A wave without ranks or row blocks of its own only takes part in the copies and barriers.
+                if (active[0] || active[1]) {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        mfma_step(xs, sx, t, __builtin_bit_cast(f16x8, va[0][t]), __builtin_bit_cast(f16x8, va[1][t]));
+                        // the registers of this step are free again: fetch the next chunk's fragment into them
+                        va[0][t] = load_v(c + 1, 0, t);
+                        va[1][t] = load_v(c + 1, 1, t);
                     }
-                    // the registers of this step are free again: fetch the next chunk's fragment into them
-                    va[0][t] = load_v(c + 1, 0, t);
-                    va[1][t] = load_v(c + 1, 1, t);
                 }
             }
         }
-        }
-        // D[v] of (s, mb): rank rank0 + 8*(v/4) + 4*h + v%4, row 32*mb + i32; ranks up to the next
-        // multiple of 16 are written (they are exact zeros) because the consumers read that far.
+        // D[v] of (s, mb): rank rank0 + 8*(v/4) + 4*h + v%4, row 32*(blk0 + mb) + i32; ranks up to the
+        // next multiple of 16 are written (they are exact zeros) because the consumers read that far.
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const WeightDev& w = ti.w[NW == 1 ? 0 : s];
             const int rpad = (w.r + 15) & ~15;
             const BufRsrc pb = make_rsrc(a.Tp[NW == 1 ? 0 : s], a.tp_bytes);
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                const int m = 32 * mb + i32;
+            for (int mb = 0; mb < MBT; ++mb) {
+                const int m = 32 * (blk0 + mb) + i32;
 #pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    const int rank = rank0[s] + 8 * vq + 4 * h;
+                for (int vq4 = 0; vq4 < 4; ++vq4) {
+                    const int rank = rank0[s] + 8 * vq4 + 4 * h;
                     f32x4 o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = acc[s][mb][4 * vq + e];
-                    const bool ok = m < ti.rows && rank < rpad;
+                    for (int e = 0; e < 4; ++e) o[e] = acc[s][mb][4 * vq4 + e];
+                    const bool ok = active[s] && m < ti.rows && rank < rpad;
                     __builtin_amdgcn_raw_buffer_store_b128(
                         __builtin_bit_cast(u32x4, o), pb,
                         ok ? (uint32_t)((part * a.t_part_stride + (ti.row0 + m) * a.ldt + rank) * 4) : kOobOffset, 0,
@@ -277,6 +278,11 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
                 }
             }
         }
+    };
+    if (small) {
+        pass(std::integral_constant<int, MB == 1 ? MB : 1>{}, wave, 0);
+    } else {
+        for (int pass0 = 0; pass0 < rmax; pass0 += PASS) pass(std::integral_constant<int, MB>{}, 0, pass0);
     }
     // This part is complete once its stores are; the last part of the tile to get here adds all
     // parts in part order (so the sum does not depend on which one that was), writes T as fp16
@@ -548,6 +554,12 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     // that blocks past the tile's rows cost nothing and the loop body has no branches (the
     // instruction scheduler interleaves conversion, LDS reads and MFMAs only within a basic block).
     const int mb_used = (ti.rows + 31) / 32;
+    // The tile's "T is ready" flag is asked for once, by every wave for itself, while the last chunk
+    // is still being multiplied (a read of a word written during the launch takes about a
+    // microsecond): the workgroups that form T were dispatched long before, so the answer is nearly
+    // always yes, and the wave goes from its last chunk straight to the low-rank term.
+    uint32_t early_flag = 0u;
+    const bool wants_t = any_rank && bz == 0;
     auto k_loop = [&](auto mbu_c) {
         constexpr int MBU = decltype(mbu_c)::value;
         auto compute = [&](int slot, RawUnit (&ru)[2], auto&& between) {
@@ -598,6 +610,8 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                 MILO_WAIT_VMEM((PD - 2) * PER);
                 __syncthreads();        // everyone's copies of chunk c landed; everyone left chunk c-1
                 issue(c + PD - 1, (slot + PD - 1) % PD, ring[(slot + PD - 1) % PD]);
+                if (wants_t && c == c_end - 1 && lane == 0)
+                    early_flag = __hip_atomic_load(a.flags + 4 * by + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 compute(slot, ring[slot], [](int) {});
             }
         }
@@ -677,8 +691,8 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                     }
                 }
                 if (!waited) {
-                    if (tid == 0) wait_flag(a.flags + 4 * by + 1, 1u, a.flags_status);
-                    __syncthreads();
+                    // every wave asks for itself (no barrier: a wave that is done early goes on early)
+                    if (lane == 0 && early_flag < 1u) wait_flag(a.flags + 4 * by + 1, 1u, a.flags_status);
                     waited = true;
                 }
                 u32x4 bv[2][MB];
@@ -700,12 +714,13 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
             }
         }
         if (!waited) {          // (not reached: some rank is positive)
-            if (tid == 0) wait_flag(a.flags + 4 * by + 1, 1u, a.flags_status);
-            __syncthreads();
+            if (lane == 0 && early_flag < 1u) wait_flag(a.flags + 4 * by + 1, 1u, a.flags_status);
         }
-        // the last reader of this M-tile's T clears its control words for the next launch
-        __syncthreads();
-        if (tid == 0) {
+        // the last reader of this M-tile's T clears its control words for the next launch (the MoE
+        // call clears all of them before every forward instead: the returning atomic is a round
+        // trip to memory per workgroup)
+        if (a.self_clean) __syncthreads();
+        if (a.self_clean && tid == 0) {
             const uint32_t readers = gx - (uint32_t)a.v_tiles;
             if (atomicAdd(a.flags + 4 * by + 2, 1u) == readers - 1u) {
                 __hip_atomic_store(a.flags + 4 * by, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -61,7 +61,8 @@ struct TiledArgs {
     int m_tiles;        // upper bound of the number of M-tiles (set by launch_tiled)
     int lr3_rank;       // largest rank an INT3 compensator of this launch may have (0: none can occur)
     int weights_once;   // non-zero: every weight is read by one M-tile only (non-temporal loads)
-    uint32_t* flags;    // per M-tile t: [4t] parts done, [4t+1] T ready, [4t+2] readers done; zero between launches
+    uint32_t* flags;    // per M-tile t: [4t] parts done, [4t+1] T ready, [4t+2] readers done; zero at launch
+    int self_clean;     // non-zero: the last reader of a tile's T clears its words (else the caller does before the next launch)
     uint32_t* flags_status;  // set non-zero if a wait ever gave up
     // EPI 0: fp16 [rows x ldo], or with ksplit > 1 fp32 partial sums, split z at out + z * out_split_stride
     // EPI 1: fp16 [rows x ldo];  EPI 2: fp16 [.. x ldo], split z at out + z * out_split_stride

@@ -318,7 +318,7 @@ static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_m
     size_t off = 0;
     L->off_header = off; off = align_up(off + 64, 256);
     L->max_tiles32 = max_tiles32;
-    L->off_flags = off;  off = align_up(off + (size_t)max_tiles32 * 16, 256);
+    L->off_flags = off;  off = align_up(off + 2 * (size_t)max_tiles32 * 16, 256);   // gate/up launch, down launch
     L->off_sorted = off; off = align_up(off + (size_t)P * 4, 256);
     L->off_token = off;  off = align_up(off + (size_t)P * 4, 256);
     L->off_slots = off;  off = align_up(off + (size_t)max_tiles32 * sizeof(TileDesc), 256);
@@ -412,7 +412,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
     ra.ids = topk_ids; ra.P = P; ra.E = E; ra.bm = L.bm;
     ra.topk = topk; ra.sorted = sorted; ra.sorted_token = sorted_token; ra.tiles = slots; ra.header = header;
     uint32_t* flags = reinterpret_cast<uint32_t*>(ws + L.off_flags);
-    ra.flags = flags; ra.n_flags = (int32_t)(4 * L.max_tiles32);
+    ra.flags = flags; ra.n_flags = (int32_t)(2 * 4 * L.max_tiles32);
     ra.max_tiles = L.max_tiles;
     route_kernel<<<dim3((unsigned)E), dim3(kRouteThreads), 0, stream>>>(ra);
     int st = launch_status();
@@ -438,7 +438,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         ga.T[0] = T1; ga.T[1] = T3; ga.ldt = L.ldt; ga.t_bytes = (uint64_t)P * L.ldt * 2;
         ga.Tp[0] = Tp1; ga.Tp[1] = Tp3; ga.tp_bytes = (uint64_t)L.parts_up * P * L.ldt * 4;
         ga.t_part_stride = (int64_t)P * L.ldt; ga.t_parts = L.parts_up; ga.v_tiles = L.parts_up; ga.ksplit = 1;
-        ga.out_split_stride = 0; ga.flags = flags; ga.weights_once = once;
+        ga.out_split_stride = 0; ga.flags = flags; ga.self_clean = 0; ga.weights_once = once;
         ga.flags_status = reinterpret_cast<uint32_t*>(header + 3);
         ga.lr3_rank = r_max < MILO_LR3_MAX_RANK ? r_max : MILO_LR3_MAX_RANK;    // (any weight's compensator may be INT3)
         ga.out = Hbuf; ga.ldo = F; ga.out_rows = nullptr; ga.out_scale = nullptr;
@@ -455,7 +455,8 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         da.T[0] = T1; da.T[1] = T1; da.ldt = L.ldt; da.t_bytes = (uint64_t)P * L.ldt * 2;
         da.Tp[0] = Tp1; da.Tp[1] = Tp1; da.tp_bytes = (uint64_t)L.parts_down * P * L.ldt * 4;
         da.t_part_stride = (int64_t)P * L.ldt; da.t_parts = L.parts_down; da.v_tiles = L.parts_down;
-        da.ksplit = L.splits_down; da.out_split_stride = (int64_t)P * H; da.flags = flags; da.weights_once = once;
+        da.ksplit = L.splits_down; da.out_split_stride = (int64_t)P * H; da.flags = flags + 4 * L.max_tiles32;
+        da.self_clean = 0; da.weights_once = once;
         da.flags_status = reinterpret_cast<uint32_t*>(header + 3);
         da.lr3_rank = r_max < MILO_LR3_MAX_RANK ? r_max : MILO_LR3_MAX_RANK;
         da.out = O; da.ldo = H; da.out_rows = sorted; da.out_scale = topk_weights;
