@@ -678,8 +678,8 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
             // row of this lane's feature in UL: band feature index (NW = 2: the second weight's follow)
             const f16* ulrow = reinterpret_cast<const f16*>(smem) +
                                (int64_t)((NW == 1) ? (64 * wave + 32 * s + i32) : (128 * s + 32 * wave + i32)) * ldu;
-            for (int ks = 0; ks < r; ks += 32) {
-                f16x8 av[2];
+            // One k-step pair (32 ranks): U fragments (they do not depend on T), T fragments.
+            auto load_u = [&](int ks, f16x8 (&av)[2]) {
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const int k0 = ks + 16 * j + 8 * h;
@@ -690,12 +690,8 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                         av[j] = load_row8(urow, k0, r, ualigned);
                     }
                 }
-                if (!waited) {
-                    // every wave asks for itself (no barrier: a wave that is done early goes on early)
-                    if (lane == 0 && early_flag < 1u) wait_flag(a.flags + 4 * by + 1, 1u, a.flags_status);
-                    waited = true;
-                }
-                u32x4 bv[2][MB];
+            };
+            auto load_t = [&](int ks, u32x4 (&bv)[2][MB]) {
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const int k0 = ks + 16 * j + 8 * h;
@@ -706,11 +702,36 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                             tb, (m < ti.rows && k0 < rpad) ? (uint32_t)(((ti.row0 + m) * a.ldt + k0) * 2) : kOobOffset);
                     }
                 }
+            };
+            auto multiply = [&](const f16x8 (&av)[2], const u32x4 (&bv)[2][MB]) {
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb)
                         acc[s][mb] = mfma32(av[j], __builtin_bit_cast(f16x8, bv[j][mb]), acc[s][mb]);
+            };
+            // Two sets of fragments: while one is multiplied the next 32 ranks are already on their
+            // way, so a rank-512 compensator costs about two memory round trips, not sixteen.
+            f16x8 avA[2], avB[2];
+            u32x4 bvA[2][MB], bvB[2][MB];
+            load_u(0, avA);
+            if (!waited) {
+                // every wave asks for itself (no barrier: a wave that is done early goes on early)
+                if (lane == 0 && early_flag < 1u) wait_flag(a.flags + 4 * by + 1, 1u, a.flags_status);
+                waited = true;
+            }
+            load_t(0, bvA);
+            for (int ks = 0; ks < r; ks += 64) {
+                if (ks + 32 < r) {
+                    load_u(ks + 32, avB);
+                    load_t(ks + 32, bvB);
+                }
+                multiply(avA, bvA);
+                if (ks + 64 < r) {
+                    load_u(ks + 64, avA);
+                    load_t(ks + 64, bvA);
+                }
+                if (ks + 32 < r) multiply(avB, bvB);
             }
         }
         if (!waited) {          // (not reached: some rank is positive)

@@ -235,6 +235,86 @@ __global__ __launch_bounds__(kRouteThreads) void order_tiles_kernel(const TileDe
     if (tid == 0) header[1] = n;
 }
 
+// Routing and work list in one launch for decode-sized batches (at most kSmallPairs routed pairs and
+// kSmallExperts experts): with a handful of tokens the two kernels above are all latency, and so is
+// the launch between them.  One workgroup; thread p owns pair p.  The group of an expert starts at
+// the number of pairs with a smaller id, a pair's place inside it is the number of earlier pairs with
+// the same id (both counted from a copy of the ids in LDS), which is the same stable order as
+// route_kernel's.  Tiles are written straight into the final list: tiles of experts with a rank
+// above 32 first, then the others, in expert order (order_tiles_kernel's order for 32-row tiles,
+// the only tile height such a batch gets).
+constexpr int kSmallPairs = 256, kSmallExperts = 256;
+__global__ __launch_bounds__(kSmallPairs) void route_small_kernel(const RouteArgs a, TileDesc* __restrict__ list,
+                                                                  const milo_w3lr_expert* __restrict__ experts) {
+    __shared__ int32_t s_id[kSmallPairs];
+    __shared__ int32_t s_cnt[kSmallExperts], s_start[kSmallExperts], s_tile0[kSmallExperts];
+    __shared__ int32_t s_bad, s_total;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_bad = 0;
+    int id = -1;
+    if (tid < a.P) {
+        id = a.ids[tid];
+        if (id < 0 || id >= a.E) id = -1;
+    }
+    s_id[tid] = id;
+    __syncthreads();
+    if (tid < a.P && id < 0) s_bad = 1;
+    // expert e = tid: its pair count, the pairs before its group, and the tiles before its own in the list
+    if (tid < a.E) {
+        int cnt = 0, less = 0;
+        for (int p = 0; p < a.P; ++p) {
+            const int v = s_id[p];
+            cnt += v == tid;
+            less += v >= 0 && v < tid;
+        }
+        s_cnt[tid] = cnt;
+        s_start[tid] = less;
+    }
+    __syncthreads();
+    if (tid < a.E) {
+        const milo_w3lr_expert& me = experts[tid];
+        const bool low = me.w1.r <= 32 && me.w3.r <= 32 && me.w2.r <= 32;
+        int before = 0, high_tiles = 0;
+        for (int e = 0; e < a.E; ++e) {
+            const int nt = (s_cnt[e] + a.bm - 1) / a.bm;
+            if (nt == 0) continue;
+            const milo_w3lr_expert& ex = experts[e];
+            const bool elow = ex.w1.r <= 32 && ex.w3.r <= 32 && ex.w2.r <= 32;
+            high_tiles += elow ? 0 : nt;
+            if (elow == low && e < tid) before += nt;
+        }
+        s_tile0[tid] = low ? high_tiles + before : before;
+        const int nt = (s_cnt[tid] + a.bm - 1) / a.bm;
+        for (int i = 0; i < nt; ++i) {
+            TileDesc td;
+            td.expert = tid;
+            td.row0 = s_start[tid] + i * a.bm;
+            td.rows = s_cnt[tid] - i * a.bm < a.bm ? s_cnt[tid] - i * a.bm : a.bm;
+            td.pad = 0;
+            list[s_tile0[tid] + i] = td;
+        }
+        if (tid == 0) {
+            int total = 0;
+            for (int e = 0; e < a.E; ++e) total += (s_cnt[e] + a.bm - 1) / a.bm;
+            s_total = total;
+        }
+    }
+    if (tid < a.P && id >= 0) {
+        int before = 0;
+        for (int p = 0; p < tid; ++p) before += s_id[p] == id;
+        const int pos = s_start[id] + before;
+        a.sorted[pos] = tid;
+        a.sorted_token[pos] = tid / a.topk;
+    }
+    for (int i = tid; i < a.n_flags; i += kSmallPairs) a.flags[i] = 0u;
+    __syncthreads();
+    if (tid == 0) {
+        a.header[0] = s_bad ? MILO_ERR_ROUTING : MILO_OK;
+        a.header[1] = s_total;
+        a.header[3] = 0;
+    }
+}
+
 // y[t, h..h+3] = fp16( sum_j O[t*topk + j, h..h+3] ), slots in order, invalid ids skipped.
 __global__ __launch_bounds__(256) void combine_kernel(const f16* __restrict__ O, int splits,
                                                       int64_t split_stride,
@@ -414,12 +494,19 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
     uint32_t* flags = reinterpret_cast<uint32_t*>(ws + L.off_flags);
     ra.flags = flags; ra.n_flags = (int32_t)(2 * 4 * L.max_tiles32);
     ra.max_tiles = L.max_tiles;
-    route_kernel<<<dim3((unsigned)E), dim3(kRouteThreads), 0, stream>>>(ra);
-    int st = launch_status();
-    if (st != MILO_OK) return st;
-    order_tiles_kernel<<<dim3(1), dim3(kRouteThreads), 0, stream>>>(slots, L.max_tiles, L.bm, tiles, header, experts);
-    st = launch_status();
-    if (st != MILO_OK) return st;
+    int st;
+    if (P <= kSmallPairs && E <= kSmallExperts && L.bm == 32) {
+        route_small_kernel<<<dim3(1), dim3(kSmallPairs), 0, stream>>>(ra, tiles, experts);
+        st = launch_status();
+        if (st != MILO_OK) return st;
+    } else {
+        route_kernel<<<dim3((unsigned)E), dim3(kRouteThreads), 0, stream>>>(ra);
+        st = launch_status();
+        if (st != MILO_OK) return st;
+        order_tiles_kernel<<<dim3(1), dim3(kRouteThreads), 0, stream>>>(slots, L.max_tiles, L.bm, tiles, header, experts);
+        st = launch_status();
+        if (st != MILO_OK) return st;
+    }
 
     RowSpace rs;
     rs.tiles = tiles; rs.n_tiles = header + 1; rs.experts = experts;

@@ -116,7 +116,30 @@ def test_out_of_range_expert_id_is_skipped_and_flagged():
 
 @pytest.mark.timeout(900)
 def test_c3_mixtral_layer_full_size():
-    _check(wl.C3)
+    # the full layer at 512 tokens, then the same experts at decode-sized batches (16, 4 and 1 tokens:
+    # routing and work list come from the single-launch kernel, tiles are 32 rows high)
+    import dataclasses
+    o_experts, layer = build_moe(wl.C3)
+    for T in (512, 16, 4, 1):
+        case = dataclasses.replace(wl.C3, T=T)
+        X = wl.moe_activations(case)
+        ids, gates = wl.moe_routing(case)
+        ref = oracle.moe_forward(X, o_experts, ids, gates)
+        Y = _forward(layer, X, ids, gates)
+        assert_close(Y, ref, f"c3 at {T} tokens")
+        assert layer.routing_status() == 0
+        Y2 = _forward(layer, X, ids, gates)
+        assert np.array_equal(Y.view(np.uint16), Y2.view(np.uint16)), "two runs differ"
+
+
+def test_routing_of_small_batches_matches_the_general_kernels():
+    # up to 256 routed pairs the routing and the work list come from one single-workgroup kernel; from
+    # 257 on from the two general kernels: the same layer just below and just above the limit, many
+    # experts empty, several tiles per expert
+    base = wl.MoECase("small_route", T=64, H=128, F=192, E=24, topk=4, seed=23, rank_choices=(0, 8, 40))
+    _check(base)                                              # 256 pairs
+    _check(wl.scaled(base, T=65, name="general_route"))      # 260 pairs
+    _check(wl.scaled(base, T=3, name="three_tokens"))
 
 
 @pytest.mark.timeout(900)
