@@ -214,9 +214,14 @@ int milo_w3lr_gemm_static(const milo_half* X, int64_t M, int64_t N, int64_t K,
  *   MILO_LR_INT3       U and V are not fp16 arrays but the INT3 blobs written by milo_pack_lr3
  *                      (Section 3.2.3, "Quantized low-rank mixture compensators"; the last step of
  *                      Algorithm 1).  Needs r <= MILO_LR3_MAX_RANK and N % 64 == 0.
+ *   MILO_ACT_BF16      (milo_w3lr_gemm_flags only) X, U, V and Y are bfloat16 instead of fp16: the
+ *                      weights are dequantized to bf16 (one rounding each, computed in binary32) and
+ *                      multiplied on the bf16 matrix cores, accumulation stays fp32.  Cannot be
+ *                      combined with MILO_LR_INT3; the MoE call takes fp16 only.
  */
 #define MILO_W3_SYMMETRIC 1u
 #define MILO_LR_INT3 2u
+#define MILO_ACT_BF16 4u
 #define MILO_LR3_MAX_RANK 128
 
 /* One packed weight with its compensator (all device pointers). */

@@ -21,6 +21,7 @@ STATUS_NAMES = {0: "MILO_OK", 1: "MILO_ERR_NULL", 2: "MILO_ERR_SHAPE", 3: "MILO_
 
 W3_SYMMETRIC = 1          # weight flags of include/milo.h
 LR_INT3 = 2
+ACT_BF16 = 4
 
 # every symbol include/milo.h declares
 EXPORTS = ("milo_status_string", "milo_version", "milo_w3_packed_bytes", "milo_pack_w3",
@@ -142,8 +143,10 @@ class PackedWeight:
         return int(self._r) if self._r is not None else int(self.U.shape[1])
 
     def with_compensator(self, U, V):
-        U = _dev(U, torch.float16, "U")
-        V = _dev(V, torch.float16, "V")
+        """fp16 factors, or bf16 ones for calls with bf16 activations (MILO_ACT_BF16)."""
+        dt = torch.bfloat16 if U.dtype == torch.bfloat16 else torch.float16
+        U = _dev(U, dt, "U")
+        V = _dev(V, dt, "V")
         assert U.shape[0] == self.N and V.shape[1] == self.K and U.shape[1] == V.shape[0]
         if U.shape[1] == 0:
             U = V = None
@@ -230,20 +233,24 @@ def gemm_workspace_bytes(M, N, K, r):
 
 def w3lr_gemm(X, pw, out=None, workspace=None):
     """milo_w3lr_gemm: Y = X dequant(Q3)^T + (X V^T) U^T."""
-    X = _dev(X, torch.float16, "X")
+    bf = isinstance(X, torch.Tensor) and X.dtype == torch.bfloat16
+    X = _dev(X, torch.bfloat16 if bf else torch.float16, "X")
     M, K = X.shape
     if K != pw.K:
         raise ValueError("X and weight disagree on K")
+    if pw.U is not None and not (pw.flags & LR_INT3) and pw.U.dtype != X.dtype:
+        raise TypeError("the compensator and the activations must have the same 16-bit type")
     if out is None:
-        out = torch.empty((M, pw.N), dtype=torch.float16, device=X.device)
+        out = torch.empty((M, pw.N), dtype=X.dtype, device=X.device)
     need = gemm_workspace_bytes(M, pw.N, K, pw.r)
     if workspace is None:
         workspace = new_workspace(need, X.device)
-    if pw.flags == 0:
+    flags = pw.flags | (ACT_BF16 if bf else 0)
+    if flags == 0:
         _check(lib().milo_w3lr_gemm(_ptr(X), M, pw.N, K, _ptr(pw.q3), _ptr(pw.U), _ptr(pw.V), pw.r, _ptr(out),
                                     _ptr(workspace), workspace.numel(), _stream()), "milo_w3lr_gemm")
     else:
-        _check(lib().milo_w3lr_gemm_flags(_ptr(X), M, pw.N, K, _ptr(pw.q3), _ptr(pw.U), _ptr(pw.V), pw.r, pw.flags,
+        _check(lib().milo_w3lr_gemm_flags(_ptr(X), M, pw.N, K, _ptr(pw.q3), _ptr(pw.U), _ptr(pw.V), pw.r, flags,
                                           _ptr(out), _ptr(workspace), workspace.numel(), _stream()),
                "milo_w3lr_gemm_flags")
     return out

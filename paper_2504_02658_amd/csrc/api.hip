@@ -65,6 +65,7 @@ static int gemm_splits(int64_t M, int64_t N, int64_t K, int r) {
 }
 
 // Adds the fp32 partial sums of the K splits in split order and rounds once.
+template <bool BF>
 __global__ __launch_bounds__(256) void splitk_sum_kernel(const float* __restrict__ part, int splits,
                                                          int64_t n4, int64_t stride, f16* __restrict__ Y) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -74,6 +75,10 @@ __global__ __launch_bounds__(256) void splitk_sum_kernel(const float* __restrict
         const f32x4 v = *reinterpret_cast<const f32x4*>(part + (int64_t)s * stride + 4 * i);
 #pragma unroll
         for (int e = 0; e < 4; ++e) sum[e] += v[e];
+    }
+    if (BF) {
+        *reinterpret_cast<u32x2*>(Y + 4 * i) = u32x2{pack_bf16(sum[0], sum[1]), pack_bf16(sum[2], sum[3])};
+        return;
     }
     f16x4 o;
 #pragma unroll
@@ -109,7 +114,8 @@ extern "C" int milo_w3lr_gemm_flags(const milo_half* X, int64_t M, int64_t N, in
                                     void* workspace, size_t workspace_bytes, void* stream_) {
     if (!X || !q3 || !Y) return MILO_ERR_NULL;
     if (!gemm_shape_ok(M, N, K)) return MILO_ERR_SHAPE;
-    if (flags & ~(MILO_W3_SYMMETRIC | MILO_LR_INT3)) return MILO_ERR_SHAPE;
+    if (flags & ~(MILO_W3_SYMMETRIC | MILO_LR_INT3 | MILO_ACT_BF16)) return MILO_ERR_SHAPE;
+    if ((flags & MILO_ACT_BF16) && (flags & MILO_LR_INT3) && r > 0) return MILO_ERR_SHAPE;
     if (r < 0 || r > N || r > K) return MILO_ERR_RANK;
     if (r > 0 && (!U || !V)) return MILO_ERR_RANK;
     if (r == 0) flags &= ~MILO_LR_INT3;
@@ -182,8 +188,12 @@ extern "C" int milo_w3lr_gemm_flags(const milo_half* X, int64_t M, int64_t N, in
     const int64_t n4 = M * N / 4;
     const int64_t blocks = (n4 + 255) / 256;
     if (blocks > 0x7fffffff) return MILO_ERR_SHAPE;
-    splitk_sum_kernel<<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(partial, splits, n4, M * N,
-                                                                        reinterpret_cast<f16*>(Y));
+    if (flags & MILO_ACT_BF16)
+        splitk_sum_kernel<true><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(partial, splits, n4, M * N,
+                                                                              reinterpret_cast<f16*>(Y));
+    else
+        splitk_sum_kernel<false><<<dim3((unsigned)blocks), dim3(256), 0, stream>>>(partial, splits, n4, M * N,
+                                                                               reinterpret_cast<f16*>(Y));
     return launch_status();
 }
 

@@ -120,7 +120,8 @@ __device__ __forceinline__ void read_bfrags(const unsigned char* slot, int j16, 
 // Q: V is the INT3 blob of milo_pack_lr3, [16 rblocks x K] in the layout of a weight: a lane loads
 // the unit of rank 16 jb + lane % 16, group 4c + lane / 16, exactly as a streaming wave does for a
 // row block, and converts it with the zero-point-free conversion (the quantizer is symmetric).
-template <int XC, bool Q>
+// BF: activations, V and T are bf16 (MILO_ACT_BF16).
+template <int XC, bool Q, bool BF>
 __device__ __forceinline__ void decode_t_worker(const DecodeArgs& a, unsigned char* smem) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const bool active = wave < kDecTWaves;
@@ -157,7 +158,9 @@ __device__ __forceinline__ void decode_t_worker(const DecodeArgs& a, unsigned ch
                 read_bfrags(xs, j16, q, bfrag);
                 read_bfrags(vs, j16, q, afrag);
 #pragma unroll
-                for (int t = 0; t < 8; ++t) tacc = mfma16(afrag[t], bfrag[t], tacc);
+                for (int t = 0; t < 8; ++t)
+                    tacc = BF ? mfma16_bf16(__builtin_bit_cast(bf16x8, afrag[t]), __builtin_bit_cast(bf16x8, bfrag[t]), tacc)
+                              : mfma16(afrag[t], bfrag[t], tacc);
             }
         }
         __syncthreads();                                    // every wave has read its slots
@@ -174,11 +177,16 @@ __device__ __forceinline__ void decode_t_worker(const DecodeArgs& a, unsigned ch
 #pragma unroll
                 for (int x = 0; x < 4; ++x) sum[x] += part[p][x];
             // element v of lane l = rank 16*jb + 4*(l/16) + v, token l%16
-            f16x4 o;
+            u32x2 ob;
+            if (BF) {
+                ob = u32x2{pack_bf16(sum[0], sum[1]), pack_bf16(sum[2], sum[3])};
+            } else {
+                f16x4 o;
 #pragma unroll
-            for (int x = 0; x < 4; ++x) o[x] = (f16)sum[x];
-            buf_store8_coherent(tb, (uint32_t)(((h * 16 + j16) * a.ldt + 16 * jb + 4 * q) * 2),
-                                __builtin_bit_cast(u32x2, o));
+                for (int x = 0; x < 4; ++x) o[x] = (f16)sum[x];
+                ob = __builtin_bit_cast(u32x2, o);
+            }
+            buf_store8_coherent(tb, (uint32_t)(((h * 16 + j16) * a.ldt + 16 * jb + 4 * q) * 2), ob);
         }
         __syncthreads();                                    // red is read before the slots are refilled
     }
@@ -223,7 +231,7 @@ constexpr int kDecLdsTotal = kDecTLds + kDecTFrags * 1024;      // 160 KB, all a
 //   unit (j, b>0):  2 (R - 1) + XC         (the rest of chunk j, X(j+1), the first b units of chunk j + 1)
 //   last chunk:     2 (R - 1 - b)          (nothing is requested any more)
 // For K up to 4096 a wave has a single chunk and everything is requested up front.
-template <int R, int XC, bool SYM>
+template <int R, int XC, bool SYM, bool BF>
 struct DecodeStream {
     const W3Buf& wb;
     BufRsrc xb;
@@ -264,7 +272,12 @@ struct DecodeStream {
                 }
             }
             pin_unit_params(u[b]);          // nothing is computed from this unit before the wait
-            dequant_unit_steps<SYM>(u[b], [&](int t, f16x8 frag) { acc[b] = mfma16(frag, bfrag[t], acc[b]); });
+            if (BF)
+                dequant_unit_steps_bf16(u[b], [&](int t, bf16x8 frag) {
+                    acc[b] = mfma16_bf16(frag, __builtin_bit_cast(bf16x8, bfrag[t]), acc[b]);
+                });
+            else
+                dequant_unit_steps<SYM>(u[b], [&](int t, f16x8 frag) { acc[b] = mfma16(frag, bfrag[t], acc[b]); });
             if (!LAST) {
                 __builtin_amdgcn_sched_barrier(0);
                 issue_w(j + 1, rb0 + b, u[b]);
@@ -302,14 +315,14 @@ __device__ __forceinline__ void scatter_u_rank(const uint32_t (&w)[32], unsigned
 
 // SYM: the weight blob is symmetric (zero-point-free conversion).  Q (with LR == 1): the compensator
 // is the pair of INT3 blobs of milo_pack_lr3.
-template <int R, int LR, int XC, bool SYM, bool Q>
+template <int R, int LR, int XC, bool SYM, bool Q, bool BF>
 __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int nworkers = LR > 0 ? a.nt : 0;
     if (LR > 0 && (int)blockIdx.x < nworkers) {
-        decode_t_worker<XC, Q>(a, smem);
+        decode_t_worker<XC, Q, BF>(a, smem);
     } else {
         const int j16 = lane & 15, q = lane >> 4;
         const int M = a.M;
@@ -327,7 +340,7 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
         bool t_ready = false;
 
         const int wave_s = __builtin_amdgcn_readfirstlane(wave);        // known to be uniform
-        DecodeStream<R, XC, SYM> st{wb,
+        DecodeStream<R, XC, SYM, BF> st{wb,
                                make_rsrc(a.X, (uint64_t)M * K * 2u),
                                XCopy(lane, K),
                                smem + wave_s * kDecSlotBytes,
@@ -442,8 +455,10 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
                     for (int h = 0; h < a.kh; ++h) {
 #pragma unroll 1
                         for (int i = 0; i < ksu; ++i, ++f)
-                            sum = mfma16(__builtin_bit_cast(f16x8, ulds[(b * kDecKS + i) * 64 + lane]),
-                                         __builtin_bit_cast(f16x8, tbuf[f * 64 + lane]), sum);
+                            sum = BF ? mfma16_bf16(__builtin_bit_cast(bf16x8, ulds[(b * kDecKS + i) * 64 + lane]),
+                                                   __builtin_bit_cast(bf16x8, tbuf[f * 64 + lane]), sum)
+                                     : mfma16(__builtin_bit_cast(f16x8, ulds[(b * kDecKS + i) * 64 + lane]),
+                                              __builtin_bit_cast(f16x8, tbuf[f * 64 + lane]), sum);
                     }
                 } else if (LR == 2) {
                     const int64_t nrow = (int64_t)nb + j16;
@@ -455,7 +470,8 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
                             const f16x8 bv = __builtin_bit_cast(
                                 f16x8, buf_load16_coherent(tb, k0 < a.ldt ? (uint32_t)(((h * 16 + j16) * a.ldt + k0) * 2)
                                                                           : kOobOffset));
-                            sum = mfma16(av, bv, sum);
+                            sum = BF ? mfma16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv), sum)
+                                     : mfma16(av, bv, sum);
                         }
                     }
                 }
@@ -467,10 +483,16 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
                 asm volatile("" : "+s"(n_out), "+s"(m_out));
                 const uint32_t n = nb + 4u * q;
                 if ((uint32_t)j16 < m_out && n < n_out) {
-                    f16x4 o;
+                    u32x2 ob;
+                    if (BF) {
+                        ob = u32x2{pack_bf16(sum[0], sum[1]), pack_bf16(sum[2], sum[3])};
+                    } else {
+                        f16x4 o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (f16)sum[e];
-                    *reinterpret_cast<f16x4*>(a.Y + ((uint64_t)j16 * n_out + n)) = o;
+                        for (int e = 0; e < 4; ++e) o[e] = (f16)sum[e];
+                        ob = __builtin_bit_cast(u32x2, o);
+                    }
+                    *reinterpret_cast<u32x2*>(a.Y + ((uint64_t)j16 * n_out + n)) = ob;
                 }
             }
             if (turn + 1 < turns) __syncthreads();      // slots, U and the partial sums are reused
@@ -526,12 +548,12 @@ typedef void (*DecodeKernel)(const DecodeArgs);
 template <int R, int LR, bool SYM, bool Q>
 static DecodeKernel decode_variant_xc(int xc) {
     if constexpr (LR == 2) {
-        return w3lr_decode_kernel<R, LR, 8, false, false>;
+        return w3lr_decode_kernel<R, LR, 8, false, false, false>;
     } else {
-        if (xc == 1) return w3lr_decode_kernel<R, LR, 1, SYM, Q>;
-        if (xc == 2) return w3lr_decode_kernel<R, LR, 2, SYM, Q>;
-        if (xc == 4) return w3lr_decode_kernel<R, LR, 4, SYM, Q>;
-        return w3lr_decode_kernel<R, LR, 8, SYM, Q>;
+        if (xc == 1) return w3lr_decode_kernel<R, LR, 1, SYM, Q, false>;
+        if (xc == 2) return w3lr_decode_kernel<R, LR, 2, SYM, Q, false>;
+        if (xc == 4) return w3lr_decode_kernel<R, LR, 4, SYM, Q, false>;
+        return w3lr_decode_kernel<R, LR, 8, SYM, Q, false>;
     }
 }
 template <int LR, bool SYM, bool Q>
@@ -544,7 +566,15 @@ static DecodeKernel decode_variant_r(int R, int xc) {
         return decode_variant_xc<1, LR, SYM, Q>(xc);
     }
 }
-static DecodeKernel decode_variant(int R, int lr, int xc, bool sym, bool q) {
+// bf16 activations: R x LR with all eight activation copies (no specialisation by M)
+template <int LR>
+static DecodeKernel decode_variant_bf(int R) {
+    if (R == 4) return w3lr_decode_kernel<4, LR, 8, false, false, true>;
+    if (R == 2) return w3lr_decode_kernel<2, LR, 8, false, false, true>;
+    return w3lr_decode_kernel<1, LR, 8, false, false, true>;
+}
+static DecodeKernel decode_variant(int R, int lr, int xc, bool sym, bool q, bool bf = false) {
+    if (bf) return q ? nullptr : lr == 0 ? decode_variant_bf<0>(R) : lr == 1 ? decode_variant_bf<1>(R) : decode_variant_bf<2>(R);
     if (q) return lr == 1 ? decode_variant_r<1, false, true>(R, xc) : nullptr;
     if (sym && R == 4 && lr < 2) return lr == 0 ? decode_variant_r<0, true, false>(R, xc) : decode_variant_r<1, true, false>(R, xc);
     if (lr == 0) return decode_variant_r<0, false, false>(R, xc);
@@ -562,8 +592,8 @@ static int decode_capacity() {
         for (int R = 1; R <= 4; R *= 2)
             for (int lr = 0; lr < 3; ++lr)
                 for (int xc = 1; xc <= 8; xc *= 2)
-                    for (int v = 0; v < 3; ++v) {       // plain, symmetric, INT3 compensator
-                        const DecodeKernel k = decode_variant(R, lr, xc, v == 1, v == 2);
+                    for (int v = 0; v < 4; ++v) {       // plain, symmetric, INT3 compensator, bf16
+                        const DecodeKernel k = decode_variant(R, lr, xc, v == 1, v == 2, v == 3);
                         if (k && hipFuncSetAttribute(reinterpret_cast<const void*>(k),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize,
                                                      kDecLdsTotal) != hipSuccess)
@@ -646,7 +676,9 @@ int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream) {
     const bool q = r > 0 && (a.w.flags & MILO_LR_INT3) != 0;
     // an INT3 compensator only runs on the staged path: its T fragments must fit the workgroup's LDS
     if (q && lr != 1) return MILO_ERR_SHAPE;
-    const DecodeKernel kernel = decode_variant(R, lr, xc, (a.w.flags & MILO_W3_SYMMETRIC) != 0, q);
+    const bool bf = (a.w.flags & MILO_ACT_BF16) != 0;
+    if (bf && q) return MILO_ERR_SHAPE;
+    const DecodeKernel kernel = decode_variant(R, lr, xc, (a.w.flags & MILO_W3_SYMMETRIC) != 0, q, bf);
     if (!kernel) return MILO_ERR_HIP;
     kernel<<<dim3((unsigned)grid), dim3(kDecThreads), lr == 1 ? kDecLdsTotal : kDecLdsBytes, stream>>>(a);
     return launch_status();

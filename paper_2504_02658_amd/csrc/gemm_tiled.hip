@@ -87,7 +87,7 @@ __device__ __forceinline__ void wait_flag(const uint32_t* flag, uint32_t target,
 // lane and chunk).  NW = 1: wave w, stream s take ranks 64w + 32s ..; NW = 2: stream s is weight s,
 // ranks 32w ..; larger ranks take further passes.  T is written with device-coherent stores and
 // published through the tile's flag.
-template <int NW, int MB>
+template <int NW, int MB, bool BF>
 __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& ti, unsigned char* smem, int part,
                                             uint32_t by) {
     constexpr int BM = 32 * MB;
@@ -172,8 +172,15 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
             for (int mb = 0; mb < MBT; ++mb) {
                 const f16x8 b = __builtin_bit_cast(
                     f16x8, *reinterpret_cast<const u32x4*>(xs + (blk0 + mb) * 32 * 256 + (((8 * h + t) ^ sx) << 4)));
-                if (active[0]) acc[0][mb] = mfma32(a0, b, acc[0][mb]);
-                if (active[1]) acc[1][mb] = mfma32(a1, b, acc[1][mb]);
+                if (BF) {       // (bf16 activations: V is bf16 as well, same bits in the fragments)
+                    if (active[0])
+                        acc[0][mb] = mfma32_bf16(__builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, b), acc[0][mb]);
+                    if (active[1])
+                        acc[1][mb] = mfma32_bf16(__builtin_bit_cast(bf16x8, a1), __builtin_bit_cast(bf16x8, b), acc[1][mb]);
+                } else {
+                    if (active[0]) acc[0][mb] = mfma32(a0, b, acc[0][mb]);
+                    if (active[1]) acc[1][mb] = mfma32(a1, b, acc[1][mb]);
+                }
             }
         };
 
@@ -335,10 +342,16 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
                 }
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
-                    f16x4 o;
+                    u32x2 ob;
+                    if (BF) {
+                        ob = u32x2{pack_bf16(sum[u][0], sum[u][1]), pack_bf16(sum[u][2], sum[u][3])};
+                    } else {
+                        f16x4 o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (f16)sum[u][e];
-                    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), tb,
+                        for (int e = 0; e < 4; ++e) o[e] = (f16)sum[u][e];
+                        ob = __builtin_bit_cast(u32x2, o);
+                    }
+                    __builtin_amdgcn_raw_buffer_store_b64(ob, tb,
                                                           at[u] != kOobOffset ? at[u] * 2u : kOobOffset, 0, 17);
                 }
             }
@@ -367,10 +380,11 @@ __device__ __forceinline__ void gather16(u32x2 (&o)[4]) {
     }
 }
 
-// SYM: every weight of the launch is a symmetric blob (MILO_W3_SYMMETRIC): conversion without
-// zero-point arithmetic.
-template <int NW, int MB, int EPI, bool SYM = false>
+// MODE 1: every weight of the launch is a symmetric blob (MILO_W3_SYMMETRIC): conversion without
+// zero-point arithmetic.  MODE 2: bf16 activations, compensator and output (MILO_ACT_BF16).
+template <int NW, int MB, int EPI, int MODE = 0>
 __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const TiledArgs a) {
+    constexpr bool SYM = MODE == 1, BF = MODE == 2;
     constexpr int BM = 32 * MB;
     constexpr int BN = (NW == 1) ? 256 : 128;
     constexpr int STAGE = BM * 256;              // bytes of one X stage: BM rows x 128 columns
@@ -440,7 +454,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     const bool any_rank = ti.w[0].r > 0 || ti.w[1].r > 0;
     if ((int)bx < a.v_tiles) {
         // forms one part of T = X V^T for this M-tile (see v_tile_body)
-        if (any_rank && bz == 0) v_tile_body<NW, MB>(a, ti, smem, (int)bx, by);
+        if (any_rank && bz == 0) v_tile_body<NW, MB, BF>(a, ti, smem, (int)bx, by);
         return;
     }
 
@@ -576,7 +590,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
             f16x8 bc[MBU], bn[MBU];
 #pragma unroll
             for (int mb = 0; mb < MBU; ++mb) bc[mb] = bfrag(mb, 0);
-            dequant_units2_steps<SYM>(ru[0], ru[1], [&](int t, f16x8 a0, f16x8 a1) {
+            auto step = [&](int t, auto a0, auto a1) {
                 between(t);
                 if (t < 7) {
 #pragma unroll
@@ -584,14 +598,21 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                 }
 #pragma unroll
                 for (int mb = 0; mb < MBU; ++mb) {
-                    acc[0][mb] = mfma32(a0, bc[mb], acc[0][mb]);
-                    acc[1][mb] = mfma32(a1, bc[mb], acc[1][mb]);
+                    if constexpr (BF) {
+                        acc[0][mb] = mfma32_bf16(a0, __builtin_bit_cast(bf16x8, bc[mb]), acc[0][mb]);
+                        acc[1][mb] = mfma32_bf16(a1, __builtin_bit_cast(bf16x8, bc[mb]), acc[1][mb]);
+                    } else {
+                        acc[0][mb] = mfma32(a0, bc[mb], acc[0][mb]);
+                        acc[1][mb] = mfma32(a1, bc[mb], acc[1][mb]);
+                    }
                 }
                 if (t < 7) {
 #pragma unroll
                     for (int mb = 0; mb < MBU; ++mb) bc[mb] = bn[mb];
                 }
-            });
+            };
+            if constexpr (BF) dequant_units2_steps_bf16(ru[0], ru[1], step);
+            else dequant_units2_steps<SYM>(ru[0], ru[1], step);
         };
 
         // PD-deep pipeline: chunk c lives in ring slot c % PD (registers for the weights, LDS stage
@@ -708,7 +729,9 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                 for (int j = 0; j < 2; ++j)
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb)
-                        acc[s][mb] = mfma32(av[j], __builtin_bit_cast(f16x8, bv[j][mb]), acc[s][mb]);
+                        acc[s][mb] = BF ? mfma32_bf16(__builtin_bit_cast(bf16x8, av[j]), __builtin_bit_cast(bf16x8, bv[j][mb]),
+                                                      acc[s][mb])
+                                        : mfma32(av[j], __builtin_bit_cast(f16x8, bv[j][mb]), acc[s][mb]);
             };
             // Two sets of fragments: while one is multiplied the next 32 ranks are already on their
             // way, so a rank-512 compensator costs about two memory round trips, not sixteen.
@@ -807,11 +830,16 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
                     u32x2 o[4];
 #pragma unroll
                     for (int vq = 0; vq < 4; ++vq) {
-                        f16x4 v;
+                        if (BF) {
+                            o[vq] = u32x2{pack_bf16(acc[s][mb][4 * vq], acc[s][mb][4 * vq + 1]),
+                                          pack_bf16(acc[s][mb][4 * vq + 2], acc[s][mb][4 * vq + 3])};
+                        } else {
+                            f16x4 v;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            v[e] = (f16)(EPI == EPI_STORE ? acc[s][mb][4 * vq + e] : sc * acc[s][mb][4 * vq + e]);
-                        o[vq] = __builtin_bit_cast(u32x2, v);
+                            for (int e = 0; e < 4; ++e)
+                                v[e] = (f16)(EPI == EPI_STORE ? acc[s][mb][4 * vq + e] : sc * acc[s][mb][4 * vq + e]);
+                            o[vq] = __builtin_bit_cast(u32x2, v);
+                        }
                     }
                     store16(orow, nb, o);
                 }
@@ -820,7 +848,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     }
 }
 
-template <int NW, int MB, int EPI, bool SYM = false>
+template <int NW, int MB, int EPI, int MODE = 0>
 static int launch_one(const TiledArgs& a, dim3 grid, hipStream_t stream) {
     constexpr int lds_stages = (MB == 4 ? 2 : kTiledStages) * 32 * MB * 256;
     // room for the U array of an INT3 compensator: 256 band features x (pad16(rank) + 8) fp16
@@ -831,22 +859,22 @@ static int launch_one(const TiledArgs& a, dim3 grid, hipStream_t stream) {
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MILO_ERR_HIP;
         if (!raised[dev]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(w3lr_tiled_kernel<NW, MB, EPI, SYM>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(w3lr_tiled_kernel<NW, MB, EPI, MODE>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024) != hipSuccess)
                 return MILO_ERR_HIP;
             raised[dev] = true;
         }
     }
-    w3lr_tiled_kernel<NW, MB, EPI, SYM><<<grid, dim3(kTiledThreads), lds, stream>>>(a);
+    w3lr_tiled_kernel<NW, MB, EPI, MODE><<<grid, dim3(kTiledThreads), lds, stream>>>(a);
     return launch_status();
 }
 
-template <int NW, int EPI, bool SYM = false>
+template <int NW, int EPI, int MODE = 0>
 static int launch_tiled_mb(const TiledArgs& a, int mb, dim3 grid, hipStream_t stream) {
     switch (mb) {
-        case 1: return launch_one<NW, 1, EPI, SYM>(a, grid, stream);
-        case 2: return launch_one<NW, 2, EPI, SYM>(a, grid, stream);
-        case 4: return launch_one<NW, 4, EPI, SYM>(a, grid, stream);
+        case 1: return launch_one<NW, 1, EPI, MODE>(a, grid, stream);
+        case 2: return launch_one<NW, 2, EPI, MODE>(a, grid, stream);
+        case 4: return launch_one<NW, 4, EPI, MODE>(a, grid, stream);
         default: return MILO_ERR_SHAPE;
     }
 }
@@ -868,7 +896,8 @@ int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipSt
     if (nw == 2 && epi == EPI_SWIGLU) return launch_tiled_mb<2, EPI_SWIGLU>(b, mb, grid, stream);
     if (nw == 1 && epi == EPI_STORE) {
         // the single linear knows its one weight: a symmetric blob takes the zero-point-free conversion
-        if (!a.rs.tiles && (a.rs.w[0].flags & MILO_W3_SYMMETRIC)) return launch_tiled_mb<1, EPI_STORE, true>(b, mb, grid, stream);
+        if (!a.rs.tiles && (a.rs.w[0].flags & MILO_ACT_BF16)) return launch_tiled_mb<1, EPI_STORE, 2>(b, mb, grid, stream);
+        if (!a.rs.tiles && (a.rs.w[0].flags & MILO_W3_SYMMETRIC)) return launch_tiled_mb<1, EPI_STORE, 1>(b, mb, grid, stream);
         return launch_tiled_mb<1, EPI_STORE>(b, mb, grid, stream);
     }
     if (nw == 1 && epi == EPI_SCALE_SCATTER)

@@ -352,6 +352,130 @@ __device__ __forceinline__ void dequant_units2_steps(const RawUnit& r0, const Ra
     on_step(7, unit_frag(w0, 7), unit_frag(w1, 7));
 }
 
+// ---------------------------------------------------------------------------------------------
+// bf16 variant of the conversion (activations, compensator and output in bf16; Section 3.3 names
+// FP16 only, this is the same idea on the other 16-bit format).  bf16 has seven mantissa bits, so a
+// 3-bit field reads as an integer in place only at bit 0 (exponent pattern 0x4300: 128 + e) and at
+// bit 3 (0x4180: 16 + e); the fields at bits 6, 9 and 12 are shifted down first.  bf16 has no packed
+// arithmetic here, and its eight significant bits could not hold s * (e - z) anyway: a bf16 is the
+// upper half of a binary32, so each value is widened with a shift or a mask, w = fma(B + e, s,
+// -(B + z) s) is formed in binary32 (the product is exact, the constant is exact for integer
+// zero-points), and two results are rounded to a bf16 pair with one conversion: one rounding per
+// weight, as in the fp16 path.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+// (B + e_lo, B + e_hi) as a bf16 pair in `h`  ->  bf16 pair of s * (e - z); c = -(B + z) * s
+__device__ __forceinline__ uint32_t bf16_pair(uint32_t h, float s, float c) {
+    const float lo = __builtin_bit_cast(float, h << 16), hi = __builtin_bit_cast(float, h & 0xffff0000u);
+    return pack_bf16(__builtin_fmaf(lo, s, c), __builtin_fmaf(hi, s, c));
+}
+template <typename OnStep>
+__device__ __forceinline__ void dequant_unit_steps_bf16(const RawUnit& ru, OnStep&& on_step) {
+    const float s = (float)f16_bits(ru.sz);
+    const float z = (float)f16_bits(ru.sz >> 16);
+    const float c0 = -(128.0f + z) * s, c3 = -(16.0f + z) * s;
+    const uint32_t B0 = in_vgpr(0x43004300u), B3 = in_vgpr(0x41804180u);
+    const uint32_t M0 = in_sgpr(0x00070007u), M3 = in_sgpr(0x00380038u);
+    const uint32_t d[6] = {ru.a.x, ru.a.y, ru.a.z, ru.a.w, ru.b.x, ru.b.y};
+    uint32_t w[32];
+    int next = 0;
+#pragma unroll
+    for (int j = 0; j < 6; ++j) {
+        const uint32_t s6 = d[j] >> 6, s12 = d[j] >> 12;
+        w[5 * j + 0] = bf16_pair(and_or(d[j], M0, B0), s, c0);
+        w[5 * j + 1] = bf16_pair(and_or(d[j], M3, B3), s, c3);
+        w[5 * j + 2] = bf16_pair(and_or(s6, M0, B0), s, c0);
+        w[5 * j + 3] = bf16_pair(and_or(s6, M3, B3), s, c3);
+        w[5 * j + 4] = bf16_pair(and_or(s12, M0, B0), s, c0);
+#pragma unroll
+        for (int t = 0; t < 7; ++t) {
+            if (t == next && 4 * t + 3 <= 5 * j + 4) {
+                const u32x4 v = {w[4 * t + 0], w[4 * t + 1], w[4 * t + 2], w[4 * t + 3]};
+                on_step(t, __builtin_bit_cast(bf16x8, v));
+                ++next;
+            }
+        }
+    }
+    // pairs 30 and 31: bits 15 / 31 of words 0..2 and 3..5 carry bits 0, 1, 2
+    const uint32_t S0 = in_sgpr(0x00010001u), S1 = in_sgpr(0x00020002u), S2 = in_sgpr(0x00040004u);
+    uint32_t t0 = and_or(d[0] >> 15, S0, B0), t1 = and_or(d[3] >> 15, S0, B0);
+    t0 = and_or(d[1] >> 14, S1, t0);
+    t1 = and_or(d[4] >> 14, S1, t1);
+    t0 = and_or(d[2] >> 13, S2, t0);
+    t1 = and_or(d[5] >> 13, S2, t1);
+    w[30] = bf16_pair(t0, s, c0);
+    w[31] = bf16_pair(t1, s, c0);
+    const u32x4 v = {w[28], w[29], w[30], w[31]};
+    on_step(7, __builtin_bit_cast(bf16x8, v));
+}
+// Two units in lock step (the tiled kernel's two weight streams).  on_step(t, frag0, frag1).
+template <typename OnStep>
+__device__ __forceinline__ void dequant_units2_steps_bf16(const RawUnit& r0, const RawUnit& r1, OnStep&& on_step) {
+    const float s0 = (float)f16_bits(r0.sz), z0 = (float)f16_bits(r0.sz >> 16);
+    const float s1 = (float)f16_bits(r1.sz), z1 = (float)f16_bits(r1.sz >> 16);
+    const float c00 = -(128.0f + z0) * s0, c03 = -(16.0f + z0) * s0;
+    const float c10 = -(128.0f + z1) * s1, c13 = -(16.0f + z1) * s1;
+    const uint32_t B0 = in_vgpr(0x43004300u), B3 = in_vgpr(0x41804180u);
+    const uint32_t M0 = in_sgpr(0x00070007u), M3 = in_sgpr(0x00380038u);
+    const uint32_t d0[6] = {r0.a.x, r0.a.y, r0.a.z, r0.a.w, r0.b.x, r0.b.y};
+    const uint32_t d1[6] = {r1.a.x, r1.a.y, r1.a.z, r1.a.w, r1.b.x, r1.b.y};
+    uint32_t w0[32], w1[32];
+    int next = 0;
+#pragma unroll
+    for (int j = 0; j < 6; ++j) {
+        const uint32_t a6 = d0[j] >> 6, a12 = d0[j] >> 12, b6 = d1[j] >> 6, b12 = d1[j] >> 12;
+        w0[5 * j + 0] = bf16_pair(and_or(d0[j], M0, B0), s0, c00);
+        w1[5 * j + 0] = bf16_pair(and_or(d1[j], M0, B0), s1, c10);
+        w0[5 * j + 1] = bf16_pair(and_or(d0[j], M3, B3), s0, c03);
+        w1[5 * j + 1] = bf16_pair(and_or(d1[j], M3, B3), s1, c13);
+        w0[5 * j + 2] = bf16_pair(and_or(a6, M0, B0), s0, c00);
+        w1[5 * j + 2] = bf16_pair(and_or(b6, M0, B0), s1, c10);
+        w0[5 * j + 3] = bf16_pair(and_or(a6, M3, B3), s0, c03);
+        w1[5 * j + 3] = bf16_pair(and_or(b6, M3, B3), s1, c13);
+        w0[5 * j + 4] = bf16_pair(and_or(a12, M0, B0), s0, c00);
+        w1[5 * j + 4] = bf16_pair(and_or(b12, M0, B0), s1, c10);
+#pragma unroll
+        for (int t = 0; t < 7; ++t) {
+            if (t == next && 4 * t + 3 <= 5 * j + 4) {
+                const u32x4 v0 = {w0[4 * t + 0], w0[4 * t + 1], w0[4 * t + 2], w0[4 * t + 3]};
+                const u32x4 v1 = {w1[4 * t + 0], w1[4 * t + 1], w1[4 * t + 2], w1[4 * t + 3]};
+                on_step(t, __builtin_bit_cast(bf16x8, v0), __builtin_bit_cast(bf16x8, v1));
+                ++next;
+            }
+        }
+    }
+    const uint32_t S0 = in_sgpr(0x00010001u), S1 = in_sgpr(0x00020002u), S2 = in_sgpr(0x00040004u);
+    uint32_t p0 = and_or(d0[0] >> 15, S0, B0), q0 = and_or(d0[3] >> 15, S0, B0);
+    uint32_t p1 = and_or(d1[0] >> 15, S0, B0), q1 = and_or(d1[3] >> 15, S0, B0);
+    p0 = and_or(d0[1] >> 14, S1, p0);
+    q0 = and_or(d0[4] >> 14, S1, q0);
+    p1 = and_or(d1[1] >> 14, S1, p1);
+    q1 = and_or(d1[4] >> 14, S1, q1);
+    p0 = and_or(d0[2] >> 13, S2, p0);
+    q0 = and_or(d0[5] >> 13, S2, q0);
+    p1 = and_or(d1[2] >> 13, S2, p1);
+    q1 = and_or(d1[5] >> 13, S2, q1);
+    w0[30] = bf16_pair(p0, s0, c00);
+    w0[31] = bf16_pair(q0, s0, c00);
+    w1[30] = bf16_pair(p1, s1, c10);
+    w1[31] = bf16_pair(q1, s1, c10);
+    const u32x4 v0 = {w0[28], w0[29], w0[30], w0[31]};
+    const u32x4 v1 = {w1[28], w1[29], w1[30], w1[31]};
+    on_step(7, __builtin_bit_cast(bf16x8, v0), __builtin_bit_cast(bf16x8, v1));
+}
+__device__ __forceinline__ f32x4 mfma16_bf16(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma32_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
 // All 32 pairs of a unit at once (for the dense dequantization kernel).
 template <bool SYM = false>
 __device__ __forceinline__ void dequant_unit(const RawUnit& ru, uint32_t (&w)[32]) {

@@ -332,3 +332,59 @@ def test_symmetric_flag_changes_nothing_but_the_kernel(M, N, K, r):
     plain = api.PackedWeight(pw.N, pw.K, pw.q3, pw.U, pw.V, flags=0)
     a, b = _run(X, pw), _run(X, plain)
     assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
+# ------------------------------------------------------------------ bf16 activations (MILO_ACT_BF16)
+
+# Tolerance for the bf16 variant, from its arithmetic: every dequantized weight is rounded once to
+# bf16 (relative 2^-9 at most, 2^-9 / sqrt(12) rms; the errors of the K products are independent, so
+# they appear undiminished in the relative error of a sum), the output once more, T = X V^T once in
+# between: about 1e-3 rms in all, bounded here by 4e-3; single elements by 3e-2 of the largest output.
+BF16_REL_FRO_TOL, BF16_MAX_ABS_TOL = 4e-3, 3e-2
+
+
+def _to_bf16(x):
+    import torch
+    return torch.from_numpy(np.asarray(x, np.float32)).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("M,N,K,r", [(16, 1024, 4096, 32), (1, 272, 1408, 0), (5, 528, 14336, 64), (7, 256, 1408, 20),
+                                     (96, 512, 1024, 24), (512, 1024, 4096, 64), (40, 4096, 14336, 16), (130, 272, 832, 136)])
+def test_bf16_activations(M, N, K, r):
+    import torch
+    from paper_2504_02658_amd import api
+    case = wl.LinearCase("t", M=M, N=N, K=K, r=r, seed=700 + M + r)
+    X, W = wl.linear_inputs(case)
+    ow = oracle_weight(W, r, seed=case.seed)
+    Xb, Ub, Vb = _to_bf16(X), _to_bf16(ow["U"]), _to_bf16(ow["V"])
+    ref = oracle.w3lr_linear(Xb.float().numpy(), ow["codes"], ow["scales"], ow["zeros"],
+                             Ub.float().numpy(), Vb.float().numpy())
+    pw = gpu_weight(W, dict(ow, U=np.zeros((N, 0), np.float16)))
+    if r:
+        pw = pw.with_compensator(Ub.cuda(), Vb.cuda())
+    Y = api.w3lr_gemm(Xb.cuda(), pw)
+    assert Y.dtype == torch.bfloat16
+    Yf = Y.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(Yf))
+    rel = np.linalg.norm(Yf - ref) / np.linalg.norm(ref)
+    mx = np.max(np.abs(Yf - ref)) / np.max(np.abs(ref))
+    assert rel <= BF16_REL_FRO_TOL and mx <= BF16_MAX_ABS_TOL, (rel, mx)
+    Y2 = api.w3lr_gemm(Xb.cuda(), pw)
+    assert torch.equal(Y, Y2)
+
+
+def test_bf16_integer_case_is_exact():
+    # small integers are exact in bf16 too: codes 0..7, scale 1, zero 0, activations in {-1, 0, 1}
+    import torch
+    from paper_2504_02658_amd import api
+    rng = np.random.default_rng(4)
+    N, K = 64, 256
+    q = rng.integers(0, 8, size=(N, K), dtype=np.uint8)
+    s = np.ones((N, K // 64), np.float16)
+    z = np.zeros((N, K // 64), np.float16)
+    pw = api.PackedWeight(N, K, torch.from_numpy(oracle.pack_w3(q, s, z)).cuda())
+    for M in (8, 48):
+        X = rng.integers(-1, 2, size=(M, K)).astype(np.float32)
+        Y = api.w3lr_gemm(_to_bf16(X).cuda(), pw).float().cpu().numpy().astype(np.float64)
+        ref = oracle.w3lr_linear(X, q, s, z)
+        assert np.array_equal(Y, np.asarray(_to_bf16(ref).float().numpy(), np.float64))
