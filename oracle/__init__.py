@@ -21,3 +21,5 @@ from .linear import w3lr_linear, linear_from_dense        # noqa: F401
 from .compensator import (svd_compensator, randomized_svd_compensator,  # noqa: F401
                           quantize_compensator, dequantize_compensator)
 from .moe import moe_forward, silu                        # noqa: F401
+from .compress import (milo_compress, hqq_zero_points, shrink_lp, fixed_scales,  # noqa: F401
+                       quantize_with, stop_rule)
