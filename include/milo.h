@@ -186,6 +186,58 @@ int milo_pack_lr3(const float* U, const float* V, int64_t N, int64_t K, int r,
                   void* u3, void* v3, void* stream);
 
 /*
+ * The MiLo compression loop (Algorithm 1) for one weight: alternates a quantization step and a
+ * compensation step until the error stops improving, and writes the Q3 blob and the compensator.
+ *   quantization step (Section 3.2, Eq. update_We, Eq. update_z): target R = W - U V, scales fixed to
+ *       the round-to-nearest scales of W (fp16((max - min) / 7) per group of 64, as milo_pack_w3),
+ *       `hqq_iters` half-quadratic updates of the real-valued zero-points with the l_p shrinkage
+ *       operator (norm `p` < 1, penalty `beta` growing by the factor `kappa` per update);
+ *   compensation step (Eq. UV): rank-r truncated SVD of E = W - W_dq, U = U^ S^(1/2), V = S^(1/2) V^.
+ *       The leading triplets come from a block subspace iteration with r + 8 vectors, warm-started
+ *       from the previous iteration's right singular vectors: one round per iteration plus
+ *       `power_iters` extra rounds in the first iteration (which starts from a basis seeded by `seed`)
+ *       and `refine_iters` extra rounds in every later one.  Close to, not equal to, the exact
+ *       truncation: with the defaults of the Python binding (2 and 0) eps_t ends within about one
+ *       percent of the exact SVD's on small matrices and closer on large ones; more rounds close the gap;
+ *   error eps_t = ||W - W_dq - U V||_F (Eq. epsilon), copied to the host after every iteration; the
+ *       loop ends after `iters` iterations or when (mean of the last three errors so far) has
+ *       improved by less than the fraction `tol` over the same mean one iteration earlier
+ *       (Eq. stop_condition; a negative tol disables the rule).
+ * Output: q3 = codes of W - U V with those scales and the zero-points rounded to fp16 (any finite
+ * fp16, not integers), in the layout of milo_pack_w3; U [N x r], V [r x K] fp32 row-major (round them
+ * to fp16, or pass them to milo_pack_lr3 for Algorithm 1's last line "Quantize U, V").
+ *   W [N x K]      fp32 row-major (device, read only)
+ *   params         host pointer
+ *   q3             out, device, milo_w3_packed_bytes(N, K) bytes
+ *   U, V           out, device; may be NULL when rank == 0
+ *   eps            out, HOST array of at least params->iters doubles: eps_t of the iterations run
+ *   iters_run      out, HOST: how many iterations ran
+ *   workspace      device, at least milo_compress_w3lr_workspace(N, K, rank) bytes (about 1.1 N K floats),
+ *                  scratch; no preparation needed
+ * The call synchronizes `stream` once per iteration (the stop rule runs on the host), so it cannot be
+ * captured in a graph; it is an offline tool, not part of the inference path.
+ * Errors: NULL, SHAPE (also bad parameter values), RANK (rank < 0, > MILO_COMPRESS_MAX_RANK or
+ * > min(N, K)), WORKSPACE, ALIGN, HIP.
+ */
+#define MILO_COMPRESS_MAX_RANK 128
+typedef struct milo_compress_params {
+    int32_t rank;            /* r */
+    int32_t iters;           /* outer iterations at most, >= 1 (the paper stops at 20 at the latest) */
+    int32_t hqq_iters;       /* zero-point updates per outer iteration, >= 0 */
+    int32_t power_iters;     /* extra subspace rounds in the first outer iteration, >= 0 */
+    int32_t refine_iters;    /* extra subspace rounds in every later outer iteration, >= 0 */
+    float p;                 /* 0 < p < 1 */
+    float beta;              /* > 0 */
+    float kappa;             /* > 0 */
+    float tol;               /* stop threshold; negative: run all `iters` iterations */
+    uint32_t seed;
+} milo_compress_params;
+size_t milo_compress_w3lr_workspace(int64_t N, int64_t K, int rank);
+int milo_compress_w3lr(const float* W, int64_t N, int64_t K, const milo_compress_params* params,
+                       void* q3, float* U, float* V, double* eps, int* iters_run,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * milo_w3lr_gemm for callers that cannot allocate and cannot bring a workspace: code that runs
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
  * result and errors as milo_w3lr_gemm, bit for bit, without `workspace`: the scratch memory is a

@@ -29,7 +29,7 @@ EXPORTS = ("milo_status_string", "milo_version", "milo_w3_packed_bytes", "milo_p
            "milo_unpack_w3", "milo_dequant_w3", "milo_w3lr_gemm_workspace", "milo_w3lr_gemm",
            "milo_w3lr_gemm_static", "milo_w3lr_gemm_flags", "milo_lr3_packed_bytes", "milo_pack_lr3",
            "milo_moe_w3lr_check_experts", "milo_moe_w3lr_workspace", "milo_moe_w3lr_forward",
-           "milo_moe_w3lr_routing_status")
+           "milo_moe_w3lr_routing_status", "milo_compress_w3lr_workspace", "milo_compress_w3lr")
 
 
 class MiloError(RuntimeError):
@@ -42,6 +42,12 @@ class MiloError(RuntimeError):
 class Weight(ctypes.Structure):
     _fields_ = [("q3", ctypes.c_void_p), ("U", ctypes.c_void_p), ("V", ctypes.c_void_p), ("r", ctypes.c_int32),
                 ("flags", ctypes.c_uint32)]
+
+
+class CompressParams(ctypes.Structure):
+    _fields_ = [("rank", ctypes.c_int32), ("iters", ctypes.c_int32), ("hqq_iters", ctypes.c_int32),
+                ("power_iters", ctypes.c_int32), ("refine_iters", ctypes.c_int32), ("p", ctypes.c_float), ("beta", ctypes.c_float),
+                ("kappa", ctypes.c_float), ("tol", ctypes.c_float), ("seed", ctypes.c_uint32)]
 
 
 class Expert(ctypes.Structure):
@@ -87,6 +93,11 @@ def bind(path):
     L.milo_pack_lr3.argtypes = [vp, vp, i64, i64, ci, vp, vp, vp]
     L.milo_w3lr_gemm_static.restype = ci
     L.milo_w3lr_gemm_static.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, vp, vp]
+    L.milo_compress_w3lr_workspace.restype = sz
+    L.milo_compress_w3lr_workspace.argtypes = [i64, i64, ci]
+    L.milo_compress_w3lr.restype = ci
+    L.milo_compress_w3lr.argtypes = [vp, i64, i64, ctypes.POINTER(CompressParams), vp, vp, vp,
+                                     ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci), vp, sz, vp]
     L.milo_moe_w3lr_check_experts.restype = ci
     L.milo_moe_w3lr_check_experts.argtypes = [ctypes.POINTER(Expert), ci, i64, i64,
                                               ctypes.POINTER(ci)]
@@ -196,6 +207,28 @@ def pack_lr3(U, V):
     v3 = torch.empty(vb.value, dtype=torch.uint8, device=U.device)
     _check(lib().milo_pack_lr3(_ptr(U), _ptr(V), N, K, r, _ptr(u3), _ptr(v3), _stream()), "milo_pack_lr3")
     return u3, v3
+
+
+def compress_w3lr(W, r, iters=20, hqq_iters=20, power_iters=2, refine_iters=0, p=0.7, beta=10.0, kappa=1.01, tol=1e-4, seed=1):
+    """milo_compress_w3lr (Algorithm 1): fp32 CUDA weight [N, K] -> (PackedWeight without compensator,
+    U [N, r] fp32, V [r, K] fp32, list of the errors eps_t of the iterations run)."""
+    W = _dev(W, torch.float32, "W")
+    N, K = W.shape
+    prm = CompressParams(r, iters, hqq_iters, power_iters, refine_iters, p, beta, kappa, tol, seed)
+    nbytes = packed_bytes(N, K)
+    q3 = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=W.device)
+    U = torch.empty((N, max(r, 1)), dtype=torch.float32, device=W.device)[:, :r].contiguous()
+    V = torch.empty((max(r, 1), K), dtype=torch.float32, device=W.device)[:r]
+    wsb = int(lib().milo_compress_w3lr_workspace(N, K, r))
+    if wsb == 0:
+        _check(2 if 0 <= r <= min(N, K) else 4, "milo_compress_w3lr_workspace")
+    ws = torch.empty(wsb, dtype=torch.uint8, device=W.device)
+    eps = (ctypes.c_double * max(iters, 1))()
+    ran = ctypes.c_int(0)
+    _check(lib().milo_compress_w3lr(_ptr(W), N, K, ctypes.byref(prm), _ptr(q3), _ptr(U) if r else None,
+                                    _ptr(V) if r else None, eps, ctypes.byref(ran), _ptr(ws), wsb, _stream()),
+           "milo_compress_w3lr")
+    return PackedWeight(N, K, q3[:nbytes]), U, V, [eps[i] for i in range(ran.value)]
 
 
 def unpack_w3(pw):

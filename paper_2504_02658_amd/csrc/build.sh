@@ -7,6 +7,7 @@ mkdir -p "$OUT" _build
 FLAGS="-O3 --offload-arch=gfx950 -fPIC -std=c++17 -Xclang -target-feature -Xclang -packed-fp32-ops -fhip-fp32-correctly-rounded-divide-sqrt -Wno-unused-command-line-argument"
 pids=()
 hipcc $FLAGS -ffp-contract=off -c pack.hip -o _build/pack.o & pids+=($!)
+hipcc $FLAGS -ffp-contract=off -c compress.hip -o _build/compress.o & pids+=($!)
 hipcc $FLAGS -c gemm_tiled.hip -o _build/gemm_tiled.o & pids+=($!)
 hipcc $FLAGS -c gemm_decode.hip -o _build/gemm_decode.o & pids+=($!)
 hipcc $FLAGS -c moe.hip -o _build/moe.o & pids+=($!)
@@ -85,8 +86,8 @@ if bad or n == 0 or waits == 0:
     sys.exit("tiled kernel: scratch access inside the K loop (or nothing checked): %r" % bad[:4])
 print("tiled kernel: no scratch access around %d hand-counted waits in %d variants" % (waits, n))
 PY
-hipcc --offload-arch=gfx950 -shared -fPIC -o "$OUT/libmilo.so" _build/pack.o _build/gemm_tiled.o _build/gemm_decode.o _build/moe.o _build/api.o _build/gemm_static.o
-hipcc --offload-arch=gfx950 -shared -fPIC -o "$OUT/libmilo_fullwaits.so" _build/pack.o _build/gemm_tiled_fw.o _build/gemm_decode_fw.o _build/moe.o _build/api.o _build/gemm_static.o
+hipcc --offload-arch=gfx950 -shared -fPIC -o "$OUT/libmilo.so" _build/pack.o _build/gemm_tiled.o _build/gemm_decode.o _build/moe.o _build/api.o _build/gemm_static.o _build/compress.o
+hipcc --offload-arch=gfx950 -shared -fPIC -o "$OUT/libmilo_fullwaits.so" _build/pack.o _build/gemm_tiled_fw.o _build/gemm_decode_fw.o _build/moe.o _build/api.o _build/gemm_static.o _build/compress.o
 # Every kernel the host code launches must have its launch stub in the library (a stub that the
 # compiler failed to emit only shows up as an undefined symbol when the library is loaded).
 for lib in libmilo.so libmilo_fullwaits.so; do

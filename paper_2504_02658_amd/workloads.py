@@ -77,6 +77,22 @@ def gen_weight(N, K, seed, outlier_frac=0.0, outlier_gain=8.0, std=WEIGHT_STD):
     return W
 
 
+def gen_weight_lowrank(N, K, seed, modes=8, gain=6.0, decay=0.75, outlier_frac=0.0, std=WEIGHT_STD):
+    """gen_weight plus `modes` rank-one components whose strengths fall off geometrically from `gain`
+    times the top singular value of the Gaussian part: the spectrum with a few dominant directions
+    over a flat bulk that the compressor's low-rank step is meant for."""
+    W = gen_weight(N, K, seed, outlier_frac=outlier_frac, std=std)
+    rng = _rng(seed, 4)
+    bulk_top = std * (np.sqrt(N) + np.sqrt(K))
+    for k in range(modes):
+        a = rng.standard_normal(N).astype(np.float32)
+        b = rng.standard_normal(K).astype(np.float32)
+        a /= np.linalg.norm(a)
+        b /= np.linalg.norm(b)
+        W += np.float32(gain * decay ** k * bulk_top) * np.outer(a, b)
+    return W
+
+
 def gen_activations(M, K, seed):
     """fp16 [M, K], N(0, 1)."""
     return _rng(seed, 3).standard_normal((M, K), dtype=np.float32).astype(np.float16)

@@ -89,6 +89,32 @@ def test_host_side_argument_errors(L):
     assert L.milo_workspace_status(odd, st) == 7
 
 
+def test_compressor_argument_errors(L):
+    # milo_compress_w3lr validates on the host before it touches the device
+    p = ctypes.c_void_p(0x10000)
+    null = ctypes.c_void_p(0)
+    st = ctypes.c_void_p(0)
+    eps = (ctypes.c_double * 32)()
+    ran = ctypes.c_int(0)
+    assert L.milo_compress_w3lr_workspace(14336, 4096, 32) > 14336 * 4096 * 4
+    assert L.milo_compress_w3lr_workspace(1024, 1000, 8) == 0
+    assert L.milo_compress_w3lr_workspace(1024, 1024, 129) == 0
+
+    def call(W=p, N=1024, K=1024, ws=p, wsb=1 << 40, U=p, V=p, **kw):
+        f = dict(rank=16, iters=20, hqq_iters=20, power_iters=2, refine_iters=0, p=0.7, beta=10.0, kappa=1.01,
+                 tol=1e-4, seed=1)
+        f.update(kw)
+        prm = api.CompressParams(*(f[name] for name, _ in api.CompressParams._fields_))
+        return L.milo_compress_w3lr(W, N, K, ctypes.byref(prm), p, U, V, eps, ctypes.byref(ran), ws, wsb, st)
+
+    assert call(W=null) == 1 and call(U=null) == 1 and call(ws=null) == 1
+    assert call(rank=-1) == 4 and call(rank=129) == 4 and call(N=16, K=64, rank=32) == 4
+    assert call(K=1000) == 2 and call(N=1000) == 2
+    assert call(iters=0) == 2 and call(hqq_iters=-1) == 2 and call(p=1.5) == 2 and call(beta=0.0) == 2
+    assert call(wsb=1024) == 5
+    assert call(W=ctypes.c_void_p(0x10008)) == 7
+
+
 def test_bench_refuses_more_than_one_gpu():
     # the benchmark measures one GPU; asking for more ends with a message, before any GPU work
     import subprocess, sys, os

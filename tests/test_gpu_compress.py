@@ -1,0 +1,170 @@
+"""GPU parity of milo_compress_w3lr (Algorithm 1) against the fp64 oracle.
+
+The library's loop differs from the oracle's in two documented ways: its arithmetic is fp32, and its
+truncated SVD comes from a warm-started block subspace iteration instead of an exact factorization.
+Neither is a bit-exact match, so the tests compare what the algorithm fixes: the fixed scales bit for
+bit, the error sequence eps_t within a tolerance, and the consistency of the outputs with each other
+(the codes are the quantization of W - U V with the stored parameters; eps is the error of the stored
+pieces), each checked with oracle functions on the library's own outputs.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2504_02658_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+# eps_t against the oracle's, with the subspace iteration run to convergence (many rounds): what is left
+# is fp32 against fp64, which moves single codes at rounding boundaries and through them the later
+# iterations.  With the default number of rounds the iteration captures slightly less of E than the
+# exact SVD (the bulk of E's spectrum is flat, so it converges slowly), which moves eps by a fraction of
+# the share of ||E||^2 that the compensator holds: up to 1.7 % on these small matrices.
+EPS_REL_TOL_CONVERGED = 2e-3
+EPS_REL_TOL_DEFAULT = 3e-2
+
+
+def _compress(W, r, **kw):
+    import torch
+    from paper_2504_02658_amd import api
+    pw, U, V, eps = api.compress_w3lr(torch.from_numpy(W).cuda(), r, **kw)
+    codes, scales, zeros = (t.cpu().numpy() for t in api.unpack_w3(pw))
+    return dict(pw=pw, codes=codes, scales=scales, zeros=zeros, U=U.cpu().numpy().astype(np.float64),
+                V=V.cpu().numpy().astype(np.float64), eps=eps)
+
+
+def _check_outputs(W, out, r, what):
+    """What must hold whatever the SVD's accuracy: scales, codes, balance and the reported error."""
+    W64 = W.astype(np.float64)
+    s16, _ = oracle.fixed_scales(W)
+    assert np.array_equal(out["scales"].view(np.uint16), s16.view(np.uint16)), f"{what}: scales are not W's RTN scales"
+    assert np.all(np.isfinite(out["zeros"].astype(np.float32)))
+    R = W64 - out["U"] @ out["V"]
+    q, Wdq = oracle.quantize_with(R, s16.astype(np.float64), out["zeros"].astype(np.float64))
+    same = np.mean(q.astype(np.uint8) == out["codes"])
+    assert same >= 0.999, f"{what}: only {same:.5f} of the codes are the quantization of W - U V"
+    assert np.max(np.abs(q - out["codes"])) <= 1
+    if r > 0:
+        nu = np.linalg.norm(out["U"], axis=0)
+        nv = np.linalg.norm(out["V"], axis=1)
+        assert np.allclose(nu, nv, rtol=1e-3), f"{what}: U and V do not share the singular values evenly"
+        assert np.all(np.diff(nu) <= 1e-3 * nu[0]), f"{what}: components not in descending order"
+        gram = (out["U"].T @ out["U"]) / np.outer(nu, nu)
+        assert np.max(np.abs(gram - np.eye(r))) < 1e-3, f"{what}: columns of U are not orthogonal"
+    # the error of the stored pieces (z rounded to fp16) is the reported one up to that rounding
+    stored = np.linalg.norm(W64 - oracle.dequantize(out["codes"], out["scales"], out["zeros"]) - out["U"] @ out["V"])
+    assert abs(stored - out["eps"][-1]) <= 5e-3 * out["eps"][-1], (what, stored, out["eps"][-1])
+
+
+@pytest.mark.parametrize("name,N,K,r,kw", [
+    ("dominant directions", 256, 512, 16, dict(modes=8)),
+    ("outlier channels", 192, 384, 8, dict(modes=4, outlier_frac=0.02)),
+    ("flat spectrum", 128, 256, 24, dict(modes=0)),
+])
+def test_error_sequence_matches_the_oracle(name, N, K, r, kw):
+    W = wl.gen_weight_lowrank(N, K, seed=3100 + r, **kw)
+    iters = 6
+    ref = oracle.milo_compress(W, r, iters=iters, tol=-1.0)
+    quick = _compress(W, r, iters=iters, tol=-1.0)
+    out = _compress(W, r, iters=iters, tol=-1.0, power_iters=40, refine_iters=10)
+    assert len(out["eps"]) == iters == len(ref["eps"]) == len(quick["eps"])
+    rel = np.abs(np.array(out["eps"]) / np.array(ref["eps"]) - 1.0)
+    rel_quick = np.array(quick["eps"]) / np.array(ref["eps"]) - 1.0
+    print(name, "eps oracle", ref["eps"], "library", out["eps"], "default rounds", quick["eps"])
+    assert np.all(rel <= EPS_REL_TOL_CONVERGED), f"{name}: eps_t differs by {rel.max():.2e} relative"
+    assert np.all(rel_quick <= EPS_REL_TOL_DEFAULT) and np.all(rel_quick > -EPS_REL_TOL_CONVERGED), \
+        f"{name}: eps_t with the default rounds is off by {rel_quick}"
+    _check_outputs(W, quick, r, name + " (default rounds)")
+    _check_outputs(W, out, r, name)
+    # the converged subspace is the exact one: same singular values as the oracle's factors
+    sv = np.linalg.norm(out["U"], axis=0) ** 2
+    sv_ref = np.linalg.norm(ref["U"], axis=0) ** 2
+    assert np.allclose(sv[: r // 2], sv_ref[: r // 2], rtol=2e-2), (sv, sv_ref)
+    # the compressed weight is as good as the oracle's: same error, and the zero-points agree on most groups
+    dz = np.abs(out["zeros"].astype(np.float64) - ref["zeros"].astype(np.float64))
+    assert np.median(dz) < 2e-2, f"{name}: zero-points differ (median {np.median(dz):.3f})"
+
+
+def test_zero_rank_is_the_half_quadratic_quantizer_alone():
+    # r = 0: no compensator, one pass of zero-point updates; compare z itself with the oracle's inner loop
+    W = wl.gen_weight(160, 320, seed=3201, outlier_frac=0.03)
+    out = _compress(W, 0, iters=1)
+    s16, z0 = oracle.fixed_scales(W)
+    z = oracle.hqq_zero_points(W.astype(np.float64), s16.astype(np.float64), z0)
+    dz = np.abs(out["zeros"].astype(np.float64) - z)
+    # fp16 storage of z (|z| < 8: half an ulp is 2^-9) plus fp32 rounding at a code boundary now and then
+    assert np.quantile(dz, 0.95) <= 2.0 ** -8, np.quantile(dz, 0.95)
+    _, Wdq = oracle.quantize_with(W.astype(np.float64), s16.astype(np.float64), z)
+    e_ref = np.linalg.norm(W - Wdq)
+    assert abs(out["eps"][0] - e_ref) <= 1e-3 * e_ref
+    _check_outputs(W, out, 0, "rank 0")
+    # and it beats round-to-nearest in the l_p sense it optimizes
+    q, sr, zr = oracle.quantize_rtn(W)
+    lp = lambda E: np.sum(np.abs(E) ** 0.7)
+    assert lp(W - oracle.dequantize(out["codes"], out["scales"], out["zeros"])) < lp(W - oracle.dequantize(q, sr, zr))
+
+
+def test_stop_rule_and_improvement_over_one_shot():
+    W = wl.gen_weight_lowrank(256, 512, seed=3301, modes=6, outlier_frac=0.01)
+    out = _compress(W, 16, iters=20, tol=1e-4)
+    eps = out["eps"]
+    ran = len(eps)
+    assert 2 <= ran <= 20
+    for t in range(1, ran):
+        assert not oracle.stop_rule(eps[:t], 1e-4), f"ran past a stop at iteration {t}"
+    assert ran == 20 or oracle.stop_rule(eps, 1e-4)
+    assert eps[-1] < eps[0], "iterating did not lower the error"
+    # one-shot baseline: round-to-nearest codes, exact truncated SVD of the residual
+    q, s, z = oracle.quantize_rtn(W)
+    _, _, S = oracle.svd_compensator(W.astype(np.float64) - oracle.dequantize(q, s, z), 16)
+    assert eps[-1] < np.sqrt(np.sum(S[16:] ** 2))
+    _check_outputs(W, out, 16, "stop rule")
+
+
+def test_compressed_weight_feeds_the_gemm():
+    # Algorithm 1's outputs through the inference kernel: closer to the uncompressed product than the
+    # round-to-nearest weight without compensator, and equal to the oracle's linear on the same pieces
+    import torch
+    from paper_2504_02658_amd import api
+    from helpers import assert_close
+    N, K, r, M = 512, 1024, 32, 8
+    W = wl.gen_weight_lowrank(N, K, seed=3401, modes=8)
+    X = wl.gen_activations(M, K, seed=3401)
+    out = _compress(W, r, iters=5, tol=-1.0)
+    U16, V16 = out["U"].astype(np.float16), out["V"].astype(np.float16)
+    pw = out["pw"].with_compensator(torch.from_numpy(U16).cuda(), torch.from_numpy(V16).cuda())
+    Y = api.w3lr_gemm(torch.from_numpy(X).cuda(), pw).cpu().numpy()
+    ref = oracle.w3lr_linear(X, out["codes"], out["scales"], out["zeros"], U16, V16)
+    assert_close(Y, ref, "gemm on a compressed weight")
+    exact = X.astype(np.float64) @ W.astype(np.float64).T
+    q, s, z = oracle.quantize_rtn(W)
+    rtn = X.astype(np.float64) @ oracle.dequantize(q, s, z).T
+    assert np.linalg.norm(Y - exact) < 0.9 * np.linalg.norm(rtn - exact)
+
+
+@pytest.mark.timeout(600)
+def test_mixtral_up_projection_size():
+    # the full 14336 x 4096 weight, rank 32, three iterations: properties on the whole result, codes
+    # checked on sampled rows (the oracle's exact SVD of this size is not a matter of seconds)
+    import torch
+    from paper_2504_02658_amd import api
+    N, K, r = 14336, 4096, 32
+    W = wl.gen_weight_lowrank(N, K, seed=3501, modes=8)
+    Wd = torch.from_numpy(W).cuda()
+    pw, U, V, eps = api.compress_w3lr(Wd, r, iters=3, tol=-1.0)
+    assert len(eps) == 3 and eps[2] < eps[1] < eps[0]
+    codes, scales, zeros = (t.cpu().numpy() for t in api.unpack_w3(pw))
+    U64, V64 = U.cpu().numpy().astype(np.float64), V.cpu().numpy().astype(np.float64)
+    rows = np.random.default_rng(5).choice(N, size=96, replace=False)
+    s16, _ = oracle.fixed_scales(W[rows])
+    assert np.array_equal(scales[rows].view(np.uint16), s16.view(np.uint16))
+    R = W[rows].astype(np.float64) - U64[rows] @ V64
+    q, _ = oracle.quantize_with(R, s16.astype(np.float64), zeros[rows].astype(np.float64))
+    assert np.mean(q.astype(np.uint8) == codes[rows]) >= 0.999
+    nu, nv = np.linalg.norm(U64, axis=0), np.linalg.norm(V64, axis=1)
+    assert np.allclose(nu, nv, rtol=1e-3)
+    gram = (U64.T @ U64) / np.outer(nu, nu)
+    assert np.max(np.abs(gram - np.eye(r))) < 1e-3
+    # error of the stored pieces on the sampled rows against the same rows of the reported total
+    part = np.linalg.norm(W[rows].astype(np.float64) - oracle.dequantize(codes[rows], scales[rows], zeros[rows]) - U64[rows] @ V64)
+    assert abs(part * np.sqrt(N / 96) / eps[-1] - 1.0) < 0.05
