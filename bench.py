@@ -11,7 +11,8 @@ value = (packed blob: codes, scales, zero-points; + U + V bytes) / time per step
 Prints ONE JSON line.  Besides the headline it carries, under "extra", the other workloads of the
 metric, each with its own roofline object: c1 at M = 1 and 4, Mixtral's down projection at decode,
 the small configuration c0, the prefill GEMM c2 and the two MoE layers c3 and c4 (plus c3's shape at
-a decode-sized batch).  --only NAME[,NAME...] restricts the run to some legs (for profiler runs).
+a decode-sized batch), and the time the compressor (Algorithm 1, offline) takes for one weight of c1's
+shape.  --only NAME[,NAME...] restricts the run to some legs (for profiler runs).
 """
 import argparse
 import json
@@ -25,7 +26,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_FP16_PEAK_TFLOPS = 2500.0
 MIN_TIMED_MS = 20.0             # a timed region shorter than this is repeated until it is not
-LEGS = ("c1", "c1_small_m", "w2_decode", "c0", "c2", "c3", "c4")
+LEGS = ("c1", "c1_small_m", "w2_decode", "c0", "c2", "c3", "c4", "compress")
 
 
 def measured_traffic():
@@ -328,6 +329,22 @@ def main():
             extra["c3_shape_16_tokens"] = {"us_per_layer": round(msd * 1e3, 1), "experts_used": len(used),
                                            "roofline": hbm_roofline(wb, msd, "grouped W3 kernels of the MoE layer")}
         del layer, experts
+        torch.cuda.empty_cache()
+
+    if "compress" in legs:
+        # Algorithm 1 for one weight of c1's shape: 20 iterations (the paper's early stop), stop rule off
+        # so that the work is fixed; wall clock around the call, which synchronizes by itself
+        cc = wl.C1[16]
+        Wc = torch.from_numpy(wl.gen_weight_lowrank(cc.N, cc.K, cc.seed, outlier_frac=0.01)).to(dev)
+        api.compress_w3lr(Wc, cc.r, iters=2, tol=-1.0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        _, _, _, eps_c = api.compress_w3lr(Wc, cc.r, iters=20, tol=-1.0)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        extra["compress_c1_weight"] = {"seconds": round(dt, 3), "iters": len(eps_c), "N": cc.N, "K": cc.K, "r": cc.r,
+                                       "eps_first": round(eps_c[0], 4), "eps_last": round(eps_c[-1], 4)}
+        del Wc
         torch.cuda.empty_cache()
 
     if extra:

@@ -71,8 +71,12 @@ __global__ __launch_bounds__(kPackThreads) void hqq_kernel(const float* __restri
     const float4 r4 = *reinterpret_cast<const float4*>(RE + at);
     const float r[4] = {r4.x, r4.y, r4.z, r4.w};
     const float sf = s[gu];
+    const float inv_s = 1.0f / sf;
     float zf = z[gu];
+    // |e|^(p-1) through the hardware's exp2 and log2 (about 1 ulp each): the threshold it feeds is a
+    // smooth function, no decision hangs on its last bits.  The code itself does: code_of divides.
     for (int it = 0; it < iters; ++it) {
+        const float inv_beta = 1.0f / beta;
         float acc = 0.0f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -80,9 +84,9 @@ __global__ __launch_bounds__(kPackThreads) void hqq_kernel(const float* __restri
             const float wdq = sf * (q - zf);
             const float e = r[i] - wdq;
             const float ae = fabsf(e);
-            const float thr = ae > 0.0f ? powf(ae, pm1) / beta : 0.0f;     // |e|^(p-1) / beta
+            const float thr = ae > 0.0f ? __builtin_amdgcn_exp2f(pm1 * __builtin_amdgcn_logf(ae)) * inv_beta : 0.0f;
             const float m = copysignf(fmaxf(ae - thr, 0.0f), e);           // shrink_lp(e)
-            acc += q - (r[i] - m) / sf;
+            acc += q - (r[i] - m) * inv_s;
         }
 #pragma unroll
         for (int m = 1; m < 16; m <<= 1) acc += shfl_xor16(acc, m);
@@ -343,7 +347,8 @@ __global__ __launch_bounds__(kSmallThreads) void cholesky_inverse_kernel(const f
 }
 
 // Gm [l x l] symmetric (B B^T) = Ub diag(lambda) Ub^T by cyclic Jacobi rotations, l / 2 disjoint
-// pairs per step in round-robin order.  With sigma = sqrt(lambda) sorted descending it writes
+// pairs per step in round-robin order, at most `sweeps` sweeps (fewer when a sweep finds nothing to
+// rotate, which a warm-started basis reaches quickly).  With sigma = sqrt(lambda) sorted descending it writes
 //   Mx [l x r] = Ub_r sigma_r^(1/2),  Vm [r x l] = sigma_r^(-1/2) Ub_r^T,  Wm [l x l] = sigma^-1 Ub^T
 // (rows of Vm and Wm whose sigma is negligible are zero) and sigma itself.
 __global__ __launch_bounds__(kSmallThreads) void jacobi_factors_kernel(const float* __restrict__ Gm, int l, int r, int sweeps,
@@ -366,7 +371,10 @@ __global__ __launch_bounds__(kSmallThreads) void jacobi_factors_kernel(const flo
     __syncthreads();
     const int n = (l + 1) & ~1;            // players of the round-robin; player l (if l is odd) sits out
     const int half = n / 2;
+    __shared__ int rotated;
     for (int sweep = 0; sweep < sweeps; ++sweep) {
+        if (tid == 0) rotated = 0;
+        __syncthreads();
         for (int step = 0; step < n - 1; ++step) {
             if (tid < half) {
                 const int a = tid == 0 ? 0 : 1 + (tid - 1 + step) % (n - 1);
@@ -377,7 +385,8 @@ __global__ __launch_bounds__(kSmallThreads) void jacobi_factors_kernel(const flo
                 if (q < l) {
                     const float apq = A[p * ld + q];
                     const float app = A[p * ld + p], aqq = A[q * ld + q];
-                    if (fabsf(apq) > 1e-20f && fabsf(apq) > 1e-9f * sqrtf(fabsf(app * aqq))) {
+                    if (fabsf(apq) > 1e-30f && fabsf(apq) > 6e-8f * sqrtf(fabsf(app * aqq))) {
+                        rotated = 1;
                         const float tau = (aqq - app) / (2.0f * apq);
                         const float t = copysignf(1.0f, tau) / (fabsf(tau) + sqrtf(1.0f + tau * tau));
                         c = 1.0f / sqrtf(1.0f + t * t);
@@ -416,6 +425,8 @@ __global__ __launch_bounds__(kSmallThreads) void jacobi_factors_kernel(const flo
             }
             __syncthreads();
         }
+        if (rotated == 0) break;       // a whole sweep without a rotation: diagonal to working precision
+        __syncthreads();
     }
     // order: place[i] = position of eigenvalue i in descending order
     for (int i = tid; i < l; i += kSmallThreads) lam[i] = A[i * ld + i];
