@@ -11,7 +11,7 @@ value = (packed blob: codes, scales, zero-points; + U + V bytes) / time per step
 Prints ONE JSON line.  Besides the headline it carries, under "extra", the other workloads of the
 metric, each with its own roofline object: c1 at M = 1 and 4, Mixtral's down projection at decode,
 the small configuration c0, the prefill GEMM c2 and the two MoE layers c3 and c4 (plus c3's shape at
-a decode-sized batch), and the time the compressor (Algorithm 1, offline) takes for one weight of c1's
+a decode-sized batch), c1 with the INT3 compensator, the symmetric weight and bf16 activations, and the time the compressor (Algorithm 1, offline) takes for one weight of c1's
 shape.  --only NAME[,NAME...] restricts the run to some legs (for profiler runs).
 """
 import argparse
@@ -26,7 +26,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_FP16_PEAK_TFLOPS = 2500.0
 MIN_TIMED_MS = 20.0             # a timed region shorter than this is repeated until it is not
-LEGS = ("c1", "c1_small_m", "w2_decode", "c0", "c2", "c3", "c4", "compress")
+LEGS = ("c1", "c1_small_m", "c1_variants", "w2_decode", "c0", "c2", "c3", "c4", "compress")
 
 
 def measured_traffic():
@@ -139,7 +139,7 @@ def clone_weight(pw):
     from paper_2504_02658_amd import api
     return api.PackedWeight(pw.N, pw.K, pw.q3.clone(),
                             None if pw.U is None else pw.U.clone(),
-                            None if pw.V is None else pw.V.clone())
+                            None if pw.V is None else pw.V.clone(), flags=pw.flags, r=pw.r if pw.U is not None else None)
 
 
 def hbm_roofline(nbytes, ms, kernel, **more):
@@ -193,9 +193,9 @@ def main():
         pw = fit_compensator(W, api.pack_w3(W), case.r, seed=case.seed)
         return W, pw
 
-    def gemm_leg(M, K, N, r, weights, steps, warmup):
-        X = torch.from_numpy(wl.gen_activations(M, K, 1001)).to(dev)
-        Y = torch.empty((M, N), dtype=torch.float16, device=dev)
+    def gemm_leg(M, K, N, r, weights, steps, warmup, dtype=torch.float16):
+        X = torch.from_numpy(wl.gen_activations(M, K, 1001)).to(dev).to(dtype)
+        Y = torch.empty((M, N), dtype=dtype, device=dev)
         ws = api.new_workspace(api.gemm_workspace_bytes(M, N, K, r), dev)
         step = lambda i: api.w3lr_gemm(X, weights[i % len(weights)], out=Y, workspace=ws)
         ms, timed = time_steps(step, steps, len(weights), warmup)
@@ -205,7 +205,7 @@ def main():
     result, extra = None, {}
     case = wl.C1[16]
     W1 = pw1 = copies = None
-    if legs & {"c1", "c1_small_m"} or not args.no_cpu_baseline:
+    if legs & {"c1", "c1_small_m", "c1_variants"} or not args.no_cpu_baseline:
         W1, pw1 = build_linear(case)
     if legs & {"c1", "c1_small_m"}:
         copies = [pw1] + [clone_weight(pw1) for _ in range(args.copies - 1)]
@@ -255,6 +255,26 @@ def main():
         del copies[1:]
         copies = None
         torch.cuda.empty_cache()
+
+    if "c1_variants" in legs:
+        # the same call with the other forms of the weight (Section 3.2.3 INT3 compensator, Section 3.3
+        # symmetric conversion) and with bf16 activations; same cold protocol
+        def variant(name, pw, dtype=torch.float16, note=""):
+            cps = [pw] + [clone_weight(pw) for _ in range(args.copies - 1)]
+            ms, _ = gemm_leg(16, case.K, case.N, case.r, cps, args.steps, args.warmup, dtype)
+            extra[name] = {"us": round(ms * 1e3, 3), "note": note,
+                           "roofline": hbm_roofline(pw.weight_bytes(), ms, "w3lr_decode_kernel")}
+            del cps
+            torch.cuda.empty_cache()
+
+        u3, v3 = api.pack_lr3(pw1.U.float(), pw1.V.float())
+        variant("c1_M16_int3_compensator", pw1.with_int3_compensator(u3, v3, case.r),
+                note="U, V as INT3 blobs (3.5 bit per element instead of 16)")
+        pws = fit_compensator(W1, api.pack_w3(W1, symmetric=True), case.r, seed=case.seed)
+        variant("c1_M16_symmetric", pws, note="symmetric quantizer, zero-point-free conversion")
+        pwb = api.PackedWeight(pw1.N, pw1.K, pw1.q3, pw1.U.to(torch.bfloat16), pw1.V.to(torch.bfloat16))
+        variant("c1_M16_bf16", pwb, dtype=torch.bfloat16, note="bf16 activations, compensator and output")
+        del u3, v3, pws, pwb
 
     if "w2_decode" in legs:
         # Mixtral's down projection at decode (the other expert GEMM shape of Section 4): long K
