@@ -63,6 +63,22 @@ static int gemm_splits(int64_t M, int64_t N, int64_t K, int r) {
     const int64_t m_tiles = (M + bm - 1) / bm;
     return tiled_k_splits(m_tiles * ((N + 255) / 256), K, r > 0 ? m_tiles * tiled_t_parts(K) : 0);
 }
+// Parts of T = X V^T per M-tile for the single GEMM.  T must be there when the column tiles reach their
+// epilogue: a part should take at most half as long as a column tile's share of K.  A part walks its
+// chunks once per 256 ranks, and with K splits a column tile's share is short, so both call for more
+// (shorter) parts than the default of eight chunks each.
+static int gemm_t_parts(int64_t M, int64_t N, int64_t K, int r) {
+    if (r <= 0) return 0;
+    const int base = tiled_t_parts(K);
+    const int64_t nchunks = (K / 64 + 1) / 2;
+    const int64_t cps = (nchunks + gemm_splits(M, N, K, r) - 1) / gemm_splits(M, N, K, r);
+    const int64_t passes = ((int64_t)r + 255) / 256;
+    int64_t cpp = cps / (2 * passes);
+    if (cpp < 1) cpp = 1;
+    int64_t parts = (nchunks + cpp - 1) / cpp;
+    if (parts > 16) parts = 16;
+    return parts > base ? (int)parts : base;
+}
 
 // Adds the fp32 partial sums of the K splits in split order and rounds once.
 template <bool BF>
@@ -95,7 +111,7 @@ extern "C" size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int 
     if (M <= 16) return decode_workspace_bytes(r, K);
     // control words | four flag words per 32-row tile | T = X V^T, fp16 [M x pad16(r)] | its fp32
     // partials per part of K | with K splits, their fp32 partial sums [M x N] each
-    const size_t parts = r > 0 ? (size_t)tiled_t_parts(K) : 0;
+    const size_t parts = (size_t)gemm_t_parts(M, N, K, r);
     const int splits = gemm_splits(M, N, K, r);
     return 256 + align_up((size_t)((M + 31) / 32) * 16, 256) +
            align_up((size_t)M * (size_t)rank_pad(r) * 2 + 256, 256) +
@@ -157,7 +173,7 @@ extern "C" int milo_w3lr_gemm_flags(const milo_half* X, int64_t M, int64_t N, in
     const int bm = 32 * mb;
     const int64_t m_tiles = (M + bm - 1) / bm;
     if (m_tiles > 65535) return MILO_ERR_SHAPE;
-    const int parts = r > 0 ? tiled_t_parts(K) : 0;
+    const int parts = gemm_t_parts(M, N, K, r);
     const int splits = gemm_splits(M, N, K, r);
     if ((uint64_t)M * K * 2 >= 0x80000000ull || ((uint64_t)r + 256) * K * 2 >= 0xFFFFFFF0ull ||
         (uint64_t)(parts > 0 ? parts : 1) * M * ldt * 4 >= 0xFFFFFFF0ull || (N & 3) != 0)
@@ -181,6 +197,17 @@ extern "C" int milo_w3lr_gemm_flags(const milo_half* X, int64_t M, int64_t N, in
     ga.flags = tile_flags; ga.flags_status = ctrl + 3; ga.weights_once = m_tiles == 1;
     ga.lr3_rank = (w.flags & MILO_LR_INT3) ? r : 0;
     ga.self_clean = 1;
+    // Ranks of the size the paper gives dense layers (Section 3.2.2, Dense-512, Dense-1024): the parts of T
+    // share the addition of their partial sums, and with K splits every split applies a share of the
+    // ranks (the fp32 partial sums of the splits are added anyway), in blocks of 64.
+    ga.t_dist = r > 64 ? 1 : 0;
+    ga.lr_splits = 1; ga.lr_step = 0;
+    if (splits > 1 && r > 64) {
+        const int nblk = (r + 63) / 64;
+        const int per = (nblk + (splits < nblk ? splits : nblk) - 1) / (splits < nblk ? splits : nblk);
+        ga.lr_step = 64 * per;
+        ga.lr_splits = (nblk + per - 1) / per;
+    }
     ga.out = splits > 1 ? static_cast<void*>(partial) : static_cast<void*>(Y);
     ga.ldo = N; ga.out_split_stride = M * N; ga.out_rows = nullptr; ga.out_scale = nullptr;
     int st = launch_tiled(ga, 1, mb, EPI_STORE, (int)m_tiles, stream);

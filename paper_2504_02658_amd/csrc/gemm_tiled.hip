@@ -294,11 +294,18 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
     // This part is complete once its stores are; the last part of the tile to get here adds all
     // parts in part order (so the sum does not depend on which one that was), writes T as fp16
     // and raises the tile's flag.
+    // With large ranks (t_dist) that sum is too much for one workgroup (t_parts x rows x ranks x 4 bytes
+    // through a single CU): every part then waits until all parts are written, adds its share of the
+    // elements, and the flag counts the parts that are done.  The parts of a tile are neighbours in
+    // dispatch order and none of them waits for anything else, so that wait ends.
     wait_vmem();
     __syncthreads();
     int last = 0;
-    if (tid == 0) last = atomicAdd(a.flags + 4 * by, 1u) == (uint32_t)a.t_parts - 1u;
-    if (!__syncthreads_or(last)) return;
+    if (tid == 0) {
+        last = atomicAdd(a.flags + 4 * by, 1u) == (uint32_t)a.t_parts - 1u;
+        if (a.t_dist) wait_flag(a.flags + 4 * by, (uint32_t)a.t_parts, a.flags_status);
+    }
+    if (!__syncthreads_or(last) && !a.t_dist) return;
 #pragma unroll
     for (int s = 0; s < NW; ++s) {
         const WeightDev& w = ti.w[s];
@@ -308,10 +315,13 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
         const BufRsrc tb = make_rsrc(a.T[s], a.t_bytes);
         // all partials of two elements (up to NB parts at a time) are requested at once: the sum
         // costs a few memory round trips, not one per part
-        const int items = ti.rows * rquads;
+        const int all_items = ti.rows * rquads;
+        const int share = a.t_dist ? (all_items + a.t_parts - 1) / a.t_parts : all_items;
+        const int item_lo = a.t_dist ? part * share : 0;
+        const int items = item_lo + share < all_items ? item_lo + share : all_items;
         auto sum_parts = [&](auto nb_c) {
             constexpr int NB = decltype(nb_c)::value;
-            for (int item0 = tid; item0 < items; item0 += 2 * kTiledThreads) {
+            for (int item0 = item_lo + tid; item0 < items; item0 += 2 * kTiledThreads) {
                 uint32_t at[2];
                 f32x4 sum[2];
 #pragma unroll
@@ -361,8 +371,10 @@ __device__ __forceinline__ void v_tile_body(const TiledArgs& a, const TileInfo& 
     }
     wait_vmem();
     __syncthreads();
-    if (tid == 0)
-        __hip_atomic_store(a.flags + 4 * by + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) {
+        if (a.t_dist) atomicAdd(a.flags + 4 * by + 1, 1u);
+        else __hip_atomic_store(a.flags + 4 * by + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 // Lanes i and i + 32 hold, for the same row of a 32x32 accumulator block, interleaved groups of
@@ -573,7 +585,8 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     // microsecond): the workgroups that form T were dispatched long before, so the answer is nearly
     // always yes, and the wave goes from its last chunk straight to the low-rank term.
     uint32_t early_flag = 0u;
-    const bool wants_t = any_rank && bz == 0;
+    const bool wants_t = any_rank && bz < (uint32_t)a.lr_splits;
+    const uint32_t t_ready = a.t_dist ? (uint32_t)a.t_parts : 1u;     // value of the tile's flag when T is complete
     auto k_loop = [&](auto mbu_c) {
         constexpr int MBU = decltype(mbu_c)::value;
         auto compute = [&](int slot, RawUnit (&ru)[2], auto&& between) {
@@ -649,7 +662,7 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
     // Low-rank term: r extra k-steps with A = U rows and B = T rows.  T of this M-tile is formed
     // by other workgroups of this launch (see v_tile_body): wait for the tile's flag (they were
     // dispatched before this workgroup and never wait themselves), then read T coherently.
-    if (any_rank && bz == 0) {
+    if (wants_t) {
         const BufRsrc tb0 = make_rsrc(a.T[0], a.t_bytes);
         const BufRsrc tb1 = make_rsrc(a.T[1], a.t_bytes);
         // Two k-steps of 16 ranks at a time: their U fragments (which do not depend on T) and then
@@ -737,35 +750,39 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
             // way, so a rank-512 compensator costs about two memory round trips, not sixteen.
             f16x8 avA[2], avB[2];
             u32x4 bvA[2][MB], bvB[2][MB];
-            load_u(0, avA);
+            // ranks of this K split: all of them, or with lr_splits > 1 (large ranks in a split GEMM, whose
+            // partial sums are added anyway) this split's lr_step ranks
+            const int ks_lo = a.lr_splits > 1 ? (int)bz * a.lr_step : 0;
+            const int ks_hi = a.lr_splits > 1 && ks_lo + a.lr_step < r ? ks_lo + a.lr_step : r;
+            load_u(ks_lo, avA);
             if (!waited) {
                 // every wave asks for itself (no barrier: a wave that is done early goes on early)
-                if (lane == 0 && early_flag < 1u) wait_flag(a.flags + 4 * by + 1, 1u, a.flags_status);
+                if (lane == 0 && early_flag < t_ready) wait_flag(a.flags + 4 * by + 1, t_ready, a.flags_status);
                 waited = true;
             }
-            load_t(0, bvA);
-            for (int ks = 0; ks < r; ks += 64) {
-                if (ks + 32 < r) {
+            load_t(ks_lo, bvA);
+            for (int ks = ks_lo; ks < ks_hi; ks += 64) {
+                if (ks + 32 < ks_hi) {
                     load_u(ks + 32, avB);
                     load_t(ks + 32, bvB);
                 }
                 multiply(avA, bvA);
-                if (ks + 64 < r) {
+                if (ks + 64 < ks_hi) {
                     load_u(ks + 64, avA);
                     load_t(ks + 64, bvA);
                 }
-                if (ks + 32 < r) multiply(avB, bvB);
+                if (ks + 32 < ks_hi) multiply(avB, bvB);
             }
         }
         if (!waited) {          // (not reached: some rank is positive)
-            if (lane == 0 && early_flag < 1u) wait_flag(a.flags + 4 * by + 1, 1u, a.flags_status);
+            if (lane == 0 && early_flag < t_ready) wait_flag(a.flags + 4 * by + 1, t_ready, a.flags_status);
         }
         // the last reader of this M-tile's T clears its control words for the next launch (the MoE
         // call clears all of them before every forward instead: the returning atomic is a round
         // trip to memory per workgroup)
         if (a.self_clean) __syncthreads();
         if (a.self_clean && tid == 0) {
-            const uint32_t readers = gx - (uint32_t)a.v_tiles;
+            const uint32_t readers = (gx - (uint32_t)a.v_tiles) * (uint32_t)a.lr_splits;
             if (atomicAdd(a.flags + 4 * by + 2, 1u) == readers - 1u) {
                 __hip_atomic_store(a.flags + 4 * by, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(a.flags + 4 * by + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

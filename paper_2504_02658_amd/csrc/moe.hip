@@ -526,6 +526,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         ga.Tp[0] = Tp1; ga.Tp[1] = Tp3; ga.tp_bytes = (uint64_t)L.parts_up * P * L.ldt * 4;
         ga.t_part_stride = (int64_t)P * L.ldt; ga.t_parts = L.parts_up; ga.v_tiles = L.parts_up; ga.ksplit = 1;
         ga.out_split_stride = 0; ga.flags = flags; ga.self_clean = 0; ga.weights_once = once;
+        ga.t_dist = 0; ga.lr_splits = 1; ga.lr_step = 0;
         ga.flags_status = reinterpret_cast<uint32_t*>(header + 3);
         ga.lr3_rank = r_max < MILO_LR3_MAX_RANK ? r_max : MILO_LR3_MAX_RANK;    // (any weight's compensator may be INT3)
         ga.out = Hbuf; ga.ldo = F; ga.out_rows = nullptr; ga.out_scale = nullptr;
@@ -544,6 +545,7 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         da.t_part_stride = (int64_t)P * L.ldt; da.t_parts = L.parts_down; da.v_tiles = L.parts_down;
         da.ksplit = L.splits_down; da.out_split_stride = (int64_t)P * H; da.flags = flags + 4 * L.max_tiles32;
         da.self_clean = 0; da.weights_once = once;
+        da.t_dist = 0; da.lr_splits = 1; da.lr_step = 0;
         da.flags_status = reinterpret_cast<uint32_t*>(header + 3);
         da.lr3_rank = r_max < MILO_LR3_MAX_RANK ? r_max : MILO_LR3_MAX_RANK;
         da.out = O; da.ldo = H; da.out_rows = sorted; da.out_scale = topk_weights;

@@ -80,6 +80,27 @@ def test_high_rank_compensators(M, N, K, r):
     _check_case(M, N, K, r, seed=500 + M)
 
 
+@pytest.mark.parametrize("M,N,K,r", [(512, 4096, 4096, 512), (300, 2048, 4096, 1024), (512, 4096, 4096, 200)])
+def test_dense_layer_ranks_in_a_split_gemm(M, N, K, r):
+    # Dense-512 / Dense-1024 on an attention-sized projection: too few tiles for the chip, so K is split
+    # over workgroups; the parts of T share the addition of their partial sums and every K split applies
+    # a share of the ranks.  Two runs on one workspace agree bit for bit.
+    import torch
+    from paper_2504_02658_amd import api
+    case = wl.LinearCase("dense", M=M, N=N, K=K, r=r, seed=700 + r)
+    X, W = wl.linear_inputs(case)
+    ow = oracle_weight(W, r, seed=case.seed)
+    pw = gpu_weight(W, ow, check_pack=False)
+    ref = oracle.w3lr_linear(X, **ow)
+    ws = api.new_workspace(api.gemm_workspace_bytes(M, N, K, r))
+    Xd = torch.from_numpy(X).cuda()
+    Y1 = api.w3lr_gemm(Xd, pw, workspace=ws).cpu().numpy()
+    Y2 = api.w3lr_gemm(Xd, pw, workspace=ws).cpu().numpy()
+    assert api.workspace_status(ws) == 0
+    assert_close(Y1, ref, f"M{M} N{N} K{K} r{r}")
+    assert np.array_equal(Y1.view(np.uint16), Y2.view(np.uint16)), "two runs differ"
+
+
 def test_rank_zero_equals_no_compensator_and_is_deterministic():
     import torch
     from paper_2504_02658_amd import api
