@@ -9,6 +9,7 @@
 //   down      O[split][pair] = gate_weight * lin_w2(H) over the split's share of K (fp16, one row
 //             per routed pair); T2 = H V2^T is formed inside this launch as well
 //   combine   y_t = fp16( sum over the token's slots and the K splits, in a fixed order, of O )
+#include <math.h>
 #include <stdlib.h>
 
 #include "milo_host.h"
@@ -394,7 +395,25 @@ static bool moe_layout(int64_t T, int64_t H, int64_t F, int E, int topk, int r_m
     if ((uint64_t)(parts > 0 ? parts : 1) * (uint64_t)P * (uint64_t)L->ldt * 4 >= 0xFFFFFFF0ull) return false;
     // the down projection has few column tiles (hidden / 256): split K when they do not fill the chip
     // (counted in full tiles: the partly filled last tile of an expert is cheap)
-    L->splits_down = tiled_k_splits(((P + L->bm - 1) / L->bm) * ((H + 255) / 256), F, 0);
+    int64_t est_tiles = (P + L->bm - 1) / L->bm;
+    int split_cap = 64;
+    if (L->bm == 32) {
+        // Decode-sized batches: nearly every tile is an expert's only, partly filled one, and it costs a
+        // full pass over the expert's weight whatever its rows, so the tiles to count are the experts
+        // that receive anything: E (1 - (1 - 1/E)^P) for evenly spread pairs.  Measured on the Mixtral
+        // shape (16, 4 and 1 tokens), splits beyond eight lose more to short workgroups than they gain.
+        const double used = (double)E * (1.0 - pow(1.0 - 1.0 / (double)E, (double)P));
+        if ((int64_t)(used + 0.5) > est_tiles) est_tiles = (int64_t)(used + 0.5);
+        split_cap = 8;
+    }
+    L->splits_down = tiled_k_splits(est_tiles * ((H + 255) / 256), F, 0);
+    if (L->splits_down > split_cap) L->splits_down = split_cap;
+    static const int splits_override = [] {
+        const char* e = getenv("MILO_MOE_SPLITS");
+        const int v = e ? atoi(e) : 0;
+        return (v >= 1 && v <= 16) ? v : 0;
+    }();
+    if (splits_override) L->splits_down = splits_override;
     size_t off = 0;
     L->off_header = off; off = align_up(off + 64, 256);
     L->max_tiles32 = max_tiles32;
