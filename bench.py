@@ -11,8 +11,8 @@ value = (packed blob: codes, scales, zero-points; + U + V bytes) / time per step
 Prints ONE JSON line.  Besides the headline it carries, under "extra", the other workloads of the
 metric, each with its own roofline object: c1 at M = 1 and 4, Mixtral's down projection at decode,
 the small configuration c0, the prefill GEMM c2 and the two MoE layers c3 and c4 (plus c3's shape at
-a decode-sized batch), c1 with the INT3 compensator, the symmetric weight and bf16 activations, and the time the compressor (Algorithm 1, offline) takes for one weight of c1's
-shape.  --only NAME[,NAME...] restricts the run to some legs (for profiler runs).
+a decode-sized batch), c1 with the INT3 compensator, the symmetric weight and bf16 activations, the time the compressor (Algorithm 1, offline) takes for one weight of c1's
+shape, and what a library copy and a library fp16 GEMM reach on the same box (context).  --only NAME[,NAME...] restricts the run to some legs (for profiler runs).
 """
 import argparse
 import json
@@ -26,7 +26,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_FP16_PEAK_TFLOPS = 2500.0
 MIN_TIMED_MS = 20.0             # a timed region shorter than this is repeated until it is not
-LEGS = ("c1", "c1_small_m", "c1_variants", "w2_decode", "c0", "c2", "c3", "c4", "compress")
+LEGS = ("c1", "c1_small_m", "c1_variants", "w2_decode", "c0", "c2", "c3", "c4", "compress", "context")
 
 
 def measured_traffic():
@@ -365,6 +365,24 @@ def main():
         extra["compress_c1_weight"] = {"seconds": round(dt, 3), "iters": len(eps_c), "N": cc.N, "K": cc.K, "r": cc.r,
                                        "eps_first": round(eps_c[0], 4), "eps_last": round(eps_c[-1], 4)}
         del Wc
+        torch.cuda.empty_cache()
+
+    if "context" in legs:
+        # What library kernels (not this repository's code) reach on the same box: a device-to-device
+        # copy and a dense fp16 GEMM.  Context for the two rooflines, not a target and not a baseline.
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        ms, _ = time_steps(lambda i: dst.copy_(src), 10, 1, 3)
+        A = torch.randn((8192, 8192), device=dev, dtype=torch.float16)
+        B = torch.randn((8192, 8192), device=dev, dtype=torch.float16)
+        C = torch.empty((8192, 8192), device=dev, dtype=torch.float16)
+        msg, _ = time_steps(lambda i: torch.matmul(A, B, out=C), 10, 1, 3)
+        extra["achievable_context"] = {
+            "note": "library kernels on this box, for context: torch device copy of 1 GiB (bytes read + written) "
+                    "and torch.matmul 8192^3 fp16 with random operands",
+            "copy_TBps": round(2 * (1 << 30) / (ms * 1e-3) / 1e12, 2),
+            "dense_fp16_gemm_TFLOPs": round(2 * 8192.0 ** 3 / (msg * 1e-3) / 1e12, 1)}
+        del src, dst, A, B, C
         torch.cuda.empty_cache()
 
     if extra:

@@ -42,6 +42,15 @@ extern "C" int milo_workspace_init(void* workspace, size_t workspace_bytes, void
     return launch_status();
 }
 
+namespace milo {
+bool gemm_takes_decode(int64_t M, int64_t N, int64_t K, int r) {
+    // Up to 16 rows the weight-streaming kernel wins on every shape measured (the tiled kernel at a
+    // 32-row tile needs K splits and a second kernel for so few tiles: 1.3 to 2 times slower).
+    (void)N; (void)K; (void)r;
+    return M <= 16;
+}
+}  // namespace milo
+
 static int64_t rank_pad(int r) { return ((int64_t)r + 15) / 16 * 16; }
 
 // Tile height (in blocks of 32 rows) and K splits of the tiled kernel for an [M x N x K] problem.
@@ -108,7 +117,7 @@ static bool gemm_shape_ok(int64_t M, int64_t N, int64_t K) {
 
 extern "C" size_t milo_w3lr_gemm_workspace(int64_t M, int64_t N, int64_t K, int r) {
     if (!gemm_shape_ok(M, N, K) || r < 0) return 0;
-    if (M <= 16) return decode_workspace_bytes(r, K);
+    if (gemm_takes_decode(M, N, K, r)) return decode_workspace_bytes(r, K);
     // control words | four flag words per 32-row tile | T = X V^T, fp16 [M x pad16(r)] | its fp32
     // partials per part of K | with K splits, their fp32 partial sums [M x N] each
     const size_t parts = (size_t)gemm_t_parts(M, N, K, r);
@@ -152,7 +161,7 @@ extern "C" int milo_w3lr_gemm_flags(const milo_half* X, int64_t M, int64_t N, in
     w.V = reinterpret_cast<const f16*>(V);
     w.r = r;
     w.flags = flags;
-    const bool decode = M <= 16;
+    const bool decode = gemm_takes_decode(M, N, K, r);
     if (decode) {
         // 32-bit buffer offsets in the decode kernel
         if ((uint64_t)M * K * 2 >= 0xFFFFFFF0ull || ((uint64_t)r + 128) * K * 2 >= 0xFFFFFFF0ull ||

@@ -49,7 +49,7 @@ extern "C" int milo_w3lr_gemm_static(const milo_half* X, int64_t M, int64_t N, i
     // but a call that failed half-way may not have, and the flag words of another shape lie
     // elsewhere: the control block and the flag / sign-off words behind it are cleared first, by
     // a small fill kernel (not a memset, so that the call can be captured in a HIP graph).
-    size_t head = 256 + (M <= 16 ? (size_t)kDecDoneBytes : align_up((size_t)((M + 31) / 32) * 16, 256));
+    size_t head = 256 + (gemm_takes_decode(M, N, K, r) ? (size_t)kDecDoneBytes : align_up((size_t)((M + 31) / 32) * 16, 256));
     if (head > need) head = need;
     const size_t n16 = head / 16;
     scratch_clear_kernel<<<dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(

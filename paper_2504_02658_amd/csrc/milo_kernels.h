@@ -87,6 +87,8 @@ enum { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_SCALE_SCATTER = 2 };
 int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipStream_t stream);
 // Parts of T and K splits the launchers use for a K of nchunks 128-column chunks.
 int tiled_t_parts(int64_t K);
+// Which of the two GEMM kernels milo_w3lr_gemm takes for a problem (true: the weight-streaming decode kernel).
+bool gemm_takes_decode(int64_t M, int64_t N, int64_t K, int r);
 
 constexpr int kDecDoneBytes = 8192;  // sign-off words: up to 2048 resident workgroups
 constexpr int kDecMaxWorkers = 32;  // workgroups forming T = X V^T in the decode kernel
