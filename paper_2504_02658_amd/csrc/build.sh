@@ -50,10 +50,13 @@ for m in re.finditer(r"^(_ZN4milo18w3lr_decode_kernelILi(\d+)ELi(\d+)ELi(\d+)E\S
     for b in range(1, R):
         want += [2 * (R - 1) + XC] + unit                           #       unit b, next unit b
     want += nz([2 * (R - 1 - b) for b in range(R)])                 # last chunk
-    first = next((i for i, e in enumerate(ev) if e == "buffer_load_dwordx4 lds"), None)
-    got = ev[first:first + len(want)] if first is not None else None
-    if got != want:
-        sys.exit("%s: requests and waits of the streaming loop are not in the counted order:\n%r\nexpected\n%r" % (name, got, want))
+    # the streaming loop is the one place with counted waits: its whole sequence must appear as it is
+    # (what a T worker does before it, when it goes on to stream, is complete by then: it ends with a
+    # wait for everything)
+    found = any(ev[i:i + len(want)] == want for i in range(len(ev) - len(want) + 1))
+    counted = [e for e in ev if isinstance(e, int)]
+    if not found or counted != [e for e in want if isinstance(e, int)]:
+        sys.exit("%s: requests and waits of the streaming loop are not in the counted order:\n%r\nexpected\n%r" % (name, ev, want))
     checked += 1
 if checked == 0:
     sys.exit("decode kernel: nothing checked; the check is out of date")
