@@ -140,6 +140,46 @@ def test_compressed_weight_feeds_the_gemm():
     q, s, z = oracle.quantize_rtn(W)
     rtn = X.astype(np.float64) @ oracle.dequantize(q, s, z).T
     assert np.linalg.norm(Y - exact) < 0.9 * np.linalg.norm(rtn - exact)
+    # Algorithm 1's last line: U, V quantized to INT3, consumed by the kernel as blobs
+    U32, V32 = out["U"].astype(np.float32), out["V"].astype(np.float32)
+    u3, v3 = api.pack_lr3(torch.from_numpy(U32).cuda(), torch.from_numpy(V32).cuda())
+    uq, vq = oracle.quantize_compensator(U32, V32)
+    assert np.array_equal(u3.cpu().numpy(), oracle.pack_w3(*uq)) and np.array_equal(v3.cpu().numpy(), oracle.pack_w3(*vq))
+    Ud, Vd = oracle.dequantize_compensator(uq, vq, r)
+    Y3 = api.w3lr_gemm(torch.from_numpy(X).cuda(), out["pw"].with_int3_compensator(u3, v3, r)).cpu().numpy()
+    assert_close(Y3, oracle.w3lr_linear(X, out["codes"], out["scales"], out["zeros"], Ud, Vd), "INT3 compensator")
+    assert np.linalg.norm(Y3 - exact) < 0.95 * np.linalg.norm(rtn - exact)
+
+
+@pytest.mark.parametrize("N,K,r", [(16, 64, 0), (16, 64, 8), (48, 192, 40), (272, 1408, 128), (256, 512, 128)])
+def test_smallest_and_largest_shapes(N, K, r):
+    # one row block and one group; a rank that fills min(N, K) up to the sketch; the largest rank the call
+    # takes (its factorizations then need nearly all of a workgroup's LDS)
+    W = wl.gen_weight_lowrank(N, K, seed=3600 + N + r, modes=min(4, N // 4))
+    ref = oracle.milo_compress(W, r, iters=3, tol=-1.0)
+    out = _compress(W, r, iters=3, tol=-1.0, power_iters=30, refine_iters=10)
+    assert len(out["eps"]) == 3
+    rel = np.abs(np.array(out["eps"]) / np.array(ref["eps"]) - 1.0)
+    assert np.all(rel <= 5e-3), (out["eps"], ref["eps"])
+    _check_outputs(W, out, r, f"N{N} K{K} r{r}")
+
+
+def test_constant_and_zero_groups():
+    # groups without a range (scale 1, codes 0, z = -w) next to ordinary ones; an all-zero weight
+    import torch
+    W = wl.gen_weight(64, 256, seed=3700)
+    W[:8, :64] = 0.25
+    W[8:16, 64:128] = 0.0
+    W[16:24] = 0.0
+    for r in (0, 8):
+        ref = oracle.milo_compress(W, r, iters=2, tol=-1.0)
+        out = _compress(W, r, iters=2, tol=-1.0, power_iters=20)
+        assert np.all(np.isfinite(out["eps"])) and np.all(np.isfinite(out["U"])) and np.all(np.isfinite(out["V"]))
+        assert np.allclose(out["eps"], ref["eps"], rtol=5e-3)
+        _check_outputs(W, out, r, f"degenerate groups, r={r}")
+    out = _compress(np.zeros((32, 128), np.float32), 8, iters=2, tol=-1.0)
+    assert np.all(np.array(out["eps"]) == 0.0) and np.all(out["codes"] == 0)
+    assert np.all(out["U"] @ out["V"] == 0.0)
 
 
 @pytest.mark.timeout(600)
