@@ -266,10 +266,10 @@ int milo_w3lr_gemm_static(const milo_half* X, int64_t M, int64_t N, int64_t K,
  *   MILO_LR_INT3       U and V are not fp16 arrays but the INT3 blobs written by milo_pack_lr3
  *                      (Section 3.2.3, "Quantized low-rank mixture compensators"; the last step of
  *                      Algorithm 1).  Needs r <= MILO_LR3_MAX_RANK and N % 64 == 0.
- *   MILO_ACT_BF16      (milo_w3lr_gemm_flags only) X, U, V and Y are bfloat16 instead of fp16: the
- *                      weights are dequantized to bf16 (one rounding each, computed in binary32) and
- *                      multiplied on the bf16 matrix cores, accumulation stays fp32.  Cannot be
- *                      combined with MILO_LR_INT3; the MoE call takes fp16 only.
+ *   MILO_ACT_BF16      (a call flag: milo_w3lr_gemm_flags, milo_moe_w3lr_forward_flags; not stored in a
+ *                      weight) X, U, V and Y are bfloat16 instead of fp16: the weights are dequantized
+ *                      to bf16 (one rounding each, computed in binary32) and multiplied on the bf16
+ *                      matrix cores, accumulation stays fp32.  Cannot be combined with MILO_LR_INT3.
  */
 #define MILO_W3_SYMMETRIC 1u
 #define MILO_LR_INT3 2u
@@ -297,6 +297,10 @@ typedef struct milo_w3lr_expert {
  */
 int milo_moe_w3lr_check_experts(const milo_w3lr_expert* experts, int E, int64_t H, int64_t F,
                                 int* r_max_out);
+/* The same for a table that will be used with call flags (MILO_ACT_BF16: the compensators are bf16
+ * arrays, and no weight may carry MILO_LR_INT3).  Errors: as above; SHAPE also for unknown flags. */
+int milo_moe_w3lr_check_experts_flags(const milo_w3lr_expert* experts, int E, int64_t H, int64_t F,
+                                      unsigned flags, int* r_max_out);
 
 /*
  * Top-k routed MoE feed-forward layer over compensated W3A16 experts:
@@ -323,6 +327,17 @@ int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, int64_t F,
                           const milo_w3lr_expert* experts, int E, int r_max,
                           const int32_t* topk_ids, const float* topk_weights, int topk,
                           milo_half* Y, void* workspace, size_t workspace_bytes, void* stream);
+/*
+ * The same with call flags: 0, or MILO_ACT_BF16 for bfloat16 X, Y and compensators (the intermediate
+ * SwiGLU output and the per-pair expert outputs are bfloat16 too).  The expert table must have passed
+ * milo_moe_w3lr_check_experts_flags with the same flags.  milo_moe_w3lr_forward is this call with flags 0.
+ * Errors: as milo_moe_w3lr_forward; SHAPE also for unknown flags.
+ */
+int milo_moe_w3lr_forward_flags(const milo_half* X, int64_t T, int64_t H, int64_t F,
+                                const milo_w3lr_expert* experts, int E, int r_max,
+                                const int32_t* topk_ids, const float* topk_weights, int topk,
+                                unsigned flags, milo_half* Y, void* workspace, size_t workspace_bytes,
+                                void* stream);
 
 /*
  * Waits for `stream` and returns MILO_ERR_ROUTING if the last milo_moe_w3lr_forward that used

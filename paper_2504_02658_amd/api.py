@@ -29,7 +29,8 @@ EXPORTS = ("milo_status_string", "milo_version", "milo_w3_packed_bytes", "milo_p
            "milo_unpack_w3", "milo_dequant_w3", "milo_w3lr_gemm_workspace", "milo_w3lr_gemm",
            "milo_w3lr_gemm_static", "milo_w3lr_gemm_flags", "milo_lr3_packed_bytes", "milo_pack_lr3",
            "milo_moe_w3lr_check_experts", "milo_moe_w3lr_workspace", "milo_moe_w3lr_forward",
-           "milo_moe_w3lr_routing_status", "milo_compress_w3lr_workspace", "milo_compress_w3lr")
+           "milo_moe_w3lr_routing_status", "milo_moe_w3lr_check_experts_flags", "milo_moe_w3lr_forward_flags",
+           "milo_compress_w3lr_workspace", "milo_compress_w3lr")
 
 
 class MiloError(RuntimeError):
@@ -101,6 +102,11 @@ def bind(path):
     L.milo_moe_w3lr_check_experts.restype = ci
     L.milo_moe_w3lr_check_experts.argtypes = [ctypes.POINTER(Expert), ci, i64, i64,
                                               ctypes.POINTER(ci)]
+    L.milo_moe_w3lr_check_experts_flags.restype = ci
+    L.milo_moe_w3lr_check_experts_flags.argtypes = [ctypes.POINTER(Expert), ci, i64, i64, ctypes.c_uint,
+                                                    ctypes.POINTER(ci)]
+    L.milo_moe_w3lr_forward_flags.restype = ci
+    L.milo_moe_w3lr_forward_flags.argtypes = [vp, i64, i64, i64, vp, ci, ci, vp, vp, ci, ctypes.c_uint, vp, vp, sz, vp]
     L.milo_moe_w3lr_workspace.restype = sz
     L.milo_moe_w3lr_workspace.argtypes = [i64, i64, i64, ci, ci, ci]
     L.milo_moe_w3lr_forward.restype = ci
@@ -305,16 +311,18 @@ def w3lr_gemm_static(X, pw, out=None):
 class MoELayer:
     """Expert table of one MoE layer: validates on the host, keeps the device copy of the table."""
 
-    def __init__(self, experts, H, F):
-        # experts: list of (w1, w3, w2) PackedWeight triples
+    def __init__(self, experts, H, F, bf16=False):
+        # experts: list of (w1, w3, w2) PackedWeight triples; bf16: the layer runs on bfloat16 activations
+        # (compensators are bf16 arrays then)
         self.H, self.F, self.E = int(H), int(F), len(experts)
+        self.flags = ACT_BF16 if bf16 else 0
         self.experts = experts                      # keeps the device buffers alive
         arr = (Expert * self.E)()
         for e, (w1, w3, w2) in enumerate(experts):
             arr[e] = Expert(w1.c_struct(), w3.c_struct(), w2.c_struct())
         rmax = ctypes.c_int(0)
-        _check(lib().milo_moe_w3lr_check_experts(arr, self.E, self.H, self.F, ctypes.byref(rmax)),
-               "milo_moe_w3lr_check_experts")
+        _check(lib().milo_moe_w3lr_check_experts_flags(arr, self.E, self.H, self.F, self.flags, ctypes.byref(rmax)),
+               "milo_moe_w3lr_check_experts_flags")
         self.r_max = int(rmax.value)
         host = np.frombuffer(bytes(arr), dtype=np.uint8).copy()
         self.table = torch.from_numpy(host).cuda()
@@ -324,7 +332,8 @@ class MoELayer:
         return int(lib().milo_moe_w3lr_workspace(T, self.H, self.F, self.E, topk, self.r_max))
 
     def forward(self, X, ids, gates, out=None, workspace=None):
-        X = _dev(X, torch.float16, "X")
+        dt = torch.bfloat16 if self.flags & ACT_BF16 else torch.float16
+        X = _dev(X, dt, "X")
         ids = _dev(ids, torch.int32, "ids")
         gates = _dev(gates, torch.float32, "gates")
         T, H = X.shape
@@ -335,11 +344,17 @@ class MoELayer:
                 self._ws = new_workspace(need, X.device)
             workspace = self._ws
         if out is None:
-            out = torch.empty((T, H), dtype=torch.float16, device=X.device)
-        _check(lib().milo_moe_w3lr_forward(_ptr(X), T, H, self.F, _ptr(self.table), self.E,
-                                           self.r_max, _ptr(ids), _ptr(gates), topk, _ptr(out),
-                                           _ptr(workspace), workspace.numel(), _stream()),
-               "milo_moe_w3lr_forward")
+            out = torch.empty((T, H), dtype=dt, device=X.device)
+        if self.flags:
+            _check(lib().milo_moe_w3lr_forward_flags(_ptr(X), T, H, self.F, _ptr(self.table), self.E,
+                                                     self.r_max, _ptr(ids), _ptr(gates), topk, self.flags, _ptr(out),
+                                                     _ptr(workspace), workspace.numel(), _stream()),
+                   "milo_moe_w3lr_forward_flags")
+        else:
+            _check(lib().milo_moe_w3lr_forward(_ptr(X), T, H, self.F, _ptr(self.table), self.E,
+                                               self.r_max, _ptr(ids), _ptr(gates), topk, _ptr(out),
+                                               _ptr(workspace), workspace.numel(), _stream()),
+                   "milo_moe_w3lr_forward")
         self.last_workspace = workspace
         return out
 

@@ -206,6 +206,7 @@ extern "C" int milo_w3lr_gemm_flags(const milo_half* X, int64_t M, int64_t N, in
     ga.flags = tile_flags; ga.flags_status = ctrl + 3; ga.weights_once = m_tiles == 1;
     ga.lr3_rank = (w.flags & MILO_LR_INT3) ? r : 0;
     ga.self_clean = 1;
+    ga.act_bf16 = (flags & MILO_ACT_BF16) ? 1 : 0;
     // Ranks of the size the paper gives dense layers (Section 3.2.2, Dense-512, Dense-1024): the parts of T
     // share the addition of their partial sums, and with K splits every split applies a share of the
     // ranks (the fp32 partial sums of the splits are added anyway), in blocks of 64.

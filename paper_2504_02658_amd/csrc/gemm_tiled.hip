@@ -811,11 +811,17 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
             u32x2 o[4];
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
-                f16x4 v;
+                float g[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    v[e] = (f16)(silu(acc[0][mb][4 * vq + e]) * acc[1][mb][4 * vq + e]);
-                o[vq] = __builtin_bit_cast(u32x2, v);
+                for (int e = 0; e < 4; ++e) g[e] = silu(acc[0][mb][4 * vq + e]) * acc[1][mb][4 * vq + e];
+                if (BF) {
+                    o[vq] = u32x2{pack_bf16(g[0], g[1]), pack_bf16(g[2], g[3])};
+                } else {
+                    f16x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (f16)g[e];
+                    o[vq] = __builtin_bit_cast(u32x2, v);
+                }
             }
             store16(orow, n0 + 32 * wave, o);
         } else {
@@ -848,8 +854,9 @@ __global__ __launch_bounds__(kTiledThreads, 2) void w3lr_tiled_kernel(const Tile
 #pragma unroll
                     for (int vq = 0; vq < 4; ++vq) {
                         if (BF) {
-                            o[vq] = u32x2{pack_bf16(acc[s][mb][4 * vq], acc[s][mb][4 * vq + 1]),
-                                          pack_bf16(acc[s][mb][4 * vq + 2], acc[s][mb][4 * vq + 3])};
+                            const float m = EPI == EPI_STORE ? 1.0f : sc;
+                            o[vq] = u32x2{pack_bf16(m * acc[s][mb][4 * vq], m * acc[s][mb][4 * vq + 1]),
+                                          pack_bf16(m * acc[s][mb][4 * vq + 2], m * acc[s][mb][4 * vq + 3])};
                         } else {
                             f16x4 v;
 #pragma unroll
@@ -910,15 +917,18 @@ int launch_tiled(const TiledArgs& a, int nw, int mb, int epi, int m_tiles, hipSt
     TiledArgs b = a;
     b.m_tiles = m_tiles;
     dim3 grid((unsigned)(n_tiles * rows8));
-    if (nw == 2 && epi == EPI_SWIGLU) return launch_tiled_mb<2, EPI_SWIGLU>(b, mb, grid, stream);
+    if (nw == 2 && epi == EPI_SWIGLU)
+        return a.act_bf16 ? launch_tiled_mb<2, EPI_SWIGLU, 2>(b, mb, grid, stream)
+                          : launch_tiled_mb<2, EPI_SWIGLU>(b, mb, grid, stream);
     if (nw == 1 && epi == EPI_STORE) {
+        if (a.act_bf16) return launch_tiled_mb<1, EPI_STORE, 2>(b, mb, grid, stream);
         // the single linear knows its one weight: a symmetric blob takes the zero-point-free conversion
-        if (!a.rs.tiles && (a.rs.w[0].flags & MILO_ACT_BF16)) return launch_tiled_mb<1, EPI_STORE, 2>(b, mb, grid, stream);
         if (!a.rs.tiles && (a.rs.w[0].flags & MILO_W3_SYMMETRIC)) return launch_tiled_mb<1, EPI_STORE, 1>(b, mb, grid, stream);
         return launch_tiled_mb<1, EPI_STORE>(b, mb, grid, stream);
     }
     if (nw == 1 && epi == EPI_SCALE_SCATTER)
-        return launch_tiled_mb<1, EPI_SCALE_SCATTER>(b, mb, grid, stream);
+        return a.act_bf16 ? launch_tiled_mb<1, EPI_SCALE_SCATTER, 2>(b, mb, grid, stream)
+                          : launch_tiled_mb<1, EPI_SCALE_SCATTER>(b, mb, grid, stream);
     return MILO_ERR_SHAPE;
 }
 

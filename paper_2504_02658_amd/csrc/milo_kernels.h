@@ -63,6 +63,7 @@ struct TiledArgs {
     int weights_once;   // non-zero: every weight is read by one M-tile only (non-temporal loads)
     uint32_t* flags;    // per M-tile t: [4t] parts done, [4t+1] T ready, [4t+2] readers done; zero at launch
     int self_clean;     // non-zero: the last reader of a tile's T clears its words (else the caller does before the next launch)
+    int act_bf16;       // non-zero: activations, compensators and outputs are bfloat16 (MILO_ACT_BF16)
     int t_dist;         // non-zero: every part of T adds a share of the rows once all parts are written, and the
                         // tile's flag counts the parts that are done (large ranks; the single GEMM only)
     int lr_splits;      // K splits that apply the low-rank term, each to lr_step ranks (1: the first split does all)

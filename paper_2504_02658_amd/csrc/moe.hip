@@ -316,7 +316,9 @@ __global__ __launch_bounds__(kSmallPairs) void route_small_kernel(const RouteArg
     }
 }
 
-// y[t, h..h+3] = fp16( sum_j O[t*topk + j, h..h+3] ), slots in order, invalid ids skipped.
+// y[t, h..h+3] = fp16( sum_j O[t*topk + j, h..h+3] ), slots in order, invalid ids skipped.  BF: rows
+// and result are bfloat16.
+template <bool BF>
 __global__ __launch_bounds__(256) void combine_kernel(const f16* __restrict__ O, int splits,
                                                       int64_t split_stride,
                                                       const int32_t* __restrict__ ids, int E,
@@ -329,7 +331,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const f16* __restrict__ O,
     f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
     const int total = topk * splits;
     for (int base = 0; base < total; base += 8) {
-        f16x4 v[8];
+        u32x2 v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int q = base + i;
@@ -339,18 +341,33 @@ __global__ __launch_bounds__(256) void combine_kernel(const f16* __restrict__ O,
                 const int id = ids[t * topk + j];
                 ok = id >= 0 && id < E;
             }
-            v[i] = f16x4{(f16)0.0f, (f16)0.0f, (f16)0.0f, (f16)0.0f};
-            if (ok) v[i] = *reinterpret_cast<const f16x4*>(O + s * split_stride + (t * topk + j) * H + h);
+            v[i] = u32x2{0u, 0u};
+            if (ok) v[i] = *reinterpret_cast<const u32x2*>(O + s * split_stride + (t * topk + j) * H + h);
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < 8; ++i) {
+            if (BF) {       // a bfloat16 is the upper half of the binary32 with the same value
+                sum[0] += __builtin_bit_cast(float, v[i].x << 16);
+                sum[1] += __builtin_bit_cast(float, v[i].x & 0xffff0000u);
+                sum[2] += __builtin_bit_cast(float, v[i].y << 16);
+                sum[3] += __builtin_bit_cast(float, v[i].y & 0xffff0000u);
+            } else {
+                const f16x4 f = __builtin_bit_cast(f16x4, v[i]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) sum[e] += (float)v[i][e];
+                for (int e = 0; e < 4; ++e) sum[e] += (float)f[e];
+            }
+        }
     }
-    f16x4 o;
+    u32x2 ob;
+    if (BF) {
+        ob = u32x2{pack_bf16(sum[0], sum[1]), pack_bf16(sum[2], sum[3])};
+    } else {
+        f16x4 o;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = (f16)sum[e];
-    *reinterpret_cast<f16x4*>(Y + t * H + h) = o;
+        for (int e = 0; e < 4; ++e) o[e] = (f16)sum[e];
+        ob = __builtin_bit_cast(u32x2, o);
+    }
+    *reinterpret_cast<u32x2*>(Y + t * H + h) = ob;
 }
 
 struct MoeLayout {
@@ -452,7 +469,13 @@ using namespace milo;
 
 extern "C" int milo_moe_w3lr_check_experts(const milo_w3lr_expert* experts, int E, int64_t H,
                                            int64_t F, int* r_max_out) {
+    return milo_moe_w3lr_check_experts_flags(experts, E, H, F, 0u, r_max_out);
+}
+
+extern "C" int milo_moe_w3lr_check_experts_flags(const milo_w3lr_expert* experts, int E, int64_t H,
+                                                 int64_t F, unsigned flags, int* r_max_out) {
     if (!experts) return MILO_ERR_NULL;
+    if (flags & ~MILO_ACT_BF16) return MILO_ERR_SHAPE;
     if (E <= 0 || !weight_shape_ok(F, H) || !weight_shape_ok(H, F)) return MILO_ERR_SHAPE;
     int r_max = 0;
     for (int e = 0; e < E; ++e) {
@@ -461,6 +484,8 @@ extern "C" int milo_moe_w3lr_check_experts(const milo_w3lr_expert* experts, int 
             const int64_t N = (i < 2) ? F : H, K = (i < 2) ? H : F;
             const int st = check_weight(*ws[i], N, K);
             if (st != MILO_OK) return st;
+            // the bf16 kernels read U and V as bf16 arrays: no INT3 compensators there
+            if ((flags & MILO_ACT_BF16) && ws[i]->r > 0 && (ws[i]->flags & MILO_LR_INT3)) return MILO_ERR_SHAPE;
             if (ws[i]->r > r_max) r_max = ws[i]->r;
         }
         // gate and up projection share a launch: their compensators are both INT3 or both fp16
@@ -484,7 +509,18 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
                                      const int32_t* topk_ids, const float* topk_weights, int topk,
                                      milo_half* Y, void* workspace, size_t workspace_bytes,
                                      void* stream_) {
+    return milo_moe_w3lr_forward_flags(X, T, H, F, experts, E, r_max, topk_ids, topk_weights, topk, 0u, Y, workspace,
+                                       workspace_bytes, stream_);
+}
+
+extern "C" int milo_moe_w3lr_forward_flags(const milo_half* X, int64_t T, int64_t H, int64_t F,
+                                           const milo_w3lr_expert* experts, int E, int r_max,
+                                           const int32_t* topk_ids, const float* topk_weights, int topk,
+                                           unsigned call_flags, milo_half* Y, void* workspace, size_t workspace_bytes,
+                                           void* stream_) {
     if (!X || !experts || !topk_ids || !topk_weights || !Y) return MILO_ERR_NULL;
+    if (call_flags & ~MILO_ACT_BF16) return MILO_ERR_SHAPE;
+    const int bf = (call_flags & MILO_ACT_BF16) ? 1 : 0;
     MoeLayout L;
     if (!moe_layout(T, H, F, E, topk, r_max, &L)) return MILO_ERR_SHAPE;
     if (r_max > H || r_max > F) return MILO_ERR_RANK;
@@ -545,9 +581,9 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         ga.Tp[0] = Tp1; ga.Tp[1] = Tp3; ga.tp_bytes = (uint64_t)L.parts_up * P * L.ldt * 4;
         ga.t_part_stride = (int64_t)P * L.ldt; ga.t_parts = L.parts_up; ga.v_tiles = L.parts_up; ga.ksplit = 1;
         ga.out_split_stride = 0; ga.flags = flags; ga.self_clean = 0; ga.weights_once = once;
-        ga.t_dist = 0; ga.lr_splits = 1; ga.lr_step = 0;
+        ga.t_dist = 0; ga.lr_splits = 1; ga.lr_step = 0; ga.act_bf16 = bf;
         ga.flags_status = reinterpret_cast<uint32_t*>(header + 3);
-        ga.lr3_rank = r_max < MILO_LR3_MAX_RANK ? r_max : MILO_LR3_MAX_RANK;    // (any weight's compensator may be INT3)
+        ga.lr3_rank = bf ? 0 : (r_max < MILO_LR3_MAX_RANK ? r_max : MILO_LR3_MAX_RANK);    // (any weight's compensator may be INT3)
         ga.out = Hbuf; ga.ldo = F; ga.out_rows = nullptr; ga.out_scale = nullptr;
         st = launch_tiled(ga, 2, mb, EPI_SWIGLU, L.max_tiles, stream);
         if (st != MILO_OK) return st;
@@ -564,9 +600,9 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
         da.t_part_stride = (int64_t)P * L.ldt; da.t_parts = L.parts_down; da.v_tiles = L.parts_down;
         da.ksplit = L.splits_down; da.out_split_stride = (int64_t)P * H; da.flags = flags + 4 * L.max_tiles32;
         da.self_clean = 0; da.weights_once = once;
-        da.t_dist = 0; da.lr_splits = 1; da.lr_step = 0;
+        da.t_dist = 0; da.lr_splits = 1; da.lr_step = 0; da.act_bf16 = bf;
         da.flags_status = reinterpret_cast<uint32_t*>(header + 3);
-        da.lr3_rank = r_max < MILO_LR3_MAX_RANK ? r_max : MILO_LR3_MAX_RANK;
+        da.lr3_rank = bf ? 0 : (r_max < MILO_LR3_MAX_RANK ? r_max : MILO_LR3_MAX_RANK);
         da.out = O; da.ldo = H; da.out_rows = sorted; da.out_scale = topk_weights;
         st = launch_tiled(da, 1, mb, EPI_SCALE_SCATTER, L.max_tiles, stream);
         if (st != MILO_OK) return st;
@@ -577,12 +613,14 @@ extern "C" int milo_moe_w3lr_forward(const milo_half* X, int64_t T, int64_t H, i
             // grid.y limit: split the token range
             for (int64_t t0 = 0; t0 < T; t0 += 65535) {
                 const int64_t nt = (T - t0) < 65535 ? (T - t0) : 65535;
-                combine_kernel<<<dim3(gx, (unsigned)nt), dim3(256), 0, stream>>>(
+                auto kern = bf ? combine_kernel<true> : combine_kernel<false>;
+                kern<<<dim3(gx, (unsigned)nt), dim3(256), 0, stream>>>(
                     O + t0 * topk * H, L.splits_down, (int64_t)P * H, topk_ids + t0 * topk, E, topk, nt, H,
                     reinterpret_cast<f16*>(Y) + t0 * H);
             }
         } else {
-            combine_kernel<<<dim3(gx, (unsigned)T), dim3(256), 0, stream>>>(
+            auto kern = bf ? combine_kernel<true> : combine_kernel<false>;
+            kern<<<dim3(gx, (unsigned)T), dim3(256), 0, stream>>>(
                 O, L.splits_down, (int64_t)P * H, topk_ids, E, topk, T, H, reinterpret_cast<f16*>(Y));
         }
         st = launch_status();

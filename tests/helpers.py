@@ -70,9 +70,16 @@ def int3_weight(W, ow):
     return dict(ow, U=Ud, V=Vd), pw.with_int3_compensator(u3, v3, r)
 
 
-def build_moe(case, threads=8, int3=False):
+def to_bf16(x):
+    """Round to bfloat16 (a torch CPU tensor; numpy has no such type)."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(np.asarray(x, np.float32))).to(torch.bfloat16)
+
+
+def build_moe(case, threads=8, int3=False, bf16=False):
     """Both sides of an MoE layer: list of oracle expert dicts and the library's MoELayer.
-    int3: every compensator is INT3-quantized (on both sides)."""
+    int3: every compensator is INT3-quantized (on both sides).  bf16: the layer runs on bfloat16
+    activations; the compensators are rounded to bfloat16 on both sides."""
     from paper_2504_02658_amd import api
     ranks = wl.expert_ranks(case)
     n_exp = case.E + case.n_shared
@@ -92,10 +99,20 @@ def build_moe(case, threads=8, int3=False):
             pairs = {k: int3_weight(b[k][0], b[k][1]) for k in ("w1", "w3", "w2")}
             o_experts.append({k: pairs[k][0] for k in pairs})
             g_experts.append(tuple(pairs[k][1] for k in ("w1", "w3", "w2")))
+        elif bf16:
+            oe, ge = {}, []
+            for k in ("w1", "w3", "w2"):
+                W, ow = b[k]
+                Ub, Vb = to_bf16(ow["U"]), to_bf16(ow["V"])
+                oe[k] = dict(ow, U=Ub.float().numpy(), V=Vb.float().numpy())
+                pw = gpu_weight(W, dict(ow, U=np.zeros((W.shape[0], 0), np.float16)))
+                ge.append(pw.with_compensator(Ub.cuda(), Vb.cuda()) if ow["U"].shape[1] else pw)
+            o_experts.append(oe)
+            g_experts.append(tuple(ge))
         else:
             o_experts.append({k: b[k][1] for k in b})
             g_experts.append(tuple(gpu_weight(b[k][0], b[k][1]) for k in ("w1", "w3", "w2")))
         for k in b:
             b[k] = None
-    layer = api.MoELayer(g_experts, case.H, case.F)
+    layer = api.MoELayer(g_experts, case.H, case.F, bf16=bf16)
     return o_experts, layer

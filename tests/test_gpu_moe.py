@@ -44,6 +44,49 @@ def test_int3_compensators_in_a_layer():
     _check(wl.scaled(base, T=400, name="int3_128", rank_choices=(16, 32, 128)), int3=True)
 
 
+# bfloat16 layer (MILO_ACT_BF16): on top of the single linear's roundings (every dequantized weight, T, the
+# output: see test_gpu_gemm) the SwiGLU output and every routed pair's expert output are rounded to bf16
+# (2^-9 relative at most, 5.6e-4 rms each) and the second linear sees the first one's error: about 1.3e-3
+# rms in all, bounded here by 6e-3; single elements by 4e-2 of the largest output.
+BF16_MOE_REL_FRO_TOL, BF16_MOE_MAX_ABS_TOL = 6e-3, 4e-2
+
+
+def _check_bf16(case):
+    import torch
+    from helpers import to_bf16
+    o_experts, layer = build_moe(case, bf16=True)
+    Xb = to_bf16(wl.moe_activations(case))
+    ids, gates = wl.moe_routing(case)
+    ref = oracle.moe_forward(Xb.float().numpy(), o_experts, ids, gates)
+    args = (Xb.cuda(), torch.from_numpy(ids).cuda(), torch.from_numpy(gates).cuda())
+    Y = layer.forward(*args)
+    assert Y.dtype == torch.bfloat16
+    Yf = Y.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(Yf))
+    rel = np.linalg.norm(Yf - ref) / np.linalg.norm(ref)
+    mx = np.max(np.abs(Yf - ref)) / np.max(np.abs(ref))
+    assert rel <= BF16_MOE_REL_FRO_TOL and mx <= BF16_MOE_MAX_ABS_TOL, (case.name, rel, mx)
+    assert layer.routing_status() == 0
+    assert torch.equal(Y, layer.forward(*args)), "two runs differ"
+
+
+def test_bf16_layer():
+    base = wl.MoECase("bf16", T=40, H=256, F=384, E=4, topk=2, seed=31, rank_choices=(0, 8, 16, 40))
+    _check_bf16(base)                                                           # 32-row tiles
+    _check_bf16(wl.scaled(base, T=400, name="bf16_128"))                        # 128-row tiles, several per expert
+    _check_bf16(wl.scaled(base, T=3, name="bf16_small"))                        # single-launch routing
+    _check_bf16(wl.scaled(wl.C4, T=512, H=512, F=704, name="bf16_c4_reduced"))  # shared experts, K splits
+
+
+def test_bf16_layer_rejects_int3_compensators():
+    from paper_2504_02658_amd import api
+    case = wl.MoECase("bf16_int3", T=8, H=256, F=384, E=2, topk=1, seed=32, rank_choices=(16,))
+    _, layer = build_moe(case, int3=True)
+    with pytest.raises(api.MiloError) as ei:
+        api.MoELayer(layer.experts, case.H, case.F, bf16=True)
+    assert ei.value.status == 2
+
+
 def test_many_tiles_take_the_xcd_placement_path():
     # 16 800 routed rows -> more than 128 M-tiles: the grouped kernels renumber their workgroups
     # per XCD and the work list is dealt over the eight ranges
