@@ -75,7 +75,7 @@ def test_bf16_layer():
     _check_bf16(base)                                                           # 32-row tiles
     _check_bf16(wl.scaled(base, T=400, name="bf16_128"))                        # 128-row tiles, several per expert
     _check_bf16(wl.scaled(base, T=3, name="bf16_small"))                        # single-launch routing
-    _check_bf16(wl.scaled(wl.C4, T=512, H=512, F=704, name="bf16_c4_reduced"))  # shared experts, K splits
+    _check_bf16(wl.scaled(wl.C4, T=256, H=512, F=704, E=16, name="bf16_c4_reduced"))  # shared experts, K splits
 
 
 def test_bf16_layer_rejects_int3_compensators():
@@ -139,7 +139,7 @@ def test_shared_experts_and_skew():
 
 def test_reduced_mixtral_and_deepseek_shapes():
     _check(wl.scaled(wl.C3, T=96, H=512, F=1792, name="c3_reduced"))
-    _check(wl.scaled(wl.C4, T=512, H=512, F=704, name="c4_reduced"))
+    _check(wl.scaled(wl.C4, T=512, H=512, F=704, E=24, name="c4_reduced"))
 
 
 def test_out_of_range_expert_id_is_skipped_and_flagged():
