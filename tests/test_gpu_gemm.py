@@ -328,6 +328,25 @@ def test_int3_compensator(M, N, K, r):
     assert_close(_run(X, pw), ref, f"INT3 compensator M{M} N{N} K{K} r{r}")
 
 
+def test_int3_and_bf16_compensators_in_a_split_gemm():
+    # rank 128 as INT3 blobs and rank 200 in bf16 on a projection whose K is split over workgroups: the
+    # K splits share the ranks, the parts of T share their sums
+    import torch
+    from paper_2504_02658_amd import api
+    X, pw, ref = _int3_case(512, 4096, 4096, 128, seed=901)
+    assert_close(_run(X, pw), ref, "INT3 rank 128, split GEMM")
+    case = wl.LinearCase("t", M=512, N=4096, K=4096, r=200, seed=902)
+    X, W = wl.linear_inputs(case)
+    ow = oracle_weight(W, 200, seed=902)
+    Xb, Ub, Vb = _to_bf16(X), _to_bf16(ow["U"]), _to_bf16(ow["V"])
+    ref = oracle.w3lr_linear(Xb.float().numpy(), ow["codes"], ow["scales"], ow["zeros"], Ub.float().numpy(), Vb.float().numpy())
+    pw = gpu_weight(W, dict(ow, U=np.zeros((4096, 0), np.float16)), check_pack=False).with_compensator(Ub.cuda(), Vb.cuda())
+    Yf = api.w3lr_gemm(Xb.cuda(), pw).float().cpu().numpy().astype(np.float64)
+    rel = np.linalg.norm(Yf - ref) / np.linalg.norm(ref)
+    mx = np.max(np.abs(Yf - ref)) / np.max(np.abs(ref))
+    assert rel <= BF16_REL_FRO_TOL and mx <= BF16_MAX_ABS_TOL, (rel, mx)
+
+
 def test_int3_compensator_full_size_c1_and_a_symmetric_weight():
     c = wl.C1[16]
     X, pw, ref = _int3_case(c.M, c.N, c.K, c.r, seed=c.seed)
