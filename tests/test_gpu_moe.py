@@ -157,6 +157,26 @@ def test_out_of_range_expert_id_is_skipped_and_flagged():
     assert layer.routing_status() == 6
 
 
+def test_status_reports_a_wait_that_gave_up():
+    # the give-up word of the layer's workspace, forced from the host (no kernel spins): the status call
+    # reports MILO_ERR_WAIT for that forward; the next forward clears the word at its start
+    import torch
+    from paper_2504_02658_amd import api
+    case = wl.MoECase("wait", T=24, H=128, F=192, E=4, topk=2, seed=16, rank_choices=(8,))
+    _, layer = build_moe(case)
+    X = torch.from_numpy(wl.moe_activations(case)).cuda()
+    ids_np, gates_np = wl.moe_routing(case)
+    ids, gates = torch.from_numpy(ids_np).cuda(), torch.from_numpy(gates_np).cuda()
+    ws = api.new_workspace(layer.workspace_bytes(case.T, case.topk))
+    Y = layer.forward(X, ids, gates, workspace=ws).clone()
+    assert layer.routing_status() == 0
+    ws.view(torch.int32)[3] = 1                         # what a kernel writes when its wait runs out
+    assert layer.routing_status() == 8
+    Y2 = layer.forward(X, ids, gates, workspace=ws)
+    assert layer.routing_status() == 0
+    assert torch.equal(Y, Y2)
+
+
 @pytest.mark.timeout(900)
 def test_c3_mixtral_layer_full_size():
     # the full layer at 512 tokens, then the same experts at decode-sized batches (16, 4 and 1 tokens:
