@@ -151,10 +151,12 @@ def test_compressed_weight_feeds_the_gemm():
     assert np.linalg.norm(Y3 - exact) < 0.95 * np.linalg.norm(rtn - exact)
 
 
-@pytest.mark.parametrize("N,K,r", [(16, 64, 0), (16, 64, 8), (48, 192, 40), (272, 1408, 128), (256, 512, 128)])
+@pytest.mark.parametrize("N,K,r", [(16, 64, 0), (16, 64, 8), (48, 192, 40), (272, 1408, 128), (256, 512, 128),
+                                   (64, 256, 1), (96, 320, 5), (128, 256, 33)])
 def test_smallest_and_largest_shapes(N, K, r):
     # one row block and one group; a rank that fills min(N, K) up to the sketch; the largest rank the call
-    # takes (its factorizations then need nearly all of a workgroup's LDS)
+    # takes (its factorizations then need nearly all of a workgroup's LDS); odd ranks (an odd number of
+    # basis vectors: one sits out in every step of the Jacobi round-robin)
     W = wl.gen_weight_lowrank(N, K, seed=3600 + N + r, modes=min(4, N // 4))
     ref = oracle.milo_compress(W, r, iters=3, tol=-1.0)
     out = _compress(W, r, iters=3, tol=-1.0, power_iters=30, refine_iters=10)
