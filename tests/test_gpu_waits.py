@@ -43,3 +43,26 @@ def test_counted_waits_equal_full_waits(M, N, K, r):
     b = _gemm(full, X, q3, U, V, r, N)
     assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
     assert np.all(np.isfinite(a)) and np.any(a != 0)
+
+
+def test_moe_layer_counted_waits_equal_full_waits(monkeypatch):
+    # the grouped kernels of the MoE call share the K loop with its counted waits: the same layer through
+    # both builds, tile heights 32 and 128, must agree bit for bit
+    import torch
+    from paper_2504_02658_amd import api
+    from helpers import build_moe
+    for T in (24, 400):
+        case = wl.MoECase("waits", T=T, H=256, F=384, E=4, topk=2, seed=41, rank_choices=(0, 8, 40))
+        _, layer = build_moe(case)
+        X = torch.from_numpy(wl.moe_activations(case)).cuda()
+        ids_np, gates_np = wl.moe_routing(case)
+        ids, gates = torch.from_numpy(ids_np).cuda(), torch.from_numpy(gates_np).cuda()
+        Y1 = layer.forward(X, ids, gates).clone()
+        assert layer.routing_status() == 0
+        with monkeypatch.context() as m:
+            m.setattr(api, "_lib", api.bind(api.FULLWAITS_LIB_PATH))
+            layer2 = api.MoELayer(layer.experts, case.H, case.F)
+            Y2 = layer2.forward(X, ids, gates).clone()
+            assert layer2.routing_status() == 0
+        assert torch.equal(Y1, Y2), f"the two builds differ at {T} tokens"
+        assert bool(torch.isfinite(Y1.float()).all()) and bool((Y1 != 0).any())
