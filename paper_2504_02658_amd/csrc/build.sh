@@ -5,24 +5,26 @@ cd "$(dirname "$0")"
 OUT=../lib
 mkdir -p "$OUT" _build
 FLAGS="-O3 --offload-arch=gfx950 -fPIC -std=c++17 -Xclang -target-feature -Xclang -packed-fp32-ops -fhip-fp32-correctly-rounded-divide-sqrt -Wno-unused-command-line-argument"
+# the decode kernel's leading scalar arguments are placed in registers at wave start (see gemm_decode.hip)
+PRELOAD="-mllvm -amdgpu-kernarg-preload-count=11"
 pids=()
 hipcc $FLAGS -ffp-contract=off -c pack.hip -o _build/pack.o & pids+=($!)
 hipcc $FLAGS -ffp-contract=off -c compress.hip -o _build/compress.o & pids+=($!)
 hipcc $FLAGS -c gemm_tiled.hip -o _build/gemm_tiled.o & pids+=($!)
-hipcc $FLAGS -c gemm_decode.hip -o _build/gemm_decode.o & pids+=($!)
+hipcc $FLAGS $PRELOAD -c gemm_decode.hip -o _build/gemm_decode.o & pids+=($!)
 hipcc $FLAGS -c moe.hip -o _build/moe.o & pids+=($!)
 hipcc $FLAGS -c api.hip -o _build/api.o & pids+=($!)
 hipcc $FLAGS -c gemm_static.hip -o _build/gemm_static.o & pids+=($!)
 # the same two GEMM kernels with every hand-counted wait replaced by a wait for everything
 hipcc $FLAGS -DMILO_FULL_WAITS -c gemm_tiled.hip -o _build/gemm_tiled_fw.o & pids+=($!)
-hipcc $FLAGS -DMILO_FULL_WAITS -c gemm_decode.hip -o _build/gemm_decode_fw.o & pids+=($!)
+hipcc $FLAGS $PRELOAD -DMILO_FULL_WAITS -c gemm_decode.hip -o _build/gemm_decode_fw.o & pids+=($!)
 for p in "${pids[@]}"; do wait $p; done
 # The decode kernel counts outstanding memory operations by hand (see gemm_decode.hip): a streaming
 # wave requests in a fixed order (per chunk XC buffer-to-LDS copies of activations and per row block a
 # 16-byte and a 12-byte load of weights) and waits with "s_waitcnt vmcnt(N)".  The compiler must not
 # reorder these requests; memory operations of its own (register spills) after a counted request only
 # make a counted wait longer, never too short, but they must stay out of the streaming loop.
-hipcc $FLAGS -S --cuda-device-only gemm_decode.hip -o _build/gemm_decode.s
+hipcc $FLAGS $PRELOAD -S --cuda-device-only gemm_decode.hip -o _build/gemm_decode.s
 python3 - <<'PY'
 import re, sys
 txt = open("_build/gemm_decode.s").read()

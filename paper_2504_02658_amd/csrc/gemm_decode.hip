@@ -316,8 +316,17 @@ __device__ __forceinline__ void scatter_u_rank(const uint32_t (&w)[32], unsigned
 // SYM: the weight blob is symmetric (zero-point-free conversion).  Q (with LR == 1): the compensator
 // is the pair of INT3 blobs of milo_pack_lr3.
 template <int R, int LR, int XC, bool SYM, bool Q, bool BF>
-__global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeArgs a) {
+__global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const void* q3_, const f16* X_, uint32_t units_, uint32_t K_,
+                                                                  uint32_t nb_, int M_, int nt_, uint32_t nmain_, uint32_t cpw_,
+                                                                  uint32_t rot_mask_, uint32_t x_bytes_, const DecodeArgs a_) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    // What a streaming wave needs for its first requests comes as leading scalar arguments, which the
+    // hardware places in registers when it starts the wave (the build asks for that with
+    // -amdgpu-kernarg-preload-count); everything else is read from the argument block when it is
+    // needed.  The values are the same as the block's.
+    DecodeArgs a = a_;
+    a.w.q3 = q3_; a.X = X_; a.units = units_; a.K = (int64_t)K_; a.nb = nb_; a.M = M_; a.nt = nt_; a.nmain = nmain_;
+    a.chunks_per_wave = cpw_; a.rot_mask = rot_mask_; a.x_bytes = x_bytes_;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int nworkers = LR > 0 ? a.nt : 0;
@@ -328,29 +337,32 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
         const int M = a.M;
         const uint32_t K = (uint32_t)a.K;                   // < 2^27 (checked on the host)
         const uint32_t G = K / kGroup;
-        const uint32_t NB = (uint32_t)(a.N >> 4);           // 16-row blocks
-        const uint32_t nchunks = (G + 3) / 4;
+        const uint32_t NB = a.nb;                           // 16-row blocks
         const int r = a.w.r;
-        const W3Buf wb = make_w3buf(a.w.q3, a.N, a.K);
-        const uint32_t nmain = gridDim.x - (uint32_t)nworkers;
-        const uint32_t turns = ((NB + R - 1) / R + nmain - 1) / nmain;
-        const BufRsrc tb = make_rsrc(a.T, (uint64_t)a.kh * 16u * (uint64_t)a.ldt * 2u);
+        W3Buf wb;
+        wb.a = make_rsrc(a.w.q3, (uint64_t)(a.units * 16u));                // (units <= 2^26)
+        wb.b = make_rsrc(reinterpret_cast<const char*>(a.w.q3) + (uint64_t)a.units * 16u, (uint64_t)(a.units * 12u));
+        const uint32_t nmain = a.nmain;
+        const BufRsrc tb = make_rsrc(a.T, (uint64_t)a.t_bytes);
         const int ksu = (r + 31) >> 5;                  // k-steps of 32 ranks in use
         // (T fragments in LDS: K part h, k-step i -> h * ksu + i)
         bool t_ready = false;
 
         const int wave_s = __builtin_amdgcn_readfirstlane(wave);        // known to be uniform
         DecodeStream<R, XC, SYM, BF> st{wb,
-                               make_rsrc(a.X, (uint64_t)M * K * 2u),
+                               make_rsrc(a.X, (uint64_t)a.x_bytes),
                                XCopy(lane, K),
                                smem + wave_s * kDecSlotBytes,
                                K, G, NB, 0u, 0u, 0u, (uint32_t)lane, (uint32_t)q, (uint32_t)j16};
-        st.C = (nchunks + kDecWaves - 1) / kDecWaves;
+        st.C = a.chunks_per_wave;
         st.span = st.C * kDecWaves;
-        st.first = (uint32_t)wave_s + (blockIdx.x * 5u) % st.span;
+        // (rotation by a masked product instead of a remainder: no division before the first request)
+        st.first = (uint32_t)wave_s + ((blockIdx.x * 5u) & a.rot_mask);
         if (st.first >= st.span) st.first -= st.span;
 
-        for (uint32_t turn = 0, blk = blockIdx.x - nworkers; turn < turns; ++turn, blk += nmain) {
+        // (every streaming workgroup has at least one turn: the number of turns is first looked at after it)
+        uint32_t turn = 0, blk = blockIdx.x - nworkers;
+        do {
             const uint32_t rb0 = blk * R;
             f32x4 acc[R];
 #pragma unroll
@@ -395,7 +407,7 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
                         }
                     }
                 } else if (LR == 1) {
-                    const BufRsrc ub = make_rsrc(a.w.U, (uint64_t)a.N * (uint64_t)r * 2u);
+                    const BufRsrc ub = make_rsrc(a.w.U, (uint64_t)a.u_bytes);
 #pragma unroll 1
                     for (int b = 0; b < R; ++b) {
                         const uint32_t nrow = (rb0 + b) * 16u + j16;
@@ -495,8 +507,9 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
                     *reinterpret_cast<u32x2*>(a.Y + ((uint64_t)j16 * n_out + n)) = ob;
                 }
             }
-            if (turn + 1 < turns) __syncthreads();      // slots, U and the partial sums are reused
-        }
+            if (turn + 1 < a.turns) __syncthreads();      // slots, U and the partial sums are reused
+            blk += nmain;
+        } while (++turn < a.turns);
     }
 
     // LR == 2: the streaming workgroups read T from memory in their epilogue, so they sign off last.
@@ -511,7 +524,7 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
     // before the kernel would have ended anyway.  No returning atomic on a shared word is
     // involved: hundreds of those on one address serialize for several microseconds.
     if (LR > 0 && blockIdx.x == 0 && wave == 0) {
-        const uint32_t nmain = gridDim.x - (uint32_t)nworkers;
+        const uint32_t nmain = a.nmain;
         bool all = false;
         for (uint32_t spins = 0; !all; ++spins) {
             all = true;
@@ -540,7 +553,8 @@ __global__ __launch_bounds__(kDecThreads) void w3lr_decode_kernel(const DecodeAr
 
 // Workgroups the device keeps resident at once (one 128-KB-LDS workgroup per CU), cached per
 // device; also raises the kernels' dynamic LDS limit once.
-typedef void (*DecodeKernel)(const DecodeArgs);
+typedef void (*DecodeKernel)(const void*, const f16*, uint32_t, uint32_t, uint32_t, int, int, uint32_t, uint32_t, uint32_t, uint32_t,
+                             const DecodeArgs);
 // Variants: R x LR x XC for plain weights with an fp16 compensator (the generic path LR == 2 is not
 // specialised by XC); with an INT3 compensator R x XC (LR == 1); with the symmetric conversion the
 // shape that matters for speed, R == 4 with LR 0 or 1 (other shapes take the plain conversion, which
@@ -680,7 +694,20 @@ int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream) {
     if (bf && q) return MILO_ERR_SHAPE;
     const DecodeKernel kernel = decode_variant(R, lr, xc, (a.w.flags & MILO_W3_SYMMETRIC) != 0, q, bf);
     if (!kernel) return MILO_ERR_HIP;
-    kernel<<<dim3((unsigned)grid), dim3(kDecThreads), lr == 1 ? kDecLdsTotal : kDecLdsBytes, stream>>>(a);
+    const uint32_t nchunks = (uint32_t)((a.K + 255) / 256);
+    a.units = (uint32_t)(a.N * (a.K / kGroup));
+    a.nb = (uint32_t)(a.N >> 4);
+    a.nmain = (uint32_t)(grid - workers);
+    a.turns = (uint32_t)((blocks + a.nmain - 1) / a.nmain);
+    a.chunks_per_wave = (nchunks + kDecWaves - 1) / kDecWaves;
+    uint32_t pow2 = kDecWaves;
+    while (pow2 * 2u <= a.chunks_per_wave * kDecWaves) pow2 *= 2u;
+    a.rot_mask = pow2 - 1u;
+    a.x_bytes = (uint32_t)((uint64_t)a.M * (uint64_t)a.K * 2u);            // (< 2^32: checked by the caller)
+    a.t_bytes = (uint32_t)((uint64_t)a.kh * 16u * (uint64_t)a.ldt * 2u);
+    a.u_bytes = (uint32_t)((uint64_t)a.N * (uint64_t)(r > 0 ? r : 0) * 2u);   // (fp16 U; < 2^32 on the staged path)
+    kernel<<<dim3((unsigned)grid), dim3(kDecThreads), lr == 1 ? kDecLdsTotal : kDecLdsBytes, stream>>>(
+        a.w.q3, a.X, a.units, (uint32_t)a.K, a.nb, a.M, a.nt, a.nmain, a.chunks_per_wave, a.rot_mask, a.x_bytes, a);
     return launch_status();
 }
 

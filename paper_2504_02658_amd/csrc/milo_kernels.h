@@ -109,6 +109,15 @@ struct DecodeArgs {
     int nt;             // number of T workers (the first nt workgroups)
     int kh;             // K parts of T (2048 columns each)
     uint32_t spin_limit;    // polls after which a wait inside the kernel gives up
+    // sizes and counts worked out on the host, so that a wave's first memory requests do not wait for
+    // arithmetic (divisions, 64-bit products) or for further loads of launch parameters
+    uint32_t units;         // N * K / 64: 16 bytes each in plane A, 12 in plane B
+    uint32_t nb;            // N / 16 row blocks
+    uint32_t nmain;         // streaming workgroups of the launch
+    uint32_t turns;         // row-block groups per streaming workgroup
+    uint32_t chunks_per_wave;   // ceil(ceil(K / 256) / 16)
+    uint32_t rot_mask;      // largest power of two not above 16 * chunks_per_wave, minus one
+    uint32_t x_bytes, t_bytes, u_bytes;     // extents of X, T and (fp16) U
 };
 size_t decode_workspace_bytes(int r, int64_t K);
 int launch_decode(DecodeArgs a, void* workspace, hipStream_t stream);
